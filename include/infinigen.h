@@ -1,0 +1,205 @@
+/*
+ * infinigen.h -- C ABI of the MI355X (gfx950) implementation of InfiniGen's attention rehearsal
+ * and of the sparse decode attention it drives (arXiv 2406.19707, Section 4).
+ *
+ * One decode step of one layer pair (Section 4.3 "Decoding Stage", Fig. 3(d)):
+ *   ig_speculate         partial query projection, scan of the skewed partial key cache,
+ *                        per-head (max - alpha) threshold, compaction into index lists
+ *   ig_gather_kv         copies only the selected K/V rows out of the KV pool (HBM, or pinned host
+ *                        memory read over PCIe)
+ *   ig_sparse_attention  softmax(q K_sel^T) V_sel on the fetched rows
+ * preceded once per model by ig_skew_offline (Section 4.2, Eq. 2 and 3) and once per request by
+ * ig_partial_index / ig_wq_build / ig_slab_build (Section 4.3 "Prefill Stage").
+ *
+ * General rules
+ *  - Every call returns an int status (IG_OK = 0).  Nothing throws or aborts across this boundary;
+ *    ig_last_error() gives the message of the last failing call on a context.
+ *  - Arrays are row-major.  Projections are y = x W with W [in, out] (Section 2.1).
+ *  - "device" pointers are HIP device memory on the context's GPU; "host" pointers are ordinary
+ *    host memory.  The caller allocates and frees every array; the library owns only the context
+ *    (small workspaces, a device status word, profiling events).
+ *  - Device calls enqueue work on the hipStream_t passed as `stream` (a void*; NULL = the null
+ *    stream) and return without synchronising.  They never read device results on the host.
+ *    Workspaces grow on the first call with a larger shape (this allocates); ig_reserve() sizes
+ *    them ahead of time, after which the hot-path calls allocate nothing.
+ *  - Calls on one context must not overlap in time on different streams: they share workspaces.
+ *  - dtype IG_F16: x, weights, K, V, q, out are IEEE half; IG_F32: float.  Partial queries,
+ *    scores and all accumulation are float32 in both cases.  Index arrays are int32.
+ */
+#ifndef INFINIGEN_H
+#define INFINIGEN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  IG_OK = 0,
+  IG_EINVAL = 1,    /* null pointer, bad flag, alpha < 0 or NaN, unpinned host pool */
+  IG_ESHAPE = 2,    /* a dimension is zero, negative or outside what the kernels support */
+  IG_EDTYPE = 3,    /* unknown dtype */
+  IG_ECAPACITY = 4, /* a selected-token list did not fit in sel_stride (reported by ig_check_status) */
+  IG_EHIP = 5,      /* a HIP runtime call failed; message holds hipGetErrorString */
+  IG_ENOCONV = 6,   /* Jacobi sweeps exceeded their cap in ig_skew_offline */
+  IG_ENOMEM = 7
+};
+
+enum { IG_F32 = 0, IG_F16 = 1 };
+enum { IG_MEM_DEVICE = 0, IG_MEM_HOST_PINNED = 1 };
+
+/* Kernel identifiers for ig_profile_read. */
+enum {
+  IG_K_PROJECT = 0,  /* partial query projection (split-K partial sums) */
+  IG_K_FINALIZE = 1, /* partial-sum reduction, bias, rotary embedding, partial skew */
+  IG_K_SCAN = 2,     /* partial key cache scan (+ max, threshold, compaction when fused) */
+  IG_K_SELECT = 3,   /* threshold + compaction from a score buffer (long sequences) */
+  IG_K_GATHER = 4,
+  IG_K_ATTENTION = 5,
+  IG_K_BUILD = 6,    /* ig_wq_build / ig_slab_build */
+  IG_K_COPY = 7,     /* ig_copy_bytes */
+  IG_K_COUNT = 8
+};
+
+typedef struct ig_ctx ig_ctx;
+
+/* Shape and parameters of one layer's rehearsal; passed by const pointer, plain data. */
+typedef struct {
+  int32_t B;        /* sequences in the batch */
+  int32_t H;        /* attention heads */
+  int32_t d;        /* head dimension; D = H*d is the model dimension */
+  int32_t r;        /* kept columns per head, floor(ratio*d) (Section 4.3: 30 %) */
+  int32_t N;        /* cached tokens per sequence that are valid */
+  int32_t N_cap;    /* tokens allocated per (sequence, head) in the pools and the slab, >= N */
+  int32_t dtype;    /* IG_F32 or IG_F16 */
+  float scale;      /* logit scale applied to speculated scores and attention logits */
+  float alpha;      /* threshold slack, >= 0; +infinity selects every token (Section 4.3) */
+  int32_t rope;     /* 0: skew folded into the query weight; 1: rotary embedding between
+                       projection and skew (the partial projection then needs the full W_Q) */
+  float rope_theta; /* rotary base (10000) */
+} ig_desc;
+
+/* ---- context ---------------------------------------------------------------------------- */
+int ig_create(int device, ig_ctx **out);
+int ig_destroy(ig_ctx *ctx);
+const char *ig_last_error(const ig_ctx *ctx);
+/* Size the context's workspaces for `desc` now (allocates; synchronous). */
+int ig_reserve(ig_ctx *ctx, const ig_desc *desc);
+/* Synchronise the device and report sticky device-side conditions: IG_ECAPACITY if any list was
+ * clamped to sel_stride since the last check, else IG_OK.  Clears the condition. */
+int ig_check_status(ig_ctx *ctx);
+
+/* ---- offline / prefill helpers (host pointers, float32, synchronous, CPU) ----------------- */
+
+/* Offline skewing (Section 4.2 "Skewed Partial Weight", Eq. 2 and Eq. 3; Section 4.3 "Prefetching
+ * Scheme").  For each head h, the [n_cal, d] block of the calibration query matrix Qcal is
+ * decomposed Q_h = U S V^T and A_h = V; the head's query / key weight columns (and biases) are
+ * multiplied by A_h from the right.  A [H,d,d] always written; sigma [H,d] (singular values,
+ * descending), Wq_s, Wk_s [D,D], bq_s, bk_s [D] written when both the input and the output
+ * pointer are non-NULL.  Column signs of A_h: largest-magnitude entry positive.
+ * ctx may be NULL (no message is kept then). */
+int ig_skew_offline(ig_ctx *ctx, int D, int H, int n_cal, const float *Wq, const float *Wk,
+                    const float *bq, const float *bk, const float *Qcal, float *A, float *sigma,
+                    float *Wq_s, float *Wk_s, float *bq_s, float *bk_s);
+
+/* Partial weight index generation (Section 4.3 "Prefill Stage"): per head, the
+ * r = floor(ratio*d) columns with the largest sum over rows of |Qs| + |Ks| (Ks NULL: |Qs| only).
+ * Qs, Ks [n, H*d] skewed queries / keys.  idx [H, r] ascending (NULL: only r_out is written).
+ * Ties go to the lower column. */
+int ig_partial_index(ig_ctx *ctx, int H, int d, int n, const float *Qs, const float *Ks,
+                     double ratio, int32_t *idx, int32_t *r_out);
+
+/* ---- setup on the device ------------------------------------------------------------------ */
+
+/* Partial query weight (Section 4.3 "Prefill Stage"): the kept columns of the skewed query
+ * weight, stored in a library-defined layout.  Wq: device [D, D] of desc->dtype -- the skewed
+ * W~_Q when desc->rope == 0, the original W_Q when desc->rope == 1 (all columns are kept then
+ * and idx_dev is ignored).  idx_dev: device int32 [H, r].  wq: device, ig_wq_bytes(desc) bytes,
+ * 16-byte aligned. */
+size_t ig_wq_bytes(const ig_desc *desc);
+int ig_wq_build(ig_ctx *ctx, const ig_desc *desc, const void *Wq, const int32_t *idx_dev, void *wq,
+                void *stream);
+
+/* Partial key cache ("slab", Section 4.3 "Prefill Stage"): columns idx of the skewed keys of all
+ * cached tokens, stored in a library-defined layout.  Kpool: [B, H, N_cap, d] skewed keys of
+ * desc->dtype, in device memory or pinned host memory (pool_space).  slab: device,
+ * ig_slab_bytes(desc) bytes, 16-byte aligned.  Tokens N..N_cap-1 are stored as zeros. */
+size_t ig_slab_bytes(const ig_desc *desc);
+int ig_slab_build(ig_ctx *ctx, const ig_desc *desc, const void *Kpool, int pool_space,
+                  const int32_t *idx_dev, void *slab, void *stream);
+
+/* ---- hot path ----------------------------------------------------------------------------- */
+
+/* Attention rehearsal of the next layer (Section 4.3 "Decoding Stage"):
+ *   q_p[b,h,:]   = x[b,:] . (partial query weight of head h) (+ bias)
+ *                  (rope: q = x W_Q (+ bias), rotated at pos[b], then q . A_p[h])
+ *   s[b,h,t]     = scale * q_p[b,h,:] . slab[b,h,t,:]                     t < N
+ *   S[b,h]       = { t : s[b,h,t] >= max_t s[b,h,t] - alpha }, ascending t
+ * x: device [B, D] of desc->dtype, the previous layer's normalised attention input.
+ * wq: from ig_wq_build.  bias: device float32, [H*r] (rope 0: skewed bias at the kept columns) or
+ * [D] (rope 1), or NULL.  A_p: device float32 [H, d, r], kept columns of each head's skewing
+ * matrix (rope 1 only, else NULL).  pos: device int32 [B], current position of each sequence
+ * (rope 1 only).  slab: from ig_slab_build.
+ * Out: sel_idx device int32 [B*H, sel_stride], sel_cnt device int32 [B*H].  A list longer than
+ * sel_stride is clamped to its first sel_stride tokens and flagged (ig_check_status).
+ * scores_opt: NULL, or device float32 [B, H, N] that receives s. */
+int ig_speculate(ig_ctx *ctx, const ig_desc *desc, const void *x, const void *wq,
+                 const float *bias, const float *A_p, const int32_t *pos, const void *slab,
+                 int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, float *scores_opt,
+                 void *stream);
+
+/* The two stages of ig_speculate on their own (same definitions, same kernels): ig_project writes
+ * the unscaled partial queries q_p, device float32 [B, H, r]; ig_scan_select consumes them. */
+int ig_project(ig_ctx *ctx, const ig_desc *desc, const void *x, const void *wq, const float *bias,
+               const float *A_p, const int32_t *pos, float *q_p, void *stream);
+int ig_scan_select(ig_ctx *ctx, const ig_desc *desc, const float *q_p, const void *slab,
+                   int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, float *scores_opt,
+                   void *stream);
+
+/* Prefetch of the selected rows (Section 4.1 overview; Section 4.3): for j < sel_cnt[b,h]
+ *   K_sel[b,h,j,:] = Kpool[b,h,sel_idx[b,h,j],:],  V_sel likewise.
+ * Kpool, Vpool: [B, H, N_cap, d] of desc->dtype in device memory (IG_MEM_DEVICE) or in pinned,
+ * GPU-mapped host memory (IG_MEM_HOST_PINNED; rows then cross PCIe, and `stream` is normally a
+ * side stream so the copy overlaps the previous layer).  K_sel, V_sel: device
+ * [B*H, sel_stride, d]; rows j >= sel_cnt are not written.  Row size d*sizeof(dtype) must be a
+ * multiple of 16 bytes. */
+int ig_gather_kv(ig_ctx *ctx, const ig_desc *desc, const void *Kpool, const void *Vpool,
+                 int pool_space, const int32_t *sel_idx, int32_t sel_stride,
+                 const int32_t *sel_cnt, void *K_sel, void *V_sel, void *stream);
+
+/* Decode attention over the fetched rows only (Section 2.1, softmax(Q K^T) V per head; Section 4.1):
+ *   l_j = scale * q[b,h,:] . K_sel[b,h,j,:], p = softmax_j(l), out[b,h,:] = sum_j p_j V_sel[b,h,j,:]
+ * over j < sel_cnt[b,h], plus one always-attended row (k_new, v_new: device [B,H,d], the token
+ * being decoded) when both are non-NULL.  q: device [B,H,d], the layer's real skewed query.
+ * out: device [B,H,d] of desc->dtype; zeros for an empty list without a new row. */
+int ig_sparse_attention(ig_ctx *ctx, const ig_desc *desc, const void *q, const void *K_sel,
+                        const void *V_sel, const int32_t *sel_cnt, int32_t sel_stride,
+                        const void *k_new, const void *v_new, void *out, void *stream);
+
+/* Same attention with the index lists applied to a device-resident pool directly (no K_sel /
+ * V_sel copy): row j of (b,h) is Kpool[b,h,sel_idx[b,h,j],:]. */
+int ig_sparse_attention_indexed(ig_ctx *ctx, const ig_desc *desc, const void *q, const void *Kpool,
+                                const void *Vpool, const int32_t *sel_idx, int32_t sel_stride,
+                                const int32_t *sel_cnt, const void *k_new, const void *v_new,
+                                void *out, void *stream);
+
+/* ---- measurement --------------------------------------------------------------------------- */
+
+/* Between ig_profile_begin and ig_profile_end every kernel the context launches carries a pair of
+ * HIP events that take the kernel's own start and stop timestamps.  ig_profile_end synchronises
+ * the device and stops recording; ig_profile_read then returns, for kernel id `which`
+ * (IG_K_*), the summed duration in milliseconds and the number of launches. */
+int ig_profile_begin(ig_ctx *ctx);
+int ig_profile_end(ig_ctx *ctx);
+int ig_profile_read(ig_ctx *ctx, int which, double *total_ms, int32_t *launches);
+
+/* Plain device-to-device copy kernel of `bytes` bytes (multiple of 16); used to scale hardware
+ * counters against a transfer of known size and to measure the achievable HBM rate. */
+int ig_copy_bytes(ig_ctx *ctx, const void *src, void *dst, size_t bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* INFINIGEN_H */

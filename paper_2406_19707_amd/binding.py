@@ -1,0 +1,269 @@
+"""Python binding of libinfinigen_hip.so: argument marshalling only.
+
+Every function has the name and argument order of its C entry point in include/infinigen.h.
+Tensor arguments are torch tensors (device memory / pinned host memory) or numpy arrays (host
+arguments of the offline calls); what crosses the boundary is their address.  There is no fallback:
+if the shared library is missing the import of any entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+__all__ = [
+    "IG_OK", "IG_EINVAL", "IG_ESHAPE", "IG_EDTYPE", "IG_ECAPACITY", "IG_EHIP", "IG_ENOCONV",
+    "IG_ENOMEM", "IG_F32", "IG_F16", "IG_MEM_DEVICE", "IG_MEM_HOST_PINNED", "IG_K_PROJECT",
+    "IG_K_FINALIZE", "IG_K_SCAN", "IG_K_SELECT", "IG_K_GATHER", "IG_K_ATTENTION", "IG_K_BUILD",
+    "IG_K_COPY", "IgDesc", "IgError", "Context", "lib", "lib_path", "ig_skew_offline",
+    "ig_partial_index", "ig_wq_bytes", "ig_slab_bytes", "EXPORTS",
+]
+
+IG_OK, IG_EINVAL, IG_ESHAPE, IG_EDTYPE, IG_ECAPACITY, IG_EHIP, IG_ENOCONV, IG_ENOMEM = range(8)
+IG_F32, IG_F16 = 0, 1
+IG_MEM_DEVICE, IG_MEM_HOST_PINNED = 0, 1
+(IG_K_PROJECT, IG_K_FINALIZE, IG_K_SCAN, IG_K_SELECT, IG_K_GATHER, IG_K_ATTENTION, IG_K_BUILD,
+ IG_K_COPY) = range(8)
+
+# every symbol include/infinigen.h declares
+EXPORTS = [
+    "ig_create", "ig_destroy", "ig_last_error", "ig_reserve", "ig_check_status", "ig_skew_offline",
+    "ig_partial_index", "ig_wq_bytes", "ig_wq_build", "ig_slab_bytes", "ig_slab_build",
+    "ig_speculate", "ig_project", "ig_scan_select", "ig_gather_kv", "ig_sparse_attention",
+    "ig_sparse_attention_indexed", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
+    "ig_copy_bytes",
+]
+
+
+class IgDesc(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("r", ctypes.c_int32), ("N", ctypes.c_int32), ("N_cap", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float), ("alpha", ctypes.c_float),
+                ("rope", ctypes.c_int32), ("rope_theta", ctypes.c_float)]
+
+    def __init__(self, B, H, d, r, N, N_cap=None, dtype=IG_F16, scale=1.0, alpha=4.0, rope=0,
+                 rope_theta=10000.0):
+        super().__init__(B, H, d, r, N, N if N_cap is None else N_cap, dtype, scale, alpha, rope,
+                         rope_theta)
+
+
+class IgError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"infinigen error {code}: {message}")
+        self.code = code
+
+
+def lib_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libinfinigen_hip.so")
+
+
+_lib = None
+_vp, _i32, _f32, _sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_float, ctypes.c_size_t
+_dp = ctypes.POINTER(IgDesc)
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        path = lib_path()
+        if not os.path.exists(path):
+            raise FileNotFoundError(f"{path} is missing: build it with "
+                                    "`python paper_2406_19707_amd/build.py` (there is no fallback)")
+        L = ctypes.CDLL(path)
+        sig = {
+            "ig_create": (ctypes.c_int, [ctypes.c_int, ctypes.POINTER(_vp)]),
+            "ig_destroy": (ctypes.c_int, [_vp]),
+            "ig_last_error": (ctypes.c_char_p, [_vp]),
+            "ig_reserve": (ctypes.c_int, [_vp, _dp]),
+            "ig_check_status": (ctypes.c_int, [_vp]),
+            "ig_skew_offline": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int] + [_vp] * 11),
+            "ig_partial_index": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp,
+                                                ctypes.c_double, _vp, ctypes.POINTER(_i32)]),
+            "ig_wq_bytes": (_sz, [_dp]),
+            "ig_wq_build": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp]),
+            "ig_slab_bytes": (_sz, [_dp]),
+            "ig_slab_build": (ctypes.c_int, [_vp, _dp, _vp, ctypes.c_int, _vp, _vp, _vp]),
+            "ig_speculate": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
+            "ig_project": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+            "ig_scan_select": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
+            "ig_gather_kv": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_int, _vp, _i32, _vp, _vp, _vp, _vp]),
+            "ig_sparse_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
+            "ig_sparse_attention_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
+            "ig_profile_begin": (ctypes.c_int, [_vp]),
+            "ig_profile_end": (ctypes.c_int, [_vp]),
+            "ig_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
+                                               ctypes.POINTER(_i32)]),
+            "ig_copy_bytes": (ctypes.c_int, [_vp, _vp, _vp, _sz, _vp]),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def _ptr(t):
+    """Address of a torch tensor / numpy array / None / raw int."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if isinstance(t, np.ndarray):
+        assert t.flags.c_contiguous
+        return t.ctypes.data
+    assert t.is_contiguous(), "tensors crossing the C ABI must be contiguous"
+    return t.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _host_f32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+
+
+def ig_wq_bytes(desc: IgDesc) -> int:
+    return lib().ig_wq_bytes(ctypes.byref(desc))
+
+
+def ig_slab_bytes(desc: IgDesc) -> int:
+    return lib().ig_slab_bytes(ctypes.byref(desc))
+
+
+def ig_skew_offline(Wq, Wk, Qcal, H, bq=None, bk=None, ctx=None):
+    """Host call. Returns dict(A, sigma, Wq_s, Wk_s, bq_s, bk_s, rc); rc is IG_OK or IG_ENOCONV."""
+    Qcal = _host_f32(Qcal)
+    n_cal, D = Qcal.shape
+    d = D // H
+    Wq, Wk, bq, bk = map(_host_f32, (Wq, Wk, bq, bk))
+    A = np.zeros((H, d, d), np.float32)
+    sigma = np.zeros((H, d), np.float32)
+    out = {k: (np.zeros_like(v) if v is not None else None)
+           for k, v in (("Wq_s", Wq), ("Wk_s", Wk), ("bq_s", bq), ("bk_s", bk))}
+    rc = lib().ig_skew_offline(ctx._h if ctx else None, D, H, n_cal, _ptr(Wq), _ptr(Wk), _ptr(bq),
+                               _ptr(bk), _ptr(Qcal), _ptr(A), _ptr(sigma), _ptr(out["Wq_s"]),
+                               _ptr(out["Wk_s"]), _ptr(out["bq_s"]), _ptr(out["bk_s"]))
+    if rc not in (IG_OK, IG_ENOCONV):
+        raise IgError(rc, ctx.last_error() if ctx else "ig_skew_offline")
+    return dict(A=A, sigma=sigma, rc=rc, **out)
+
+
+def ig_partial_index(Qs, Ks, H, ratio, ctx=None):
+    """Host call. Returns idx int32 [H, r]."""
+    Qs, Ks = _host_f32(Qs), _host_f32(Ks)
+    n, D = Qs.shape
+    d = D // H
+    r = _i32(0)
+    h = ctx._h if ctx else None
+    rc = lib().ig_partial_index(h, H, d, n, _ptr(Qs), _ptr(Ks), float(ratio), None, ctypes.byref(r))
+    if rc != IG_OK:
+        raise IgError(rc, ctx.last_error() if ctx else "ig_partial_index")
+    idx = np.zeros((H, r.value), np.int32)
+    rc = lib().ig_partial_index(h, H, d, n, _ptr(Qs), _ptr(Ks), float(ratio), _ptr(idx), ctypes.byref(r))
+    if rc != IG_OK:
+        raise IgError(rc, ctx.last_error() if ctx else "ig_partial_index")
+    return idx
+
+
+class Context:
+    """Owns one ig_ctx.  Methods mirror the C entry points and raise IgError on a non-zero status."""
+
+    def __init__(self, device: int = 0):
+        h = _vp()
+        rc = lib().ig_create(device, ctypes.byref(h))
+        if rc != IG_OK:
+            raise IgError(rc, "ig_create failed (no usable GPU?)")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().ig_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def last_error(self) -> str:
+        return lib().ig_last_error(self._h).decode()
+
+    def _ck(self, rc):
+        if rc != IG_OK:
+            raise IgError(rc, self.last_error())
+
+    def call(self, name, *args):
+        """Raw call returning the status code (used by error-path tests)."""
+        return getattr(lib(), name)(self._h, *args)
+
+    def ig_reserve(self, desc):
+        self._ck(lib().ig_reserve(self._h, ctypes.byref(desc)))
+
+    def ig_check_status(self) -> int:
+        return lib().ig_check_status(self._h)
+
+    def ig_wq_build(self, desc, Wq, idx_dev, wq, stream=None):
+        self._ck(lib().ig_wq_build(self._h, ctypes.byref(desc), _ptr(Wq), _ptr(idx_dev), _ptr(wq),
+                                   _stream(stream)))
+
+    def ig_slab_build(self, desc, Kpool, pool_space, idx_dev, slab, stream=None):
+        self._ck(lib().ig_slab_build(self._h, ctypes.byref(desc), _ptr(Kpool), pool_space,
+                                     _ptr(idx_dev), _ptr(slab), _stream(stream)))
+
+    def ig_speculate(self, desc, x, wq, bias, A_p, pos, slab, sel_idx, sel_stride, sel_cnt,
+                     scores_opt=None, stream=None):
+        self._ck(lib().ig_speculate(self._h, ctypes.byref(desc), _ptr(x), _ptr(wq), _ptr(bias),
+                                    _ptr(A_p), _ptr(pos), _ptr(slab), _ptr(sel_idx), sel_stride,
+                                    _ptr(sel_cnt), _ptr(scores_opt), _stream(stream)))
+
+    def ig_project(self, desc, x, wq, bias, A_p, pos, q_p, stream=None):
+        self._ck(lib().ig_project(self._h, ctypes.byref(desc), _ptr(x), _ptr(wq), _ptr(bias),
+                                  _ptr(A_p), _ptr(pos), _ptr(q_p), _stream(stream)))
+
+    def ig_scan_select(self, desc, q_p, slab, sel_idx, sel_stride, sel_cnt, scores_opt=None,
+                       stream=None):
+        self._ck(lib().ig_scan_select(self._h, ctypes.byref(desc), _ptr(q_p), _ptr(slab),
+                                      _ptr(sel_idx), sel_stride, _ptr(sel_cnt), _ptr(scores_opt),
+                                      _stream(stream)))
+
+    def ig_gather_kv(self, desc, Kpool, Vpool, pool_space, sel_idx, sel_stride, sel_cnt, K_sel,
+                     V_sel, stream=None):
+        self._ck(lib().ig_gather_kv(self._h, ctypes.byref(desc), _ptr(Kpool), _ptr(Vpool),
+                                    pool_space, _ptr(sel_idx), sel_stride, _ptr(sel_cnt),
+                                    _ptr(K_sel), _ptr(V_sel), _stream(stream)))
+
+    def ig_sparse_attention(self, desc, q, K_sel, V_sel, sel_cnt, sel_stride, k_new, v_new, out,
+                            stream=None):
+        self._ck(lib().ig_sparse_attention(self._h, ctypes.byref(desc), _ptr(q), _ptr(K_sel),
+                                           _ptr(V_sel), _ptr(sel_cnt), sel_stride, _ptr(k_new),
+                                           _ptr(v_new), _ptr(out), _stream(stream)))
+
+    def ig_sparse_attention_indexed(self, desc, q, Kpool, Vpool, sel_idx, sel_stride, sel_cnt,
+                                    k_new, v_new, out, stream=None):
+        self._ck(lib().ig_sparse_attention_indexed(self._h, ctypes.byref(desc), _ptr(q),
+                                                   _ptr(Kpool), _ptr(Vpool), _ptr(sel_idx),
+                                                   sel_stride, _ptr(sel_cnt), _ptr(k_new),
+                                                   _ptr(v_new), _ptr(out), _stream(stream)))
+
+    def ig_profile_begin(self):
+        self._ck(lib().ig_profile_begin(self._h))
+
+    def ig_profile_end(self):
+        self._ck(lib().ig_profile_end(self._h))
+
+    def ig_profile_read(self, which):
+        ms, n = ctypes.c_double(0), _i32(0)
+        self._ck(lib().ig_profile_read(self._h, which, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value
+
+    def ig_copy_bytes(self, src, dst, nbytes, stream=None):
+        self._ck(lib().ig_copy_bytes(self._h, _ptr(src), _ptr(dst), nbytes, _stream(stream)))

@@ -1,0 +1,375 @@
+// C ABI of libinfinigen_hip: context, argument validation, workspace management, profiling,
+// and composition of the kernels into the calls declared in include/infinigen.h.
+#include <math.h>
+#include <stdarg.h>
+#include <string.h>
+
+#include <new>
+
+#include "ig_internal.h"
+
+int ig_fail(ig_ctx *ctx, int code, const char *fmt, ...) {
+  if (ctx) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+    va_end(ap);
+  }
+  return code;
+}
+
+int ig_hip_fail(ig_ctx *ctx, hipError_t e, const char *what) {
+  return ig_fail(ctx, IG_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+int ig_ensure(ig_ctx *ctx, void **p, size_t *have, size_t need) {
+  if (*have >= need && *p) return IG_OK;
+  if (*p) {
+    IG_HIP(ctx, hipDeviceSynchronize());   // earlier launches may still read the old buffer
+    IG_HIP(ctx, hipFree(*p));
+    *p = nullptr;
+    *have = 0;
+  }
+  size_t bytes = need < 256 ? 256 : need;
+  IG_HIP(ctx, hipMalloc(p, bytes));
+  *have = bytes;
+  return IG_OK;
+}
+
+void ig_prof_events(ig_ctx *ctx, int which, hipEvent_t *e0, hipEvent_t *e1) {
+  hipEvent_t ev[2];
+  for (int i = 0; i < 2; ++i) {
+    if (!ctx->free_events.empty()) {
+      ev[i] = ctx->free_events.back();
+      ctx->free_events.pop_back();
+    } else {
+      (void)hipEventCreate(&ev[i]);
+    }
+  }
+  ctx->recs.push_back(ProfRec{which, ev[0], ev[1]});
+  *e0 = ev[0];
+  *e1 = ev[1];
+}
+
+namespace {
+
+int check_desc(ig_ctx *ctx, const ig_desc *d) {
+  if (!ctx) return IG_EINVAL;
+  if (!d) return ig_fail(ctx, IG_EINVAL, "descriptor is NULL");
+  if (d->dtype != IG_F32 && d->dtype != IG_F16) return ig_fail(ctx, IG_EDTYPE, "unknown dtype %d", d->dtype);
+  if (d->B < 1 || d->H < 1 || d->d < 1 || d->r < 1 || d->N < 1 || d->N_cap < d->N)
+    return ig_fail(ctx, IG_ESHAPE, "bad shape B=%d H=%d d=%d r=%d N=%d N_cap=%d", d->B, d->H, d->d,
+                   d->r, d->N, d->N_cap);
+  if (d->r > d->d) return ig_fail(ctx, IG_ESHAPE, "r = %d exceeds d = %d", d->r, d->d);
+  if (d->r > 256) return ig_fail(ctx, IG_ESHAPE, "r = %d exceeds 256", d->r);
+  if ((d->d * ig_elem_bytes(d->dtype)) % 16)
+    return ig_fail(ctx, IG_ESHAPE, "a row of d = %d elements must be a multiple of 16 bytes", d->d);
+  if (!(d->alpha >= 0.0f)) return ig_fail(ctx, IG_EINVAL, "alpha must be >= 0 (got %g)", (double)d->alpha);
+  if (!isfinite(d->scale)) return ig_fail(ctx, IG_EINVAL, "scale must be finite");
+  if (d->rope != 0 && d->rope != 1) return ig_fail(ctx, IG_EINVAL, "rope must be 0 or 1");
+  if (d->rope && (d->d % 2 || !(d->rope_theta > 0.0f)))
+    return ig_fail(ctx, IG_EINVAL, "rope needs an even d and a positive base");
+  if ((long)d->B * d->H > 2147483647L / 4) return ig_fail(ctx, IG_ESHAPE, "B*H too large");
+  return IG_OK;
+}
+
+int set_device(ig_ctx *ctx) {
+  IG_HIP(ctx, hipSetDevice(ctx->device));
+  return IG_OK;
+}
+
+// Device-visible address of a pool: device memory as is; pinned host memory through the mapping.
+int resolve_pool(ig_ctx *ctx, const void *p, int space, const void **out) {
+  if (space == IG_MEM_DEVICE) {
+    *out = p;
+    return IG_OK;
+  }
+  if (space != IG_MEM_HOST_PINNED) return ig_fail(ctx, IG_EINVAL, "unknown pool_space %d", space);
+  void *dp = nullptr;
+  hipError_t e = hipHostGetDevicePointer(&dp, const_cast<void *>(p), 0);
+  if (e != hipSuccess || !dp) {
+    (void)hipGetLastError();
+    return ig_fail(ctx, IG_EINVAL, "host pool is not pinned, GPU-mapped memory (%s)", hipGetErrorString(e));
+  }
+  *out = dp;
+  return IG_OK;
+}
+
+int reserve_for(ig_ctx *ctx, const ig_desc *d, bool scores) {
+  ProjGeom g = ig_proj_geom(d);
+  int rc = ig_ensure(ctx, (void **)&ctx->part, &ctx->part_bytes,
+                     (size_t)g.KS * g.Bpad * g.Cpad * sizeof(float));
+  if (rc) return rc;
+  rc = ig_ensure(ctx, (void **)&ctx->qp, &ctx->qp_bytes, (size_t)d->B * d->H * d->r * sizeof(float));
+  if (rc) return rc;
+  if (scores) {
+    const int tile = ig_tile_tokens(d->dtype);
+    const int nTiles = (d->N_cap + tile - 1) / tile;
+    rc = ig_ensure(ctx, (void **)&ctx->scores, &ctx->scores_bytes,
+                   (size_t)d->B * d->H * d->N * sizeof(float));
+    if (rc) return rc;
+    rc = ig_ensure(ctx, (void **)&ctx->tmax, &ctx->tmax_bytes, (size_t)d->B * d->H * nTiles * sizeof(float));
+  }
+  return rc;
+}
+
+}  // namespace
+
+extern "C" {
+
+int ig_create(int device, ig_ctx **out) {
+  if (!out) return IG_EINVAL;
+  *out = nullptr;
+  int n = 0;
+  if (hipGetDeviceCount(&n) != hipSuccess || device < 0 || device >= n) return IG_EHIP;
+  ig_ctx *ctx = new (std::nothrow) ig_ctx();
+  if (!ctx) return IG_ENOMEM;
+  ctx->device = device;
+  ctx->err[0] = 0;
+  ctx->part = ctx->qp = ctx->scores = ctx->tmax = nullptr;
+  ctx->part_bytes = ctx->qp_bytes = ctx->scores_bytes = ctx->tmax_bytes = 0;
+  ctx->status = nullptr;
+  ctx->profiling = false;
+  memset(ctx->prof_ms, 0, sizeof(ctx->prof_ms));
+  memset(ctx->prof_n, 0, sizeof(ctx->prof_n));
+  if (hipSetDevice(device) != hipSuccess || hipMalloc((void **)&ctx->status, 256) != hipSuccess ||
+      hipMemset(ctx->status, 0, 256) != hipSuccess) {
+    delete ctx;
+    return IG_EHIP;
+  }
+  *out = ctx;
+  return IG_OK;
+}
+
+int ig_destroy(ig_ctx *ctx) {
+  if (!ctx) return IG_EINVAL;
+  (void)hipSetDevice(ctx->device);
+  (void)hipDeviceSynchronize();
+  for (auto &r : ctx->recs) {
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  for (auto &e : ctx->free_events) (void)hipEventDestroy(e);
+  if (ctx->part) (void)hipFree(ctx->part);
+  if (ctx->qp) (void)hipFree(ctx->qp);
+  if (ctx->scores) (void)hipFree(ctx->scores);
+  if (ctx->tmax) (void)hipFree(ctx->tmax);
+  if (ctx->status) (void)hipFree(ctx->status);
+  delete ctx;
+  return IG_OK;
+}
+
+const char *ig_last_error(const ig_ctx *ctx) { return ctx ? ctx->err : "context is NULL"; }
+
+int ig_reserve(ig_ctx *ctx, const ig_desc *desc) {
+  int rc = check_desc(ctx, desc);
+  if (rc) return rc;
+  if ((rc = set_device(ctx))) return rc;
+  return reserve_for(ctx, desc, true);
+}
+
+int ig_check_status(ig_ctx *ctx) {
+  if (!ctx) return IG_EINVAL;
+  int rc = set_device(ctx);
+  if (rc) return rc;
+  IG_HIP(ctx, hipDeviceSynchronize());
+  int32_t st = 0;
+  IG_HIP(ctx, hipMemcpy(&st, ctx->status, sizeof(st), hipMemcpyDeviceToHost));
+  if (st) IG_HIP(ctx, hipMemset(ctx->status, 0, sizeof(st)));
+  if (st & IG_STATUS_CAPACITY)
+    return ig_fail(ctx, IG_ECAPACITY, "a selected-token list was longer than sel_stride and was clamped");
+  return IG_OK;
+}
+
+size_t ig_wq_bytes(const ig_desc *d) {
+  if (!d || d->H < 1 || d->d < 1 || d->r < 1) return 0;
+  ProjGeom g = ig_proj_geom(d);
+  const size_t D = (size_t)d->H * d->d;
+  return D * g.Cpad * ig_elem_bytes(d->dtype);   // both layouts hold D x Cpad elements
+}
+
+int ig_wq_build(ig_ctx *ctx, const ig_desc *d, const void *Wq, const int32_t *idx_dev, void *wq,
+                void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!Wq || !wq || (!d->rope && !idx_dev)) return ig_fail(ctx, IG_EINVAL, "ig_wq_build: NULL argument");
+  if ((uintptr_t)wq % 16) return ig_fail(ctx, IG_EINVAL, "ig_wq_build: wq must be 16-byte aligned");
+  if ((rc = set_device(ctx))) return rc;
+  return ig_launch_wq_build(ctx, d, ig_proj_geom(d), Wq, idx_dev, wq, (hipStream_t)stream);
+}
+
+size_t ig_slab_bytes(const ig_desc *d) {
+  if (!d || d->B < 1 || d->H < 1 || d->r < 1 || d->N_cap < 1) return 0;
+  const int tile = ig_tile_tokens(d->dtype);
+  const size_t nTiles = ((size_t)d->N_cap + tile - 1) / tile;
+  return (size_t)d->B * d->H * nTiles * d->r * tile * ig_elem_bytes(d->dtype);
+}
+
+int ig_slab_build(ig_ctx *ctx, const ig_desc *d, const void *Kpool, int pool_space,
+                  const int32_t *idx_dev, void *slab, void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!Kpool || !idx_dev || !slab) return ig_fail(ctx, IG_EINVAL, "ig_slab_build: NULL argument");
+  if ((uintptr_t)slab % 16) return ig_fail(ctx, IG_EINVAL, "ig_slab_build: slab must be 16-byte aligned");
+  if ((rc = set_device(ctx))) return rc;
+  const void *kp = nullptr;
+  if ((rc = resolve_pool(ctx, Kpool, pool_space, &kp))) return rc;
+  return ig_launch_slab_build(ctx, d, kp, idx_dev, slab, (hipStream_t)stream);
+}
+
+static int project_partials(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq,
+                            const float *A_p, const int32_t *pos, ProjGeom *g, hipStream_t s) {
+  if (!x || !wq) return ig_fail(ctx, IG_EINVAL, "x or wq is NULL");
+  if (d->rope && (!A_p || !pos)) return ig_fail(ctx, IG_EINVAL, "rope mode needs A_p and pos");
+  int rc = set_device(ctx);
+  if (rc) return rc;
+  if ((rc = reserve_for(ctx, d, false))) return rc;
+  *g = ig_proj_geom(d);
+  return ig_launch_project(ctx, d, *g, x, wq, ctx->part, s);
+}
+
+int ig_project(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, const float *bias,
+               const float *A_p, const int32_t *pos, float *q_p, void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!q_p) return ig_fail(ctx, IG_EINVAL, "q_p is NULL");
+  ProjGeom g;
+  if ((rc = project_partials(ctx, d, x, wq, A_p, pos, &g, (hipStream_t)stream))) return rc;
+  return ig_launch_finalize(ctx, d, g, ctx->part, bias, A_p, pos, q_p, (hipStream_t)stream);
+}
+
+static int check_sel(ig_ctx *ctx, const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt) {
+  if (!sel_idx || !sel_cnt) return ig_fail(ctx, IG_EINVAL, "sel_idx or sel_cnt is NULL");
+  if (sel_stride < 1) return ig_fail(ctx, IG_ESHAPE, "sel_stride = %d", sel_stride);
+  return IG_OK;
+}
+
+int ig_scan_select(ig_ctx *ctx, const ig_desc *d, const float *q_p, const void *slab,
+                   int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, float *scores_opt,
+                   void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!q_p || !slab) return ig_fail(ctx, IG_EINVAL, "q_p or slab is NULL");
+  if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
+  if ((rc = set_device(ctx))) return rc;
+  QSource q{q_p, 1, 0, (long)d->H * d->r, nullptr};
+  return ig_launch_scan_select(ctx, d, q, slab, sel_idx, sel_stride, sel_cnt, scores_opt,
+                               (hipStream_t)stream);
+}
+
+int ig_speculate(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, const float *bias,
+                 const float *A_p, const int32_t *pos, const void *slab, int32_t *sel_idx,
+                 int32_t sel_stride, int32_t *sel_cnt, float *scores_opt, void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!slab) return ig_fail(ctx, IG_EINVAL, "slab is NULL");
+  if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
+  ProjGeom g;
+  hipStream_t s = (hipStream_t)stream;
+  if ((rc = project_partials(ctx, d, x, wq, A_p, pos, &g, s))) return rc;
+  if (d->rope) {
+    // rotary embedding and the partial skew sit between the projection and the scan
+    if ((rc = ig_launch_finalize(ctx, d, g, ctx->part, bias, A_p, pos, ctx->qp, s))) return rc;
+    QSource q{ctx->qp, 1, 0, (long)d->H * d->r, nullptr};
+    return ig_launch_scan_select(ctx, d, q, slab, sel_idx, sel_stride, sel_cnt, scores_opt, s);
+  }
+  // folded: the scan adds the split-K partial sums (and the bias) itself
+  QSource q{ctx->part, g.KS, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias};
+  return ig_launch_scan_select(ctx, d, q, slab, sel_idx, sel_stride, sel_cnt, scores_opt, s);
+}
+
+int ig_gather_kv(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const void *Vpool, int pool_space,
+                 const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt, void *K_sel,
+                 void *V_sel, void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!Kpool || !Vpool || !K_sel || !V_sel) return ig_fail(ctx, IG_EINVAL, "ig_gather_kv: NULL argument");
+  if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
+  if ((rc = set_device(ctx))) return rc;
+  const void *kp = nullptr, *vp = nullptr;
+  if ((rc = resolve_pool(ctx, Kpool, pool_space, &kp))) return rc;
+  if ((rc = resolve_pool(ctx, Vpool, pool_space, &vp))) return rc;
+  return ig_launch_gather(ctx, d, kp, vp, sel_idx, sel_stride, sel_cnt, K_sel, V_sel,
+                          (hipStream_t)stream);
+}
+
+int ig_sparse_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K_sel,
+                        const void *V_sel, const int32_t *sel_cnt, int32_t sel_stride,
+                        const void *k_new, const void *v_new, void *out, void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!q || !K_sel || !V_sel || !sel_cnt || !out) return ig_fail(ctx, IG_EINVAL, "ig_sparse_attention: NULL argument");
+  if ((k_new == nullptr) != (v_new == nullptr)) return ig_fail(ctx, IG_EINVAL, "k_new and v_new go together");
+  if (sel_stride < 1) return ig_fail(ctx, IG_ESHAPE, "sel_stride = %d", sel_stride);
+  if ((rc = set_device(ctx))) return rc;
+  return ig_launch_attention(ctx, d, q, K_sel, V_sel, nullptr, sel_stride, sel_cnt, sel_stride, k_new,
+                             v_new, out, (hipStream_t)stream);
+}
+
+int ig_sparse_attention_indexed(ig_ctx *ctx, const ig_desc *d, const void *q, const void *Kpool,
+                                const void *Vpool, const int32_t *sel_idx, int32_t sel_stride,
+                                const int32_t *sel_cnt, const void *k_new, const void *v_new,
+                                void *out, void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!q || !Kpool || !Vpool || !out) return ig_fail(ctx, IG_EINVAL, "ig_sparse_attention_indexed: NULL argument");
+  if ((k_new == nullptr) != (v_new == nullptr)) return ig_fail(ctx, IG_EINVAL, "k_new and v_new go together");
+  if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
+  if ((rc = set_device(ctx))) return rc;
+  return ig_launch_attention(ctx, d, q, Kpool, Vpool, sel_idx, sel_stride, sel_cnt, d->N_cap, k_new,
+                             v_new, out, (hipStream_t)stream);
+}
+
+int ig_profile_begin(ig_ctx *ctx) {
+  if (!ctx) return IG_EINVAL;
+  int rc = set_device(ctx);
+  if (rc) return rc;
+  IG_HIP(ctx, hipDeviceSynchronize());
+  for (auto &r : ctx->recs) {
+    ctx->free_events.push_back(r.e0);
+    ctx->free_events.push_back(r.e1);
+  }
+  ctx->recs.clear();
+  memset(ctx->prof_ms, 0, sizeof(ctx->prof_ms));
+  memset(ctx->prof_n, 0, sizeof(ctx->prof_n));
+  ctx->profiling = true;
+  return IG_OK;
+}
+
+int ig_profile_end(ig_ctx *ctx) {
+  if (!ctx) return IG_EINVAL;
+  int rc = set_device(ctx);
+  if (rc) return rc;
+  ctx->profiling = false;
+  IG_HIP(ctx, hipDeviceSynchronize());
+  for (auto &r : ctx->recs) {
+    float ms = 0.f;
+    IG_HIP(ctx, hipEventElapsedTime(&ms, r.e0, r.e1));
+    ctx->prof_ms[r.which] += ms;
+    ctx->prof_n[r.which] += 1;
+    ctx->free_events.push_back(r.e0);
+    ctx->free_events.push_back(r.e1);
+  }
+  ctx->recs.clear();
+  return IG_OK;
+}
+
+int ig_profile_read(ig_ctx *ctx, int which, double *total_ms, int32_t *launches) {
+  if (!ctx) return IG_EINVAL;
+  if (which < 0 || which >= IG_K_COUNT) return ig_fail(ctx, IG_EINVAL, "unknown kernel id %d", which);
+  if (total_ms) *total_ms = ctx->prof_ms[which];
+  if (launches) *launches = ctx->prof_n[which];
+  return IG_OK;
+}
+
+int ig_copy_bytes(ig_ctx *ctx, const void *src, void *dst, size_t bytes, void *stream) {
+  if (!ctx) return IG_EINVAL;
+  if (!src || !dst) return ig_fail(ctx, IG_EINVAL, "ig_copy_bytes: NULL argument");
+  if (bytes % 16 || (uintptr_t)src % 16 || (uintptr_t)dst % 16)
+    return ig_fail(ctx, IG_EINVAL, "ig_copy_bytes: size and pointers must be multiples of 16");
+  int rc = set_device(ctx);
+  if (rc) return rc;
+  return ig_launch_copy(ctx, src, dst, bytes, (hipStream_t)stream);
+}
+
+}  // extern "C"

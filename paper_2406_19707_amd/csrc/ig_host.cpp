@@ -1,0 +1,153 @@
+// Host-side, offline parts of the library: weight skewing and partial weight index generation.
+// Plain C++ (no GPU calls); float32 data, double arithmetic.
+#include <math.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <algorithm>
+#include <numeric>
+#include <vector>
+
+#include "../../include/infinigen.h"
+
+struct ig_ctx;
+int ig_fail(ig_ctx *ctx, int code, const char *fmt, ...);
+
+namespace {
+
+// Eigen-decomposition of a symmetric d x d matrix by cyclic two-sided Jacobi rotations.
+// On return G's diagonal holds the eigenvalues and the columns of V the eigenvectors.
+bool jacobi_eigen(int d, std::vector<double> &G, std::vector<double> &V) {
+  V.assign((size_t)d * d, 0.0);
+  for (int i = 0; i < d; ++i) V[(size_t)i * d + i] = 1.0;
+  for (int sweep = 0; sweep < 80; ++sweep) {
+    bool rotated = false;
+    for (int p = 0; p < d - 1; ++p)
+      for (int q = p + 1; q < d; ++q) {
+        double gpq = G[(size_t)p * d + q];
+        double gpp = G[(size_t)p * d + p], gqq = G[(size_t)q * d + q];
+        if (gpq == 0.0 || fabs(gpq) <= 1e-17 * sqrt(fabs(gpp * gqq))) continue;
+        rotated = true;
+        double theta = (gqq - gpp) / (2.0 * gpq);
+        double t = (theta >= 0 ? 1.0 : -1.0) / (fabs(theta) + sqrt(theta * theta + 1.0));
+        double c = 1.0 / sqrt(t * t + 1.0), s = t * c;
+        for (int k = 0; k < d; ++k) {   // columns p, q
+          double a = G[(size_t)k * d + p], b = G[(size_t)k * d + q];
+          G[(size_t)k * d + p] = c * a - s * b;
+          G[(size_t)k * d + q] = s * a + c * b;
+        }
+        for (int k = 0; k < d; ++k) {   // rows p, q
+          double a = G[(size_t)p * d + k], b = G[(size_t)q * d + k];
+          G[(size_t)p * d + k] = c * a - s * b;
+          G[(size_t)q * d + k] = s * a + c * b;
+        }
+        for (int k = 0; k < d; ++k) {
+          double a = V[(size_t)k * d + p], b = V[(size_t)k * d + q];
+          V[(size_t)k * d + p] = c * a - s * b;
+          V[(size_t)k * d + q] = s * a + c * b;
+        }
+      }
+    if (!rotated) return true;
+  }
+  return false;
+}
+
+// out[:, head h] = W[:, head h] * A_h, rows of W processed one at a time.
+void skew_rows(int rows, int D, int H, const float *W, const float *A, float *out) {
+  const int d = D / H;
+  std::vector<double> acc(d);
+  for (int i = 0; i < rows; ++i)
+    for (int h = 0; h < H; ++h) {
+      std::fill(acc.begin(), acc.end(), 0.0);
+      const float *w = W + (size_t)i * D + (size_t)h * d;
+      const float *a = A + (size_t)h * d * d;
+      for (int k = 0; k < d; ++k) {
+        const double wk = w[k];
+        const float *ak = a + (size_t)k * d;
+        for (int j = 0; j < d; ++j) acc[j] += wk * (double)ak[j];
+      }
+      float *o = out + (size_t)i * D + (size_t)h * d;
+      for (int j = 0; j < d; ++j) o[j] = (float)acc[j];
+    }
+}
+
+}  // namespace
+
+extern "C" int ig_skew_offline(ig_ctx *ctx, int D, int H, int n_cal, const float *Wq, const float *Wk,
+                               const float *bq, const float *bk, const float *Qcal, float *A,
+                               float *sigma, float *Wq_s, float *Wk_s, float *bq_s, float *bk_s) {
+  if (D < 1 || H < 1 || D % H || n_cal < 1) return ig_fail(ctx, IG_ESHAPE, "ig_skew_offline: bad shape");
+  if (!Qcal || !A) return ig_fail(ctx, IG_EINVAL, "ig_skew_offline: Qcal or A is NULL");
+  const int d = D / H;
+  int rc = IG_OK;
+  std::vector<double> G((size_t)d * d), V, qrow(d);
+  std::vector<int> order(d);
+  for (int h = 0; h < H; ++h) {
+    // Gram matrix of the head's calibration queries: Q_h^T Q_h = V S^2 V^T, so its eigenvectors
+    // are the right singular vectors of Q_h and its eigenvalues the squared singular values.
+    std::fill(G.begin(), G.end(), 0.0);
+    for (int i = 0; i < n_cal; ++i) {
+      const float *row = Qcal + (size_t)i * D + (size_t)h * d;
+      for (int a = 0; a < d; ++a) qrow[a] = row[a];
+      for (int a = 0; a < d; ++a) {
+        const double qa = qrow[a];
+        double *g = &G[(size_t)a * d];
+        for (int b = a; b < d; ++b) g[b] += qa * qrow[b];
+      }
+    }
+    for (int a = 0; a < d; ++a)
+      for (int b = 0; b < a; ++b) G[(size_t)a * d + b] = G[(size_t)b * d + a];
+    if (!jacobi_eigen(d, G, V)) rc = IG_ENOCONV;
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) {
+      return G[(size_t)x * d + x] > G[(size_t)y * d + y];
+    });
+    float *Ah = A + (size_t)h * d * d;
+    for (int j = 0; j < d; ++j) {
+      const int src = order[j];
+      int arg = 0;
+      for (int i = 1; i < d; ++i)
+        if (fabs(V[(size_t)i * d + src]) > fabs(V[(size_t)arg * d + src])) arg = i;
+      const double sgn = V[(size_t)arg * d + src] < 0 ? -1.0 : 1.0;
+      for (int i = 0; i < d; ++i) Ah[(size_t)i * d + j] = (float)(sgn * V[(size_t)i * d + src]);
+      if (sigma) sigma[(size_t)h * d + j] = (float)sqrt(std::max(0.0, G[(size_t)src * d + src]));
+    }
+  }
+  if (Wq && Wq_s) skew_rows(D, D, H, Wq, A, Wq_s);
+  if (Wk && Wk_s) skew_rows(D, D, H, Wk, A, Wk_s);
+  if (bq && bq_s) skew_rows(1, D, H, bq, A, bq_s);
+  if (bk && bk_s) skew_rows(1, D, H, bk, A, bk_s);
+  if (rc == IG_ENOCONV) return ig_fail(ctx, rc, "ig_skew_offline: Jacobi sweeps exceeded their cap");
+  return rc;
+}
+
+extern "C" int ig_partial_index(ig_ctx *ctx, int H, int d, int n, const float *Qs, const float *Ks,
+                                double ratio, int32_t *idx, int32_t *r_out) {
+  if (H < 1 || d < 1 || n < 1) return ig_fail(ctx, IG_ESHAPE, "ig_partial_index: bad shape");
+  if (!Qs) return ig_fail(ctx, IG_EINVAL, "ig_partial_index: Qs is NULL");
+  if (!(ratio > 0.0) || ratio > 1.0) return ig_fail(ctx, IG_EINVAL, "ig_partial_index: ratio must be in (0, 1]");
+  const int r = (int)floor(ratio * (double)d);
+  if (r < 1) return ig_fail(ctx, IG_ESHAPE, "ig_partial_index: ratio * d < 1");
+  if (r_out) *r_out = r;
+  if (!idx) return IG_OK;
+  const size_t D = (size_t)H * d;
+  std::vector<double> colsum(D, 0.0);
+  for (int i = 0; i < n; ++i) {
+    const float *qrow = Qs + (size_t)i * D;
+    for (size_t c = 0; c < D; ++c) colsum[c] += fabs((double)qrow[c]);
+    if (Ks) {
+      const float *krow = Ks + (size_t)i * D;
+      for (size_t c = 0; c < D; ++c) colsum[c] += fabs((double)krow[c]);
+    }
+  }
+  std::vector<int> order(d);
+  for (int h = 0; h < H; ++h) {
+    const double *c = &colsum[(size_t)h * d];
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return c[x] > c[y]; });
+    std::vector<int> keep(order.begin(), order.begin() + r);
+    std::sort(keep.begin(), keep.end());
+    for (int k = 0; k < r; ++k) idx[(size_t)h * r + k] = keep[k];
+  }
+  return IG_OK;
+}

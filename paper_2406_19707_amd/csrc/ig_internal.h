@@ -1,0 +1,145 @@
+// Internal declarations shared by the HIP sources of libinfinigen_hip (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <vector>
+
+#include "../../include/infinigen.h"
+
+typedef _Float16 half_t;
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+// 16-byte vector view of the storage type: 8 halves or 4 floats per lane and load.
+template <typename T> struct Elem;
+template <> struct Elem<half_t> {
+  static constexpr int TPL = 8;
+  typedef half8 vec;
+};
+template <> struct Elem<float> {
+  static constexpr int TPL = 4;
+  typedef floatx4 vec;
+};
+
+constexpr int IG_WAVE = 64;
+constexpr int IG_KS_MAX = 16;     // split-K partial sums a consumer adds up at most
+constexpr int IG_STATUS_CAPACITY = 1;
+
+// Slab geometry: tokens are grouped in tiles of 64 lanes x TPL tokens; inside a tile the r kept
+// channels are planes of TILE contiguous tokens:  slab[(bh*nTiles + tile)*r*TILE + j*TILE + t%TILE].
+template <typename T> __host__ __device__ constexpr int tile_tokens() { return IG_WAVE * Elem<T>::TPL; }
+static inline int ig_tile_tokens(int dtype) { return dtype == IG_F16 ? 512 : 256; }
+static inline int ig_elem_bytes(int dtype) { return dtype == IG_F16 ? 2 : 4; }
+
+// Geometry of the partial query projection.
+struct ProjGeom {
+  int C;        // output columns: H*r (folded) or D (rope)
+  int nCblk;    // column blocks of 16
+  int Cpad;     // nCblk*16
+  int nKblk;    // K blocks of 32 (MFMA path) -- D/32
+  int KS;       // split-K factor (<= IG_KS_MAX)
+  int kb_per;   // K blocks (MFMA) or K rows (VALU) per split
+  int NBtot;    // batch blocks of 16
+  int Bpad;     // NBtot*16
+  bool mfma;    // f16 and D % 32 == 0
+};
+ProjGeom ig_proj_geom(const ig_desc *d);
+
+struct ProfRec {
+  int which;
+  hipEvent_t e0, e1;
+};
+
+struct ig_ctx {
+  int device;
+  char err[512];
+  float *part;      size_t part_bytes;    // projection partial sums [KS][Bpad][Cpad]
+  float *qp;        size_t qp_bytes;      // finalised partial queries [B,H,r]
+  float *scores;    size_t scores_bytes;  // long-sequence path: s [B*H, N]
+  float *tmax;      size_t tmax_bytes;    // long-sequence path: per-tile maxima [B*H, nTiles]
+  int32_t *status;                        // device status word (sticky flags)
+  bool profiling;
+  std::vector<ProfRec> recs;
+  std::vector<hipEvent_t> free_events;
+  double prof_ms[IG_K_COUNT];
+  int prof_n[IG_K_COUNT];
+};
+
+int ig_fail(ig_ctx *ctx, int code, const char *fmt, ...);
+int ig_hip_fail(ig_ctx *ctx, hipError_t e, const char *what);
+int ig_ensure(ig_ctx *ctx, void **p, size_t *have, size_t need);
+void ig_prof_events(ig_ctx *ctx, int which, hipEvent_t *e0, hipEvent_t *e1);
+
+#define IG_HIP(ctx, call)                                        \
+  do {                                                           \
+    hipError_t e__ = (call);                                     \
+    if (e__ != hipSuccess) return ig_hip_fail(ctx, e__, #call);  \
+  } while (0)
+
+// Launch a kernel; while profiling, attach start/stop events that take the kernel's own timestamps.
+#define IG_LAUNCH(ctx, which, kernel, grid, block, stream, ...)                                    \
+  do {                                                                                             \
+    if ((ctx)->profiling) {                                                                        \
+      hipEvent_t e0__, e1__;                                                                       \
+      ig_prof_events(ctx, which, &e0__, &e1__);                                                    \
+      hipExtLaunchKernelGGL(kernel, grid, block, 0, (hipStream_t)(stream), e0__, e1__, 0,          \
+                            __VA_ARGS__);                                                          \
+    } else {                                                                                       \
+      hipLaunchKernelGGL(kernel, grid, block, 0, (hipStream_t)(stream), __VA_ARGS__);              \
+    }                                                                                              \
+    hipError_t le__ = hipGetLastError();                                                           \
+    if (le__ != hipSuccess) return ig_hip_fail(ctx, le__, #kernel);                                \
+  } while (0)
+
+// ---- launchers implemented in the kernel sources (host functions, return IG_* codes) ----------
+int ig_launch_wq_build(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const void *Wq,
+                       const int32_t *idx, void *wq, hipStream_t s);
+int ig_launch_slab_build(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const int32_t *idx,
+                         void *slab, hipStream_t s);
+int ig_launch_project(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const void *x,
+                      const void *wq, float *part, hipStream_t s);
+int ig_launch_finalize(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const float *part,
+                       const float *bias, const float *A_p, const int32_t *pos, float *q_p,
+                       hipStream_t s);
+// q source for the scan: value(b,h,j) = bias[h*r+j] + sum_{s<ks} qsrc[s*ks_stride + b*b_stride + h*r + j]
+struct QSource {
+  const float *qsrc;
+  int ks;
+  long ks_stride;
+  long b_stride;
+  const float *bias;
+};
+int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const void *slab,
+                          int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
+                          float *scores_opt, hipStream_t s);
+int ig_launch_gather(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const void *Vpool,
+                     const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt,
+                     void *K_sel, void *V_sel, hipStream_t s);
+int ig_launch_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, const void *V,
+                        const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt,
+                        int kv_rows_per_bh, const void *k_new, const void *v_new, void *out,
+                        hipStream_t s);
+int ig_launch_copy(ig_ctx *ctx, const void *src, void *dst, size_t bytes, hipStream_t s);
+
+// ---- wave helpers -------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int u = __shfl_up(v, o, 64);
+    if (lane >= o) v += u;
+  }
+  return v;
+}

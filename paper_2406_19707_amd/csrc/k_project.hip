@@ -1,0 +1,269 @@
+// Partial query projection (Section 4.3 "Decoding Stage": attention input of the previous layer
+// times the partial query weight) and the small finalisation step (bias, rotary embedding and the
+// partial skew A_h[:, idx_h] for models whose skew cannot be folded into W_Q).
+//
+// The projection reads the weight once (it is weight-read bound: B is 4..20 rows).  For half
+// precision it runs on the matrix cores: the weight blob is stored in MFMA fragment order, so that
+// every wave-wide load is one contiguous 1 KiB piece, the batch rows are the N side of a
+// 16x16x32 MFMA, and K is split across waves to get enough waves in flight; the split-K partial
+// sums are written out and added, in a fixed order, by the consumer.  float32 (and half with
+// D % 32 != 0) uses a plain FMA kernel over the same split.
+#include "ig_internal.h"
+
+ProjGeom ig_proj_geom(const ig_desc *d) {
+  ProjGeom g;
+  const int D = d->H * d->d;
+  g.C = d->rope ? D : d->H * d->r;
+  g.nCblk = (g.C + 15) / 16;
+  g.Cpad = g.nCblk * 16;
+  g.NBtot = (d->B + 15) / 16;
+  g.Bpad = g.NBtot * 16;
+  g.mfma = d->dtype == IG_F16 && D % 32 == 0;
+  const int units = g.mfma ? D / 32 : D;          // K units that can be split
+  g.nKblk = g.mfma ? D / 32 : 0;
+  // aim for >= 2048 waves (8 per compute unit) but never more than IG_KS_MAX partial sums
+  const int col_waves = g.mfma ? g.nCblk : (g.Cpad + 63) / 64;
+  int ks = (2048 + col_waves - 1) / col_waves;
+  if (ks > IG_KS_MAX) ks = IG_KS_MAX;
+  if (ks > units) ks = units;
+  if (ks < 1) ks = 1;
+  g.kb_per = (units + ks - 1) / ks;
+  g.KS = (units + g.kb_per - 1) / g.kb_per;
+  return g;
+}
+
+namespace {
+
+// ---- weight blob construction -------------------------------------------------------------------
+// Column c of the blob is column colmap(c) of Wq: h*d + idx[h*r + j] for c = h*r + j (folded), or c
+// itself (rope: every column kept).
+__device__ __forceinline__ int colmap(int c, int d, int r, const int32_t *idx) {
+  if (!idx) return c;
+  int h = c / r, j = c % r;
+  return h * d + idx[h * r + j];
+}
+
+// MFMA fragment order: piece (cblk, kblk) is 64 lanes x 8 halves; lane (kg = lane/16, i = lane%16)
+// holds W[k = kblk*32 + kg*8 + e][col(cblk*16 + i)], e < 8.
+__global__ void wq_build_mfma(const half_t *W, const int32_t *idx, half8 *blob, int D, int d, int r,
+                              int C, int nCblk, int nKblk) {
+  long g = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  long total = (long)nCblk * nKblk * 64;
+  if (g >= total) return;
+  int lane = g & 63;
+  long piece = g >> 6;
+  int kblk = piece % nKblk, cblk = piece / nKblk;
+  int i = lane & 15, kg = lane >> 4;
+  int c = cblk * 16 + i;
+  half8 v;
+  if (c < C) {
+    int col = colmap(c, d, r, idx);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = W[(long)(kblk * 32 + kg * 8 + e) * D + col];
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = (half_t)0;
+  }
+  blob[g] = v;
+}
+
+// Plain layout for the FMA kernel: blob[k][c], c < Cpad (zero padded).
+template <typename T>
+__global__ void wq_build_plain(const T *W, const int32_t *idx, T *blob, int D, int d, int r, int C,
+                               int Cpad) {
+  long g = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (g >= (long)D * Cpad) return;
+  int c = g % Cpad;
+  long k = g / Cpad;
+  blob[g] = (c < C) ? W[k * D + colmap(c, d, r, idx)] : (T)0;
+}
+
+// ---- projection ---------------------------------------------------------------------------------
+// Wave (cblk, ks): part[ks][n][cblk*16 + i] = sum over its K blocks of W^T-fragment x x-fragment.
+// A operand = weight piece (M side = 16 output columns), B operand = 16 batch rows of x.
+// Result lane l, register v -> column cblk*16 + 4*(l/16) + v, batch row l%16.
+template <int NB>
+__global__ __launch_bounds__(256) void project_mfma(const half8 *__restrict__ blob,
+                                                    const half_t *__restrict__ x,
+                                                    float *__restrict__ part, int B, int D,
+                                                    int nCblk, int nKblk, int kb_per, int KS,
+                                                    int Bpad, int Cpad) {
+  const int lane = threadIdx.x & 63;
+  const long gw = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (gw >= (long)nCblk * KS) return;
+  const int cblk = gw % nCblk, ks = gw / nCblk;
+  const int nb0 = blockIdx.y * NB;
+  const int n = lane & 15, kg = lane >> 4;
+  const int kb0 = ks * kb_per, kb1 = min(nKblk, kb0 + kb_per);
+  floatx4 acc[NB];
+#pragma unroll
+  for (int i = 0; i < NB; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const half8 *wp = blob + ((long)cblk * nKblk + kb0) * 64 + lane;
+  const half8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll 4
+  for (int kb = kb0; kb < kb1; ++kb, wp += 64) {
+    half8 a = *wp;
+#pragma unroll
+    for (int i = 0; i < NB; ++i) {
+      int row = (nb0 + i) * 16 + n;
+      half8 bfrag = zero;
+      if (row < B) bfrag = *reinterpret_cast<const half8 *>(x + (long)row * D + kb * 32 + kg * 8);
+      acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bfrag, acc[i], 0, 0, 0);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    int row = (nb0 + i) * 16 + n;
+    if (row < Bpad) {
+      float *o = part + ((long)ks * Bpad + row) * Cpad + cblk * 16 + kg * 4;
+      *reinterpret_cast<floatx4 *>(o) = acc[i];
+    }
+  }
+}
+
+// One thread per output column, 16 batch rows per pass, K rows [ks*kb_per, ...).
+template <typename T>
+__global__ __launch_bounds__(64) void project_fma(const T *__restrict__ blob, const T *__restrict__ x,
+                                                  float *__restrict__ part, int B, int D, int kb_per,
+                                                  int Bpad, int Cpad) {
+  const int c = blockIdx.x * 64 + threadIdx.x;
+  const int ks = blockIdx.y;
+  const int n0 = blockIdx.z * 16;
+  if (c >= Cpad) return;
+  const int k0 = ks * kb_per, k1 = min(D, k0 + kb_per);
+  float acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+  for (int k = k0; k < k1; ++k) {
+    float wv = (float)blob[(long)k * Cpad + c];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      int row = n0 + i;
+      float xv = (row < B) ? (float)x[(long)row * D + k] : 0.f;
+      acc[i] = fmaf(xv, wv, acc[i]);
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < 16; ++i) part[((long)ks * Bpad + n0 + i) * Cpad + c] = acc[i];
+}
+
+// ---- finalisation -------------------------------------------------------------------------------
+// folded: q_p[b,h,j] = bias[h*r+j] + sum_s part[s][b][h*r+j]
+// rope:   q[c] = bias[h*d+c] + sum_s part[s][b][h*d+c]; rotate pairs (c, c+d/2) by
+//         pos[b]*theta^(-2c/d) (angle in double: positions reach 1e5 where float loses the phase);
+//         q_p[b,h,k] = sum_c q_rot[c] * A_p[h][c][k]
+__global__ __launch_bounds__(256) void finalize_query(const float *__restrict__ part,
+                                                      const float *__restrict__ bias,
+                                                      const float *__restrict__ A_p,
+                                                      const int32_t *__restrict__ pos,
+                                                      float *__restrict__ q_p, int H, int d, int r,
+                                                      int KS, long ks_stride, int Cpad, int rope,
+                                                      float theta) {
+  __shared__ float q[512];
+  __shared__ float qr[512];
+  const int bh = blockIdx.x, b = bh / H, h = bh % H;
+  const int t = threadIdx.x;
+  if (!rope) {
+    for (int j = t; j < r; j += blockDim.x) {
+      float acc = bias ? bias[h * r + j] : 0.f;
+      for (int s = 0; s < KS; ++s) acc += part[s * ks_stride + (long)b * Cpad + h * r + j];
+      q_p[(long)bh * r + j] = acc;
+    }
+    return;
+  }
+  for (int c = t; c < d; c += blockDim.x) {
+    float acc = bias ? bias[h * d + c] : 0.f;
+    for (int s = 0; s < KS; ++s) acc += part[s * ks_stride + (long)b * Cpad + h * d + c];
+    q[c] = acc;
+  }
+  __syncthreads();
+  const int half = d / 2;
+  for (int c = t; c < half; c += blockDim.x) {
+    double ang = (double)pos[b] * exp2(-2.0 * (double)c / (double)d * log2((double)theta));
+    double sn, cs;
+    sincos(ang, &sn, &cs);
+    float a = q[c], bb = q[c + half];
+    qr[c] = (float)((double)a * cs - (double)bb * sn);
+    qr[c + half] = (float)((double)bb * cs + (double)a * sn);
+  }
+  __syncthreads();
+  for (int k = t; k < r; k += blockDim.x) {
+    float acc = 0.f;
+    const float *ap = A_p + (long)h * d * r + k;
+    for (int c = 0; c < d; ++c) acc = fmaf(qr[c], ap[(long)c * r], acc);
+    q_p[(long)bh * r + k] = acc;
+  }
+}
+
+}  // namespace
+
+int ig_launch_wq_build(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const void *Wq,
+                       const int32_t *idx, void *wq, hipStream_t s) {
+  const int D = d->H * d->d;
+  const int32_t *ix = d->rope ? nullptr : idx;
+  if (g.mfma) {
+    long total = (long)g.nCblk * g.nKblk * 64;
+    auto k = wq_build_mfma;
+    IG_LAUNCH(ctx, IG_K_BUILD, k, dim3((unsigned)((total + 255) / 256)), dim3(256), s,
+              (const half_t *)Wq, ix, (half8 *)wq, D, (int)d->d, (int)d->r, g.C, g.nCblk, g.nKblk);
+  } else if (d->dtype == IG_F16) {
+    long total = (long)D * g.Cpad;
+    auto k = wq_build_plain<half_t>;
+    IG_LAUNCH(ctx, IG_K_BUILD, k, dim3((unsigned)((total + 255) / 256)), dim3(256), s,
+              (const half_t *)Wq, ix, (half_t *)wq, D, (int)d->d, (int)d->r, g.C, g.Cpad);
+  } else {
+    long total = (long)D * g.Cpad;
+    auto k = wq_build_plain<float>;
+    IG_LAUNCH(ctx, IG_K_BUILD, k, dim3((unsigned)((total + 255) / 256)), dim3(256), s,
+              (const float *)Wq, ix, (float *)wq, D, (int)d->d, (int)d->r, g.C, g.Cpad);
+  }
+  return IG_OK;
+}
+
+int ig_launch_project(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const void *x,
+                      const void *wq, float *part, hipStream_t s) {
+  const int D = d->H * d->d;
+  if (g.mfma) {
+    long waves = (long)g.nCblk * g.KS;
+    dim3 block(256);
+    if (g.NBtot == 1) {
+      auto k = project_mfma<1>;
+      IG_LAUNCH(ctx, IG_K_PROJECT, k, dim3((unsigned)((waves + 3) / 4), 1), block, s,
+                (const half8 *)wq, (const half_t *)x, part, (int)d->B, D, g.nCblk, g.nKblk, g.kb_per,
+                g.KS, g.Bpad, g.Cpad);
+    } else if (g.NBtot == 2) {
+      auto k = project_mfma<2>;
+      IG_LAUNCH(ctx, IG_K_PROJECT, k, dim3((unsigned)((waves + 3) / 4), 1), block, s,
+                (const half8 *)wq, (const half_t *)x, part, (int)d->B, D, g.nCblk, g.nKblk, g.kb_per,
+                g.KS, g.Bpad, g.Cpad);
+    } else {
+      auto k = project_mfma<4>;
+      IG_LAUNCH(ctx, IG_K_PROJECT, k, dim3((unsigned)((waves + 3) / 4), (unsigned)((g.NBtot + 3) / 4)),
+                block, s, (const half8 *)wq, (const half_t *)x, part, (int)d->B, D, g.nCblk, g.nKblk,
+                g.kb_per, g.KS, g.Bpad, g.Cpad);
+    }
+  } else {
+    dim3 grid((g.Cpad + 63) / 64, g.KS, g.NBtot), block(64);
+    if (d->dtype == IG_F16) {
+      auto k = project_fma<half_t>;
+      IG_LAUNCH(ctx, IG_K_PROJECT, k, grid, block, s, (const half_t *)wq, (const half_t *)x, part,
+                (int)d->B, D, g.kb_per, g.Bpad, g.Cpad);
+    } else {
+      auto k = project_fma<float>;
+      IG_LAUNCH(ctx, IG_K_PROJECT, k, grid, block, s, (const float *)wq, (const float *)x, part,
+                (int)d->B, D, g.kb_per, g.Bpad, g.Cpad);
+    }
+  }
+  return IG_OK;
+}
+
+int ig_launch_finalize(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const float *part,
+                       const float *bias, const float *A_p, const int32_t *pos, float *q_p,
+                       hipStream_t s) {
+  if (d->rope && d->d > 512) return ig_fail(ctx, IG_ESHAPE, "rope: d = %d exceeds 512", d->d);
+  auto k = finalize_query;
+  IG_LAUNCH(ctx, IG_K_FINALIZE, k, dim3(d->B * d->H), dim3(256), s, part, bias, A_p, pos, q_p,
+            (int)d->H, (int)d->d, (int)d->r, g.KS, (long)g.Bpad * g.Cpad, g.Cpad, (int)d->rope,
+            (float)d->rope_theta);
+  return IG_OK;
+}

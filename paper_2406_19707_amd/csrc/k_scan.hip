@@ -1,0 +1,355 @@
+// Partial key cache scan, per-head maximum, (max - alpha) threshold and compaction
+// (Section 4.3 "Decoding Stage": speculated score = partial query x partial key cache; tokens whose
+// score reaches the maximum minus alpha are kept).
+//
+// Layout the scan relies on (written by ig_slab_build): per (sequence, head) the tokens are cut
+// into tiles of 64 x TPL tokens (TPL = 8 halves or 4 floats = 16 bytes per lane); inside a tile the
+// r kept channels are planes of TILE contiguous tokens.  A wave owns one tile: for every channel it
+// issues one fully coalesced 1 KiB load (lane l gets tokens l*TPL .. l*TPL+TPL-1 of that channel)
+// and multiplies by the wave-uniform partial query entry, so a token's score is accumulated in
+// one lane without any cross-lane reduction.  The kernel is HBM-bound (1 FMA per 2 bytes).
+#include "ig_internal.h"
+
+namespace {
+
+struct ScanArgs {
+  const void *slab;
+  const float *qsrc;
+  const float *bias;
+  int32_t *sel_idx;
+  int32_t *sel_cnt;
+  float *scores_out;   // optional dump (fused) / score buffer (tiled)
+  float *tmax;         // tiled path: per-tile maxima
+  int32_t *status;
+  long ks_stride;
+  long b_stride;
+  int ks;
+  int H, r, N, nTiles;
+  int sel_stride;
+  float scale, alpha;
+};
+
+// Partial query of (b,h) into LDS, scaled, zero-padded to `padded` entries.
+// value(j) = scale * (bias[h*r+j] + sum_s qsrc[s*ks_stride + b*b_stride + h*r + j]); the partial
+// sums are loaded up front (independent loads) and added in a fixed order.
+__device__ __forceinline__ void stage_query(const ScanArgs &a, int b, int h, float *q_lds, int padded) {
+  for (int j = threadIdx.x; j < padded; j += blockDim.x) {
+    float v = 0.f;
+    if (j < a.r) {
+      const float *p = a.qsrc + (long)b * a.b_stride + (long)h * a.r + j;
+      float part[IG_KS_MAX];
+#pragma unroll
+      for (int s = 0; s < IG_KS_MAX; ++s) part[s] = (s < a.ks) ? p[(long)s * a.ks_stride] : 0.f;
+      float acc = a.bias ? a.bias[h * a.r + j] : 0.f;
+#pragma unroll
+      for (int s = 0; s < IG_KS_MAX; ++s) acc += part[s];
+      v = acc * a.scale;
+    }
+    q_lds[j] = v;
+  }
+}
+
+template <typename T, int CH>
+__device__ __forceinline__ void load_block(const T *tile, int r, int j0, int lane,
+                                           typename Elem<T>::vec (&v)[CH]) {
+  constexpr int TPL = Elem<T>::TPL;
+  constexpr int TILE = IG_WAVE * TPL;
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    int jj = min(j0 + j, r - 1);   // channels past r re-read the last plane; their query entry is 0
+    v[j] = *reinterpret_cast<const typename Elem<T>::vec *>(tile + (long)jj * TILE + lane * TPL);
+  }
+}
+
+template <typename T, int CH>
+__device__ __forceinline__ void fma_block(const typename Elem<T>::vec (&v)[CH], const float *q_lds,
+                                          int j0, float (&acc)[Elem<T>::TPL]) {
+  constexpr int TPL = Elem<T>::TPL;
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    float qj = q_lds[j0 + j];
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) acc[e] = fmaf((float)v[j][e], qj, acc[e]);
+  }
+}
+
+// Threshold + ordered compaction of the scores a block holds in registers.  Wave w holds the
+// scores of tokens t0 + lane*TPL + e (e < TPL); waves are in ascending token order.  `base`
+// is the number of tokens already emitted for this (b,h).  Returns the block's total.
+template <int TPL, int NW>
+__device__ __forceinline__ int compact_block(const float (&sc)[TPL], int t0, int N, float thr,
+                                             int base, int32_t *list, int sel_stride, int *lds_cnt,
+                                             int w, int lane) {
+  unsigned mask = 0;
+#pragma unroll
+  for (int e = 0; e < TPL; ++e) {
+    int t = t0 + lane * TPL + e;
+    if (t < N && sc[e] >= thr) mask |= 1u << e;
+  }
+  int cnt = __popc(mask);
+  int incl = wave_incl_scan(cnt, lane);
+  int total = __shfl(incl, 63, 64);
+  if (lane == 0) lds_cnt[w] = total;
+  __syncthreads();
+  int before = 0, all = 0;
+#pragma unroll
+  for (int k = 0; k < NW; ++k) {
+    int c = lds_cnt[k];
+    before += (k < w) ? c : 0;
+    all += c;
+  }
+  int pos = base + before + incl - cnt;
+#pragma unroll
+  for (int e = 0; e < TPL; ++e) {
+    if (mask & (1u << e)) {
+      if (pos < sel_stride) list[pos] = t0 + lane * TPL + e;
+      ++pos;
+    }
+  }
+  __syncthreads();   // lds_cnt may be reused by the caller
+  return all;
+}
+
+// One workgroup per (b,h); wave w scans tile w (nTiles <= NW).  Scores never leave registers.
+template <typename T, int CH, int NW>
+__global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
+  constexpr int TPL = Elem<T>::TPL;
+  constexpr int TILE = IG_WAVE * TPL;
+  __shared__ float q_lds[256 + CH];
+  __shared__ float lds_max[NW];
+  __shared__ int lds_cnt[NW];
+  const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const bool active = w < a.nTiles;
+  const T *tile = static_cast<const T *>(a.slab) + ((long)bh * a.nTiles + (active ? w : 0)) * a.r * TILE;
+  const int padded = (a.r + CH - 1) / CH * CH;
+
+  typename Elem<T>::vec v[CH];
+  float acc[TPL];
+#pragma unroll
+  for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
+
+  // query partial sums first, then the first block of slab loads, so that waiting for the query
+  // leaves the slab loads in flight
+  stage_query(a, b, h, q_lds, padded);
+  if (active) load_block<T, CH>(tile, a.r, 0, lane, v);
+  __syncthreads();
+  if (active) {
+    fma_block<T, CH>(v, q_lds, 0, acc);
+    for (int j0 = CH; j0 < a.r; j0 += CH) {
+      load_block<T, CH>(tile, a.r, j0, lane, v);
+      fma_block<T, CH>(v, q_lds, j0, acc);
+    }
+  }
+  const int t0 = w * TILE;
+  float m = -INFINITY;
+#pragma unroll
+  for (int e = 0; e < TPL; ++e) {
+    int t = t0 + lane * TPL + e;
+    if (!active || t >= a.N) acc[e] = -INFINITY;
+    m = fmaxf(m, acc[e]);
+  }
+  if (a.scores_out && active) {
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) {
+      int t = t0 + lane * TPL + e;
+      if (t < a.N) a.scores_out[(long)bh * a.N + t] = acc[e];
+    }
+  }
+  m = wave_max(m);
+  if (lane == 0) lds_max[w] = m;
+  __syncthreads();
+  float mm = lds_max[0];
+#pragma unroll
+  for (int k = 1; k < NW; ++k) mm = fmaxf(mm, lds_max[k]);
+  const float thr = mm - a.alpha;
+  int all = compact_block<TPL, NW>(acc, t0, a.N, thr, 0, a.sel_idx + (long)bh * a.sel_stride,
+                                   a.sel_stride, lds_cnt, w, lane);
+  if (threadIdx.x == 0) {
+    a.sel_cnt[bh] = min(all, a.sel_stride);
+    if (all > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
+  }
+}
+
+// Long sequences / few heads: one wave per tile, 4 tiles per workgroup; scores and per-tile maxima
+// go to a buffer, and select_scores does the threshold pass.
+template <typename T, int CH>
+__global__ __launch_bounds__(256) void scan_tiles(ScanArgs a) {
+  constexpr int TPL = Elem<T>::TPL;
+  constexpr int TILE = IG_WAVE * TPL;
+  __shared__ float q_lds[256 + CH];
+  const int bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int tileno = blockIdx.x * 4 + w;
+  const bool active = tileno < a.nTiles;
+  const T *tile = static_cast<const T *>(a.slab) + ((long)bh * a.nTiles + (active ? tileno : 0)) * a.r * TILE;
+  const int padded = (a.r + CH - 1) / CH * CH;
+  typename Elem<T>::vec v[CH];
+  float acc[TPL];
+#pragma unroll
+  for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
+  stage_query(a, b, h, q_lds, padded);
+  if (active) load_block<T, CH>(tile, a.r, 0, lane, v);
+  __syncthreads();
+  if (!active) return;
+  fma_block<T, CH>(v, q_lds, 0, acc);
+  for (int j0 = CH; j0 < a.r; j0 += CH) {
+    load_block<T, CH>(tile, a.r, j0, lane, v);
+    fma_block<T, CH>(v, q_lds, j0, acc);
+  }
+  const int t0 = tileno * TILE;
+  float m = -INFINITY;
+#pragma unroll
+  for (int e = 0; e < TPL; ++e) {
+    int t = t0 + lane * TPL + e;
+    if (t < a.N) {
+      a.scores_out[(long)bh * a.N + t] = acc[e];
+      m = fmaxf(m, acc[e]);
+    }
+  }
+  m = wave_max(m);
+  if (lane == 0) a.tmax[(long)bh * a.nTiles + tileno] = m;
+}
+
+// Threshold + compaction from the score buffer: one workgroup of 16 waves per (b,h).
+__global__ __launch_bounds__(1024) void select_scores(ScanArgs a) {
+  constexpr int NW = 16, TPL = 4;
+  __shared__ float lds_max[NW];
+  __shared__ int lds_cnt[NW];
+  const int bh = blockIdx.x;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  float m = -INFINITY;
+  for (int k = threadIdx.x; k < a.nTiles; k += 1024) m = fmaxf(m, a.tmax[(long)bh * a.nTiles + k]);
+  m = wave_max(m);
+  if (lane == 0) lds_max[w] = m;
+  __syncthreads();
+  float mm = lds_max[0];
+#pragma unroll
+  for (int k = 1; k < NW; ++k) mm = fmaxf(mm, lds_max[k]);
+  const float thr = mm - a.alpha;
+  const float *s = a.scores_out + (long)bh * a.N;
+  int base = 0;
+  for (int c0 = 0; c0 < a.N; c0 += 1024 * TPL) {
+    const int t0 = c0 + w * 64 * TPL;
+    float sc[TPL];
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) {
+      int t = t0 + lane * TPL + e;
+      sc[e] = (t < a.N) ? s[t] : -INFINITY;
+    }
+    base += compact_block<TPL, NW>(sc, t0, a.N, thr, base, a.sel_idx + (long)bh * a.sel_stride,
+                                   a.sel_stride, lds_cnt, w, lane);
+  }
+  if (threadIdx.x == 0) {
+    a.sel_cnt[bh] = min(base, a.sel_stride);
+    if (base > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
+  }
+}
+
+// channel block size: the smallest multiple of 4 (<= 40) whose multiples cover r with least waste
+int pick_ch(int r, int cap) {
+  int best = 4, best_waste = 1 << 30;
+  for (int ch = cap; ch >= 4; ch -= 4) {
+    int blocks = (r + ch - 1) / ch;
+    int waste = blocks * ch - r + (blocks - 1) * 2;   // prefer fewer blocks on ties
+    if (waste < best_waste) { best_waste = waste; best = ch; }
+  }
+  return best;
+}
+
+template <typename T, int NW>
+int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) {
+  dim3 grid(BH), block(NW * 64);
+#define CASE(CHV)                                                              \
+  case CHV: {                                                                  \
+    auto k = scan_select_fused<T, CHV, NW>;                                    \
+    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                           \
+    return IG_OK;                                                              \
+  }
+  switch (ch) {
+    CASE(4) CASE(8) CASE(12) CASE(16) CASE(20)
+    default: break;
+  }
+  if constexpr (NW <= 8) {
+    switch (ch) {
+      CASE(24) CASE(28) CASE(32) CASE(36) CASE(40)
+      default: break;
+    }
+  }
+#undef CASE
+  return ig_fail(ctx, IG_ESHAPE, "scan: unsupported channel block %d", ch);
+}
+
+template <typename T>
+int launch_tiles(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) {
+  dim3 grid((a.nTiles + 3) / 4, BH), block(256);
+#define CASE(CHV)                                                              \
+  case CHV: {                                                                  \
+    auto k = scan_tiles<T, CHV>;                                               \
+    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                           \
+    break;                                                                     \
+  }
+  switch (ch) {
+    CASE(4) CASE(8) CASE(12) CASE(16) CASE(20) CASE(24) CASE(28) CASE(32) CASE(36) CASE(40)
+    default: return ig_fail(ctx, IG_ESHAPE, "scan: unsupported channel block %d", ch);
+  }
+#undef CASE
+  auto k2 = select_scores;
+  IG_LAUNCH(ctx, IG_K_SELECT, k2, dim3(BH), dim3(1024), s, a);
+  return IG_OK;
+}
+
+template <typename T>
+int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
+  const int BH = d->B * d->H;
+  const int nTiles = a.nTiles;
+  // Fused when a (b,h) fits one workgroup and there are enough (b,h) pairs to fill the chip;
+  // otherwise one wave per tile so that long sequences spread over all compute units.
+  const bool fused = nTiles <= 16 && (BH >= 128 || nTiles <= 4);
+  if (fused) {
+    if (nTiles <= 4) return launch_fused<T, 4>(ctx, a, BH, pick_ch(d->r, 40), s);
+    if (nTiles <= 8) return launch_fused<T, 8>(ctx, a, BH, pick_ch(d->r, 40), s);
+    return launch_fused<T, 16>(ctx, a, BH, pick_ch(d->r, 20), s);
+  }
+  size_t need_s = (size_t)BH * d->N * sizeof(float), need_m = (size_t)BH * nTiles * sizeof(float);
+  float *user_scores = a.scores_out;
+  if (!user_scores) {
+    int rc = ig_ensure(ctx, (void **)&ctx->scores, &ctx->scores_bytes, need_s);
+    if (rc) return rc;
+    a.scores_out = ctx->scores;
+  }
+  int rc = ig_ensure(ctx, (void **)&ctx->tmax, &ctx->tmax_bytes, need_m);
+  if (rc) return rc;
+  a.tmax = ctx->tmax;
+  return launch_tiles<T>(ctx, a, BH, pick_ch(d->r, 40), s);
+}
+
+}  // namespace
+
+int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const void *slab,
+                          int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
+                          float *scores_opt, hipStream_t s) {
+  ScanArgs a;
+  a.slab = slab;
+  a.qsrc = q.qsrc;
+  a.bias = q.bias;
+  a.sel_idx = sel_idx;
+  a.sel_cnt = sel_cnt;
+  a.scores_out = scores_opt;
+  a.tmax = nullptr;
+  a.status = ctx->status;
+  a.ks_stride = q.ks_stride;
+  a.b_stride = q.b_stride;
+  a.ks = q.ks;
+  a.H = d->H;
+  a.r = d->r;
+  a.N = d->N;
+  const int tile = ig_tile_tokens(d->dtype);
+  a.nTiles = (d->N_cap + tile - 1) / tile;
+  a.sel_stride = sel_stride;
+  a.scale = d->scale;
+  a.alpha = d->alpha;
+  if (d->r > 256) return ig_fail(ctx, IG_ESHAPE, "r = %d exceeds 256", d->r);
+  if (q.ks < 1 || q.ks > IG_KS_MAX) return ig_fail(ctx, IG_ESHAPE, "split-K %d out of range", q.ks);
+  return d->dtype == IG_F16 ? launch_scan<half_t>(ctx, d, a, s) : launch_scan<float>(ctx, d, a, s);
+}

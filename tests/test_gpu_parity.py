@@ -1,0 +1,226 @@
+"""GPU parity: the HIP path against the CPU oracle, element by element, through the C ABI.
+
+Bars: index lists bit-exact except tokens whose float32 oracle score lies within 1e-3 of the oracle
+threshold; gathered rows bit-exact; attention output within 2e-2 abs + 1e-2 rel for half-precision
+KV (1e-4 / 1e-4 for float32); partial queries and scores to float32 summation-order error.
+"""
+import numpy as np
+import pytest
+import torch
+
+import ig_workloads as wl
+from ig_case import make_case, run_oracle, compare_selection
+from oracle import ig_oracle as o
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import paper_2406_19707_amd as ig
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = ig.Context(0)
+    yield c
+    c.close()
+
+
+def check_case(ctx, c, alpha=None, host_pool=False, expect_fraction=None):
+    from ig_gpu import run_gpu
+    w = c.w
+    alpha = w.alpha if alpha is None else alpha
+    print(f"case {w.name} B{w.B} H{w.H} d{w.d} N{c.N}/{c.N_cap} r{c.r} {w.dtype} rope={w.rope} "
+          f"alpha={alpha} host_pool={host_pool}", flush=True)
+    ref = run_oracle(c, alpha)
+    got = run_gpu(ctx, c, alpha, host_pool=host_pool)
+    assert got["status"] == 0
+    BH = w.B * w.H
+    # partial queries and scores: float32 accumulation order only
+    qtol = 2e-5 * max(1.0, np.abs(ref.q_p).max()) * (8 if w.rope else 1)
+    assert np.abs(got["q_p"] - ref.q_p).max() <= qtol
+    stol = 1e-4 * max(1.0, np.abs(ref.s).max())
+    assert np.abs(got["scores"] - ref.s).max() <= stol
+    # index lists
+    slack = compare_selection(got["sel_idx"], got["sel_cnt"], ref, alpha)
+    frac = ref.sel_cnt.mean() / c.N
+    print(f"  selected fraction {frac:.4f} (min {ref.sel_cnt.min()}, max {ref.sel_cnt.max()}), "
+          f"in-band differences {slack}", flush=True)
+    if expect_fraction:
+        assert expect_fraction[0] <= frac <= expect_fraction[1]
+    # gathered rows: bit-exact copies of the rows the GPU's own lists name
+    Kt = c.Kt.reshape(BH, c.N_cap, w.d)
+    V = c.V.reshape(BH, c.N_cap, w.d)
+    for i in range(BH):
+        n = got["sel_cnt"][i]
+        rows = got["sel_idx"][i, :n]
+        assert np.array_equal(got["K_sel"][i, :n], Kt[i, rows])
+        assert np.array_equal(got["V_sel"][i, :n], V[i, rows])
+        assert not got["K_sel"][i, n:].any() and not got["V_sel"][i, n:].any()   # untouched
+    # attention: against the oracle on the lists the GPU produced (identical to the oracle's
+    # outside the band)
+    if slack == 0:
+        ref_out, ref_new = ref.out, ref.out_new
+    else:
+        Ks = o.gather(c.f32("Kt"), got["sel_idx"], got["sel_cnt"])
+        Vs = o.gather(c.f32("V"), got["sel_idx"], got["sel_cnt"])
+        ref_out = o.attend(c.f32("q"), Ks, Vs, got["sel_cnt"], c.scale)
+        ref_new = o.attend(c.f32("q"), Ks, Vs, got["sel_cnt"], c.scale, c.f32("k_new"), c.f32("v_new"))
+    atol, rtol = (1e-4, 1e-4) if w.dtype == "f32" else (2e-2, 1e-2)
+    for name, r_ in (("out", ref_out), ("out_new", ref_new), ("out_idx", ref_out)):
+        if got[name] is None:
+            continue
+        err = np.abs(got[name] - r_)
+        assert np.all(err <= atol + rtol * np.abs(r_)), (name, err.max())
+    return ref, got
+
+
+def test_cfg1_single_layer_f32(ctx):
+    # configs[0]: B1 H4 d64 N512 float32, r = 19, alpha 4; logit gain 8 puts the layer in the sparse regime
+    check_case(ctx, make_case(wl.WORKLOADS[1], gain=8.0), expect_fraction=(0.01, 0.5))
+
+
+def test_cfg1_literal_scale_selects_everything(ctx):
+    ref, got = check_case(ctx, make_case(wl.WORKLOADS[1], gain=1.0))
+    assert np.all(got["sel_cnt"] == 512)
+
+
+def test_all_columns_and_infinite_alpha_is_dense_attention(ctx):
+    w = wl.shrink(wl.WORKLOADS[1], B=2, N=300)
+    c = make_case(w, all_columns=True)
+    ref, got = check_case(ctx, c, alpha=float("inf"))
+    assert np.all(got["sel_cnt"] == 300)
+    q = torch.from_numpy(c.f32("q")).double().reshape(-1, 1, w.d)
+    K = torch.from_numpy(c.f32("Kt")).double().reshape(-1, c.N_cap, w.d)[:, :300]
+    V = torch.from_numpy(c.f32("V")).double().reshape(-1, c.N_cap, w.d)[:, :300]
+    dense = torch.nn.functional.scaled_dot_product_attention(q, K, V, scale=c.scale)[:, 0].numpy()
+    assert np.abs(got["out"] - dense).max() <= 1e-4
+
+
+@pytest.mark.parametrize("N,N_cap", [(2048, 2048), (1999, 2048), (700, 1024), (1, 8)])
+def test_cfg2_shape_f16_fused_four_waves(ctx, N, N_cap):
+    w = wl.shrink(wl.WORKLOADS[2], B=3, H=4, N=N, heavy_count=min(20, N))
+    check_case(ctx, make_case(w, gain=6.0, N_cap=N_cap))
+
+
+def test_cfg2_shape_with_bias_and_key_term_in_index(ctx):
+    w = wl.shrink(wl.WORKLOADS[2], B=2, H=4, N=1500)
+    check_case(ctx, make_case(w, gain=6.0, bias=True, use_keys_for_index=True))
+
+
+@pytest.mark.parametrize("N", [3000, 6000])
+def test_many_heads_fused_eight_and_sixteen_waves(ctx, N):
+    # B*H = 128 pairs: N = 3000 -> 6 tiles (8-wave workgroups), N = 6000 -> 12 tiles (16-wave)
+    w = wl.shrink(wl.WORKLOADS[2], B=8, H=16, d=32, N=N, heavy_count=30)
+    check_case(ctx, make_case(w, gain=6.0))
+
+
+def test_cfg3_shape_rope_f16(ctx):
+    w = wl.shrink(wl.WORKLOADS[3], B=2, H=4, N=4096)
+    check_case(ctx, make_case(w, gain=24.0))
+
+
+def test_cfg3_shape_rope_with_bias_ragged(ctx):
+    w = wl.shrink(wl.WORKLOADS[3], B=3, H=2, N=1234)
+    check_case(ctx, make_case(w, gain=16.0, bias=True, N_cap=1500))
+
+
+def test_cfg5_shape_long_context_tiled_path(ctx):
+    w = wl.shrink(wl.WORKLOADS[5], B=1, H=2, N=20000)
+    check_case(ctx, make_case(w, gain=6.0, N_cap=20480))
+
+
+def test_f32_long_sequence_tiled_path(ctx):
+    w = wl.shrink(wl.WORKLOADS[1], B=1, H=2, N=5000, heavy_count=16)
+    check_case(ctx, make_case(w, gain=8.0))
+
+
+@pytest.mark.parametrize("B", [20, 40])
+def test_projection_with_more_than_sixteen_sequences(ctx, B):
+    w = wl.shrink(wl.WORKLOADS[4], B=B, H=2, N=600, pool="hbm")
+    check_case(ctx, make_case(w, gain=6.0))
+
+
+def test_f16_model_dimension_not_multiple_of_32_uses_fma_projection(ctx):
+    w = wl.shrink(wl.WORKLOADS[2], B=2, H=3, d=8, N=900, ratio=0.5, n_cal=64, heavy_count=5)
+    check_case(ctx, make_case(w, gain=2.0))
+
+
+def test_host_pinned_pool_gather(ctx):
+    w = wl.shrink(wl.WORKLOADS[4], B=2, H=4, N=2048)
+    check_case(ctx, make_case(w, gain=6.0), host_pool=True)
+
+
+def test_list_longer_than_stride_is_clamped_and_flagged(ctx):
+    import paper_2406_19707_amd as ig
+    from ig_gpu import run_gpu
+    w = wl.shrink(wl.WORKLOADS[2], B=2, H=2, N=1024)
+    c = make_case(w, gain=1.0)                       # literal scale: every token selected
+    got = run_gpu(ctx, c, sel_stride=100)
+    assert got["status"] == ig.IG_ECAPACITY
+    assert np.all(got["sel_cnt"] == 100)
+    assert np.array_equal(got["sel_idx"], np.tile(np.arange(100, dtype=np.int32), (4, 1)))
+    assert ctx.ig_check_status() == ig.IG_OK          # the flag is cleared by the check
+
+
+def test_selection_is_deterministic(ctx):
+    from ig_gpu import run_gpu, Uploaded
+    w = wl.shrink(wl.WORKLOADS[2], B=4, H=8, N=2048)
+    c = make_case(w, gain=5.0)
+    up = Uploaded(ctx, c)
+    first = run_gpu(ctx, c, up=up)
+    for _ in range(19):
+        again = run_gpu(ctx, c, up=up)
+        assert np.array_equal(again["sel_cnt"], first["sel_cnt"])
+        assert np.array_equal(again["sel_idx"], first["sel_idx"])
+        assert np.array_equal(again["out"], first["out"])
+
+
+def test_empty_list_without_new_row_gives_zeros(ctx):
+    import paper_2406_19707_amd as ig
+    from ig_gpu import desc_of, dev
+    w = wl.shrink(wl.WORKLOADS[2], B=1, H=2, N=64)
+    c = make_case(w)
+    d = desc_of(c)
+    cnt = torch.zeros(2, dtype=torch.int32, device="cuda")
+    Ks = torch.ones((2, 64, w.d), dtype=torch.float16, device="cuda")
+    out = torch.full((1, 2, w.d), float("nan"), dtype=torch.float16, device="cuda")
+    ctx.ig_sparse_attention(d, dev(c.q), Ks, Ks, cnt, 64, None, None, out)
+    assert torch.all(out == 0)
+    kn, vn = dev(c.k_new), dev(c.v_new)
+    ctx.ig_sparse_attention(d, dev(c.q), Ks, Ks, cnt, 64, kn, vn, out)
+    assert torch.allclose(out, vn, atol=1e-3)         # only the new row: weight 1
+
+
+def test_error_paths(ctx):
+    import ctypes
+    import paper_2406_19707_amd as ig
+    w = wl.shrink(wl.WORKLOADS[2], B=1, H=2, N=64)
+    buf = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    p = buf.data_ptr()
+
+    def spec(desc, **kw):
+        a = dict(x=p, wq=p, slab=p, sel_idx=p, stride=64, cnt=p)
+        a.update(kw)
+        return ctx.call("ig_speculate", ctypes.byref(desc), a["x"], a["wq"], None, None, None,
+                        a["slab"], a["sel_idx"], a["stride"], a["cnt"], None, 0)
+
+    good = dict(B=1, H=2, d=128, r=38, N=64)
+    assert spec(ig.IgDesc(**good, alpha=-1.0)) == ig.IG_EINVAL
+    assert "alpha" in ctx.last_error()
+    assert spec(ig.IgDesc(**good, alpha=float("nan"))) == ig.IG_EINVAL
+    assert spec(ig.IgDesc(B=1, H=2, d=128, r=200, N=64)) == ig.IG_ESHAPE
+    assert spec(ig.IgDesc(B=1, H=2, d=128, r=38, N=0)) == ig.IG_ESHAPE
+    assert spec(ig.IgDesc(B=1, H=2, d=128, r=38, N=64, N_cap=32)) == ig.IG_ESHAPE
+    assert spec(ig.IgDesc(**good, dtype=9)) == ig.IG_EDTYPE
+    assert spec(ig.IgDesc(B=1, H=2, d=4, r=2, N=64)) == ig.IG_ESHAPE      # 8-byte rows
+    assert spec(ig.IgDesc(**good), x=None) == ig.IG_EINVAL
+    assert spec(ig.IgDesc(**good), stride=0) == ig.IG_ESHAPE
+    assert spec(ig.IgDesc(**good, rope=1)) == ig.IG_EINVAL                 # rope without A_p / pos
+    # a pageable host buffer passed as a pinned pool is refused
+    d = ig.IgDesc(**good)
+    host = np.zeros(1 << 16, np.uint8)
+    rc = ctx.call("ig_gather_kv", ctypes.byref(d), host.ctypes.data, host.ctypes.data,
+                  ig.IG_MEM_HOST_PINNED, p, 64, p, p, p, 0)
+    assert rc == ig.IG_EINVAL and "pinned" in ctx.last_error()
+    rc = ctx.call("ig_gather_kv", ctypes.byref(d), p, p, 7, p, 64, p, p, p, 0)
+    assert rc == ig.IG_EINVAL
+    torch.cuda.synchronize()
