@@ -40,6 +40,8 @@ class Workload:
     rope: bool = False       # rotary embedding between projection and skewing
     pool: str = "hbm"        # "hbm" or "host": where the full K/V pool lives
     n_cal: int = 512         # rows of the calibration input
+    gain: float = 1.0        # logit gain of the calibrated variant (scale = gain / sqrt(d)); 1 = literal
+    layers: int = 32         # decoder layers of the model the shape is taken from
 
     @property
     def D(self) -> int:
@@ -54,7 +56,8 @@ WORKLOADS = {
     1: Workload(1, "cfg1 single layer, CPU-checkable", B=1, H=4, d=64, N=512, dtype="f32",
                 ratio=0.3, alpha=4.0, decay=0.9, heavy_count=8, heavy_scale=4.0),
     2: Workload(2, "cfg2 OPT-6.7B-shaped decode layer", B=8, H=32, d=128, N=2048, dtype="f16",
-                ratio=0.3, alpha=4.0, decay=0.95, heavy_count=20, heavy_scale=3.0),
+                ratio=0.3, alpha=4.0, decay=0.95, heavy_count=20, heavy_scale=3.0, gain=32.0,
+                layers=32),
     3: Workload(3, "cfg3 Llama-2-7B-shaped decode layer", B=16, H=32, d=128, N=4096, dtype="f16",
                 ratio=0.3, alpha=5.0, decay=0.95, heavy_count=40, heavy_scale=3.0, rope=True),
     4: Workload(4, "cfg4 OPT-30B-shaped decode layer, host KV pool", B=20, H=56, d=128, N=2048,

@@ -36,6 +36,15 @@ int ig_ensure(ig_ctx *ctx, void **p, size_t *have, size_t need) {
   return IG_OK;
 }
 
+int ig_ensure_zeroed(ig_ctx *ctx, void **p, size_t *have, size_t need) {
+  if (*have >= need && *p) return IG_OK;
+  int rc = ig_ensure(ctx, p, have, need);
+  if (rc) return rc;
+  IG_HIP(ctx, hipMemset(*p, 0, *have));
+  IG_HIP(ctx, hipDeviceSynchronize());
+  return IG_OK;
+}
+
 void ig_prof_events(ig_ctx *ctx, int which, hipEvent_t *e0, hipEvent_t *e1) {
   hipEvent_t ev[2];
   for (int i = 0; i < 2; ++i) {
@@ -109,6 +118,12 @@ int reserve_for(ig_ctx *ctx, const ig_desc *d, bool scores) {
                    (size_t)d->B * d->H * d->N * sizeof(float));
     if (rc) return rc;
     rc = ig_ensure(ctx, (void **)&ctx->tmax, &ctx->tmax_bytes, (size_t)d->B * d->H * nTiles * sizeof(float));
+    if (rc) return rc;
+    rc = ig_ensure(ctx, (void **)&ctx->attn_part, &ctx->attn_part_bytes,
+                   (size_t)d->B * d->H * IG_SLICE_MAX * (d->d + 2) * sizeof(float));
+    if (rc) return rc;
+    rc = ig_ensure_zeroed(ctx, (void **)&ctx->attn_cnt, &ctx->attn_cnt_bytes,
+                          (size_t)d->B * d->H * sizeof(int32_t));
   }
   return rc;
 }
@@ -126,7 +141,9 @@ int ig_create(int device, ig_ctx **out) {
   if (!ctx) return IG_ENOMEM;
   ctx->device = device;
   ctx->err[0] = 0;
-  ctx->part = ctx->qp = ctx->scores = ctx->tmax = nullptr;
+  ctx->part = ctx->qp = ctx->scores = ctx->tmax = ctx->attn_part = nullptr;
+  ctx->attn_cnt = nullptr;
+  ctx->attn_part_bytes = ctx->attn_cnt_bytes = 0;
   ctx->part_bytes = ctx->qp_bytes = ctx->scores_bytes = ctx->tmax_bytes = 0;
   ctx->status = nullptr;
   ctx->profiling = false;
@@ -154,6 +171,8 @@ int ig_destroy(ig_ctx *ctx) {
   if (ctx->qp) (void)hipFree(ctx->qp);
   if (ctx->scores) (void)hipFree(ctx->scores);
   if (ctx->tmax) (void)hipFree(ctx->tmax);
+  if (ctx->attn_part) (void)hipFree(ctx->attn_part);
+  if (ctx->attn_cnt) (void)hipFree(ctx->attn_cnt);
   if (ctx->status) (void)hipFree(ctx->status);
   delete ctx;
   return IG_OK;

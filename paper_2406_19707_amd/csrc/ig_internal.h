@@ -26,6 +26,7 @@ template <> struct Elem<float> {
 constexpr int IG_WAVE = 64;
 constexpr int IG_KS_MAX = 16;     // split-K partial sums a consumer adds up at most
 constexpr int IG_STATUS_CAPACITY = 1;
+constexpr int IG_SLICE_MAX = 16;   // slices a selected-token list is cut into at most (gather, attention)
 
 // Slab geometry: tokens are grouped in tiles of 64 lanes x TPL tokens; inside a tile the r kept
 // channels are planes of TILE contiguous tokens:  slab[(bh*nTiles + tile)*r*TILE + j*TILE + t%TILE].
@@ -59,6 +60,8 @@ struct ig_ctx {
   float *qp;        size_t qp_bytes;      // finalised partial queries [B,H,r]
   float *scores;    size_t scores_bytes;  // long-sequence path: s [B*H, N]
   float *tmax;      size_t tmax_bytes;    // long-sequence path: per-tile maxima [B*H, nTiles]
+  float *attn_part; size_t attn_part_bytes;  // attention: per-slice softmax states [B*H][16][d+2]
+  int32_t *attn_cnt; size_t attn_cnt_bytes;  // attention: per-(b,h) arrival counters, zero between calls
   int32_t *status;                        // device status word (sticky flags)
   bool profiling;
   std::vector<ProfRec> recs;
@@ -70,6 +73,7 @@ struct ig_ctx {
 int ig_fail(ig_ctx *ctx, int code, const char *fmt, ...);
 int ig_hip_fail(ig_ctx *ctx, hipError_t e, const char *what);
 int ig_ensure(ig_ctx *ctx, void **p, size_t *have, size_t need);
+int ig_ensure_zeroed(ig_ctx *ctx, void **p, size_t *have, size_t need);
 void ig_prof_events(ig_ctx *ctx, int which, hipEvent_t *e0, hipEvent_t *e1);
 
 #define IG_HIP(ctx, call)                                        \
@@ -124,22 +128,34 @@ int ig_launch_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
 int ig_launch_copy(ig_ctx *ctx, const void *src, void *dst, size_t bytes, hipStream_t s);
 
 // ---- wave helpers -------------------------------------------------------------------------------
+// Cross-lane moves inside a 16-lane row through DPP (no LDS crossbar traffic).
+template <int CTRL> __device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+constexpr int DPP_QUAD_1032 = 0xB1, DPP_QUAD_2301 = 0x4E, DPP_ROW_HALF_MIRROR = 0x141, DPP_ROW_MIRROR = 0x140;
+
+// maximum over the 64 lanes, returned in every lane
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  v = fmaxf(v, dpp_move<DPP_QUAD_1032>(v));
+  v = fmaxf(v, dpp_move<DPP_QUAD_2301>(v));
+  v = fmaxf(v, dpp_move<DPP_ROW_HALF_MIRROR>(v));
+  v = fmaxf(v, dpp_move<DPP_ROW_MIRROR>(v));        // every lane of a row now holds the row's maximum
+  const int iv = __float_as_int(v);
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(iv, 0));
+  const float r1 = __int_as_float(__builtin_amdgcn_readlane(iv, 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(iv, 32));
+  const float r3 = __int_as_float(__builtin_amdgcn_readlane(iv, 48));
+  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+// sum over the lanes of a 16-lane row, returned in every lane of the row
+__device__ __forceinline__ float row16_sum(float v) {
+  v += dpp_move<DPP_QUAD_1032>(v);
+  v += dpp_move<DPP_QUAD_2301>(v);
+  v += dpp_move<DPP_ROW_HALF_MIRROR>(v);
+  v += dpp_move<DPP_ROW_MIRROR>(v);
   return v;
 }
-__device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
-}
-// inclusive prefix sum over the 64 lanes
-__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    int u = __shfl_up(v, o, 64);
-    if (lane >= o) v += u;
-  }
-  return v;
+// number of lanes below this one whose predicate is set, and the wave's total
+__device__ __forceinline__ int lanes_below(unsigned long long ballot) {
+  return __builtin_amdgcn_mbcnt_hi((unsigned)(ballot >> 32), __builtin_amdgcn_mbcnt_lo((unsigned)ballot, 0));
 }

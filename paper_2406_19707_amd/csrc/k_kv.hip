@@ -43,41 +43,101 @@ __global__ __launch_bounds__(256) void slab_build(const T *__restrict__ Kpool,
   }
 }
 
+// ---- work split shared by gather and attention --------------------------------------------------
+// Selected-token lists are very uneven (a few heads keep a thousand rows, most a few dozen), and
+// one compute unit moves well under 100 GB/s, so a list is cut into up to gridDim.y slices of at
+// most SLICE_ROWS rows where possible: slices = min(gridDim.y, ceil(rows / SLICE_ROWS)), slice s
+// covering rows [rows*s/slices, rows*(s+1)/slices).  Every workgroup derives this from the
+// device-side count, so the host never reads the counts; surplus workgroups leave at once.
+//
+// Workgroups are handed to the 8 XCDs round-robin by linear id, and an XCD reaches only about an
+// eighth of the HBM bandwidth, so the work has to be even per XCD, not just per compute unit:
+// heavy lists cluster by head (and H is normally a multiple of 8), so mapping (b,h) -> id = b*H+h
+// would send every slice of the heavy heads to the same XCD.  work_item() therefore decodes the
+// linear id as slice = id / BH, t = id % BH, b = t / H, h = (t % H - b - 5*slice) mod H, which puts
+// (b, h, slice) on XCD (h + b + 5*slice) % 8: the slices of one list, the sequences of one head and
+// the heads of one sequence are each spread over all XCDs.
+constexpr int SLICE_ROWS = 128;
+constexpr int SLICE_MAX = IG_SLICE_MAX;
+__device__ __forceinline__ void work_item(int H, int BH, int *bh, int *slice) {
+  const int id = blockIdx.x;
+  const int s = id / BH, t = id - s * BH;
+  const int b = t / H;
+  int h = (t - b * H - b - 5 * s) % H;
+  if (h < 0) h += H;
+  *bh = b * H + h;
+  *slice = s;
+}
+__device__ __forceinline__ bool slice_range(int rows, int s, int max_slices, int *row0, int *row1, int *slices) {
+  int n = (rows + SLICE_ROWS - 1) / SLICE_ROWS;
+  n = max(1, min(n, max_slices));
+  *slices = n;
+  if (s >= n) return false;
+  *row0 = (int)((long)rows * s / n);
+  *row1 = (int)((long)rows * (s + 1) / n);
+  return true;
+}
+
 // ---- gather -------------------------------------------------------------------------------------
-// Row copies in 16-byte units; U units per row.  grid (chunks of ROWS rows, B*H); workgroups whose
-// first row lies beyond the list's length leave at once, so the grid can be sized for the worst
-// case without the host knowing the counts.
-constexpr int GATHER_ROWS = 64;
-__global__ __launch_bounds__(256) void gather_rows(const u128 *__restrict__ Kpool,
-                                                   const u128 *__restrict__ Vpool,
-                                                   const int32_t *__restrict__ sel_idx,
-                                                   const int32_t *__restrict__ sel_cnt,
-                                                   u128 *__restrict__ K_sel, u128 *__restrict__ V_sel,
-                                                   int N_cap, int stride, int U) {
-  const int bh = blockIdx.y;
+// Row copies in 16-byte units, U units per row; grid B*H*SLICE_MAX (see work_item).  A thread's copies are
+// issued in batches of GATHER_BATCH, so that index loads, then K and V row loads, are in flight
+// together (this is also what keeps enough PCIe reads outstanding when the pool is pinned host
+// memory).
+constexpr int GATHER_BATCH = 8;
+__global__ __launch_bounds__(256) void gather_rows(
+    const u128 *__restrict__ Kpool, const u128 *__restrict__ Vpool, const int32_t *__restrict__ sel_idx,
+    const int32_t *__restrict__ sel_cnt, u128 *__restrict__ K_sel, u128 *__restrict__ V_sel, int N_cap,
+    int stride, int U, int H, int BH) {
+  int bh, slice;
+  work_item(H, BH, &bh, &slice);
   const int cnt = min(sel_cnt[bh], stride);
-  const int row0 = blockIdx.x * GATHER_ROWS;
-  if (row0 >= cnt) return;
-  const int rows = min(GATHER_ROWS, cnt - row0);
+  int row0, row1, slices;
+  if (!slice_range(cnt, slice, SLICE_MAX, &row0, &row1, &slices) || row1 <= row0) return;
   const int32_t *list = sel_idx + (long)bh * stride + row0;
   const long src0 = (long)bh * N_cap * U, dst0 = ((long)bh * stride + row0) * U;
-  const int total = rows * U;
-#pragma unroll 4
-  for (int u = threadIdx.x; u < total; u += 256) {
-    int rr = u / U, c = u - rr * U;
-    long src = src0 + (long)list[rr] * U + c;
-    u128 kv = Kpool[src];
-    u128 vv = Vpool[src];
-    K_sel[dst0 + u] = kv;
-    V_sel[dst0 + u] = vv;
+  const int total = (row1 - row0) * U;
+  // Branch-free batches (so that all loads of a batch are issued before the first store): a unit
+  // past the end is clamped to the last unit, which is then copied more than once with identical
+  // bytes.
+  for (int u0 = threadIdx.x; u0 < total; u0 += 256 * GATHER_BATCH) {
+    u128 kv[GATHER_BATCH], vv[GATHER_BATCH];
+    long src[GATHER_BATCH];
+#pragma unroll
+    for (int i = 0; i < GATHER_BATCH; ++i) {
+      const int u = min(u0 + 256 * i, total - 1);
+      const int rr = u / U, c = u - rr * U;
+      src[i] = src0 + (long)list[rr] * U + c;
+    }
+#pragma unroll
+    for (int i = 0; i < GATHER_BATCH; ++i) {
+      kv[i] = Kpool[src[i]];
+      vv[i] = Vpool[src[i]];
+    }
+#pragma unroll
+    for (int i = 0; i < GATHER_BATCH; ++i) {
+      const int u = min(u0 + 256 * i, total - 1);
+      K_sel[dst0 + u] = kv[i];
+      V_sel[dst0 + u] = vv[i];
+    }
   }
 }
 
 // ---- attention ----------------------------------------------------------------------------------
-// One workgroup (4 waves) per (b,h).  A row of d elements is covered by LPR = d*sizeof(T)/16 lanes,
-// 16 bytes each; a wave handles 64/LPR rows per step.  Every lane group keeps an online-softmax
-// state (running max, normaliser, weighted sum for its 16-byte slice of V); states are merged
-// across lane groups with shuffles and across waves through LDS.
+// grid B*H*SLICE_MAX (see work_item), 4 waves per workgroup, one slice of the (b,h) list each.  A row of d
+// elements is covered by LPR = d*sizeof(T)/16 lanes, 16 bytes each, so a wave step covers 64/LPR
+// rows; waves interleave over the rows, and steps are issued in batches of ATT_BATCH so that a
+// batch's K and V loads are all in flight before the first is used.  Every lane group keeps an
+// online-softmax state (running max, normaliser, weighted sum for its 16-byte slice of V); states
+// are merged across lane groups with shuffles and across waves through LDS, in a fixed order.
+//
+// A list with one slice writes its output directly.  With several slices each workgroup publishes
+// its state (max, normaliser, d sums) with device-coherent stores and bumps a per-(b,h) counter;
+// the workgroup that arrives last reads all states with device-coherent loads and merges them in
+// slice order, so the result does not depend on arrival order.  Coherent stores and loads are used
+// instead of a device-wide fence, which would write back and invalidate the whole L2 per
+// workgroup.  The counter is left at zero for the next call.
+constexpr int ATT_BATCH = 8;
+
 template <typename T> __device__ __forceinline__ void to_float(const u128 &raw, float (&f)[Elem<T>::TPL]);
 template <> __device__ __forceinline__ void to_float<half_t>(const u128 &raw, float (&f)[8]) {
   const half8 h = *reinterpret_cast<const half8 *>(&raw);
@@ -90,41 +150,34 @@ template <> __device__ __forceinline__ void to_float<float>(const u128 &raw, flo
   for (int e = 0; e < 4; ++e) f[e] = v[e];
 }
 
-template <int TPL> struct SoftState {
-  float m, z;
-  float acc[TPL];
-};
-
-template <int TPL>
-__device__ __forceinline__ void merge_state(SoftState<TPL> &a, float m2, float z2, const float (&acc2)[TPL]) {
-  float M = fmaxf(a.m, m2);
-  float f1 = (a.m == -INFINITY) ? 0.f : __expf(a.m - M);
-  float f2 = (m2 == -INFINITY) ? 0.f : __expf(m2 - M);
-  a.z = a.z * f1 + z2 * f2;
-#pragma unroll
-  for (int e = 0; e < TPL; ++e) a.acc[e] = a.acc[e] * f1 + acc2[e] * f2;
-  a.m = M;
+__device__ __forceinline__ float exp_or_zero(float m, float M) { return (m == -INFINITY) ? 0.f : __expf(m - M); }
+__device__ __forceinline__ void coherent_store(float *p, float v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float coherent_load(const float *p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <typename T, bool INDEXED>
-__global__ __launch_bounds__(256) void sparse_attention(const T *__restrict__ q,
-                                                        const u128 *__restrict__ K,
-                                                        const u128 *__restrict__ V,
-                                                        const int32_t *__restrict__ sel_idx,
-                                                        const int32_t *__restrict__ sel_cnt,
-                                                        int stride, int kv_rows, int LPR,
-                                                        const T *__restrict__ k_new,
-                                                        const T *__restrict__ v_new,
-                                                        T *__restrict__ out, float scale, int d) {
+__global__ __launch_bounds__(256) void sparse_attention(
+    const T *__restrict__ q, const u128 *__restrict__ K, const u128 *__restrict__ V,
+    const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt, int stride, int kv_rows,
+    int LPR, const T *__restrict__ k_new, const T *__restrict__ v_new, T *__restrict__ out, float scale,
+    int d, float *part, int32_t *counters, int H, int BH) {
   constexpr int TPL = Elem<T>::TPL;
   __shared__ float sm[4], sz[4];
   __shared__ float sacc[4][512];
-  const int bh = blockIdx.x;
+  __shared__ int s_last;
+  constexpr int max_slices = SLICE_MAX;
+  int bh, slice;
+  work_item(H, BH, &bh, &slice);
+  const int n = min(sel_cnt[bh], stride);
+  const int rows = n + (k_new ? 1 : 0);
+  int row0 = 0, row1 = 0, slices = 1;
+  if (!slice_range(rows, slice, max_slices, &row0, &row1, &slices)) return;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int RPW = 64 / LPR;            // rows per wave step
   const int sub = lane / LPR, li = lane % LPR;
-  const int n = min(sel_cnt[bh], stride);
-  const int rows = n + (k_new ? 1 : 0);
   float qf[TPL];
   {
     u128 raw = *reinterpret_cast<const u128 *>(q + (long)bh * d + li * TPL);
@@ -132,63 +185,150 @@ __global__ __launch_bounds__(256) void sparse_attention(const T *__restrict__ q,
 #pragma unroll
     for (int e = 0; e < TPL; ++e) qf[e] *= scale;
   }
-  SoftState<TPL> st;
-  st.m = -INFINITY;
-  st.z = 0.f;
+  float m = -INFINITY, z = 0.f, acc[TPL];
 #pragma unroll
-  for (int e = 0; e < TPL; ++e) st.acc[e] = 0.f;
+  for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
   const long base = (long)bh * kv_rows * LPR;
   const int32_t *list = sel_idx + (long)bh * stride;
-#pragma unroll 2
-  for (int j = w * RPW + sub; j < rows; j += 4 * RPW) {
-    u128 kr, vr;
-    if (j < n) {
-      long row = INDEXED ? (long)list[j] : (long)j;
-      kr = K[base + row * LPR + li];
-      vr = V[base + row * LPR + li];
-    } else {
-      kr = *reinterpret_cast<const u128 *>(k_new + (long)bh * d + li * TPL);
-      vr = *reinterpret_cast<const u128 *>(v_new + (long)bh * d + li * TPL);
+  const int rows_per_batch = 4 * RPW * ATT_BATCH;
+  for (int r0 = row0; r0 < row1; r0 += rows_per_batch) {
+    // Branch-free loads, so that the whole batch is in flight at once: a step past the slice's end
+    // re-reads the slice's last row and its logit is masked below; the new-token row is a pointer
+    // select, not a branch.
+    u128 kr[ATT_BATCH], vr[ATT_BATCH];
+    bool valid[ATT_BATCH];
+    long rowoff[ATT_BATCH];
+#pragma unroll
+    for (int i = 0; i < ATT_BATCH; ++i) {
+      // step i of wave w covers rows r0 + (i*4 + w)*RPW + sub
+      const int j = r0 + (i * 4 + w) * RPW + sub;
+      valid[i] = j < row1;
+      const int jc = min(j, row1 - 1);
+      const int jl = min(jc, max(n - 1, 0));
+      rowoff[i] = INDEXED ? (long)list[jl] : (long)jl;
     }
-    float kf[TPL], vf[TPL];
-    to_float<T>(kr, kf);
-    to_float<T>(vr, vf);
-    float l = 0.f;
 #pragma unroll
-    for (int e = 0; e < TPL; ++e) l = fmaf(qf[e], kf[e], l);
-    for (int o = 1; o < LPR; o <<= 1) l += __shfl_xor(l, o, 64);
-    float M = fmaxf(st.m, l);
-    float f1 = (st.m == -INFINITY) ? 0.f : __expf(st.m - M);
-    float p = __expf(l - M);
-    st.z = st.z * f1 + p;
+    for (int i = 0; i < ATT_BATCH; ++i) {
+      const int j = r0 + (i * 4 + w) * RPW + sub;
+      const bool cached = min(j, row1 - 1) < n;
+      const u128 *kp = cached ? K + base + rowoff[i] * LPR + li : reinterpret_cast<const u128 *>(k_new + (long)bh * d) + li;
+      const u128 *vp = cached ? V + base + rowoff[i] * LPR + li : reinterpret_cast<const u128 *>(v_new + (long)bh * d) + li;
+      kr[i] = *kp;
+      vr[i] = *vp;
+    }
+    float l[ATT_BATCH];
+    float bm = m;
 #pragma unroll
-    for (int e = 0; e < TPL; ++e) st.acc[e] = st.acc[e] * f1 + p * vf[e];
-    st.m = M;
+    for (int i = 0; i < ATT_BATCH; ++i) {
+      float kf[TPL];
+      to_float<T>(kr[i], kf);
+      float t = 0.f;
+#pragma unroll
+      for (int e = 0; e < TPL; ++e) t = fmaf(qf[e], kf[e], t);
+      if (LPR == 16) {
+        t = row16_sum(t);
+      } else {
+        for (int o = 1; o < LPR; o <<= 1) t += __shfl_xor(t, o, 64);
+      }
+      l[i] = valid[i] ? t : -INFINITY;
+      bm = fmaxf(bm, l[i]);
+    }
+    if (bm != -INFINITY) {
+      const float f = exp_or_zero(m, bm);
+      z *= f;
+#pragma unroll
+      for (int e = 0; e < TPL; ++e) acc[e] *= f;
+#pragma unroll
+      for (int i = 0; i < ATT_BATCH; ++i) {
+        const float p = exp_or_zero(l[i], bm);
+        float vf[TPL];
+        to_float<T>(vr[i], vf);
+        z += p;
+#pragma unroll
+        for (int e = 0; e < TPL; ++e) acc[e] = fmaf(p, vf[e], acc[e]);
+      }
+      m = bm;
+    }
   }
-  // merge lane groups of the wave (lanes with equal li hold the same slice of V)
+  // merge the lane groups of the wave (lanes with equal li hold the same slice of V)
   for (int o = LPR; o < 64; o <<= 1) {
-    float m2 = __shfl_xor(st.m, o, 64), z2 = __shfl_xor(st.z, o, 64);
-    float a2[TPL];
+    const float m2 = __shfl_xor(m, o, 64), z2 = __shfl_xor(z, o, 64);
+    const float M = fmaxf(m, m2);
+    const float f1 = exp_or_zero(m, M), f2 = exp_or_zero(m2, M);
+    z = z * f1 + z2 * f2;
 #pragma unroll
-    for (int e = 0; e < TPL; ++e) a2[e] = __shfl_xor(st.acc[e], o, 64);
-    merge_state<TPL>(st, m2, z2, a2);
+    for (int e = 0; e < TPL; ++e) acc[e] = acc[e] * f1 + __shfl_xor(acc[e], o, 64) * f2;
+    m = M;
   }
   if (lane < LPR) {
-    if (lane == 0) { sm[w] = st.m; sz[w] = st.z; }
+    if (lane == 0) { sm[w] = m; sz[w] = z; }
 #pragma unroll
-    for (int e = 0; e < TPL; ++e) sacc[w][lane * TPL + e] = st.acc[e];
+    for (int e = 0; e < TPL; ++e) sacc[w][lane * TPL + e] = acc[e];
   }
   __syncthreads();
-  for (int c = threadIdx.x; c < d; c += 256) {
-    float M = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
-    float z = 0.f, a = 0.f;
+  // merge the four waves: thread c owns output channel c
+  const float M = fmaxf(fmaxf(sm[0], sm[1]), fmaxf(sm[2], sm[3]));
+  float zc = 0.f;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      float f = (sm[k] == -INFINITY) ? 0.f : __expf(sm[k] - M);
-      z += sz[k] * f;
-      a += sacc[k][c] * f;
+  for (int k = 0; k < 4; ++k) zc += sz[k] * exp_or_zero(sm[k], M);
+  if (slices == 1) {
+    for (int c = threadIdx.x; c < d; c += 256) {
+      float a = 0.f;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) a += sacc[k][c] * exp_or_zero(sm[k], M);
+      out[(long)bh * d + c] = (T)(zc > 0.f ? a / zc : 0.f);
     }
-    out[(long)bh * d + c] = (T)(z > 0.f ? a / z : 0.f);
+    return;
+  }
+  // several slices: publish this slice's state; the last arrival merges all of them
+  float *mine = part + ((long)bh * max_slices + slice) * (d + 2);
+  for (int c = threadIdx.x; c < d; c += 256) {
+    float a = 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) a += sacc[k][c] * exp_or_zero(sm[k], M);
+    coherent_store(mine + 2 + c, a);
+  }
+  if (threadIdx.x == 0) {
+    coherent_store(mine, M);
+    coherent_store(mine + 1, zc);
+  }
+  // wait until this wave's coherent stores have been acknowledged, then meet the other waves
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int prev = __hip_atomic_fetch_add(&counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (prev == slices - 1);
+    if (s_last) __hip_atomic_store(&counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  if (!s_last) return;
+  // every thread issues all of its loads (independent, predicated on the slice count) before using any
+  const float *all = part + (long)bh * max_slices * (d + 2);
+  for (int c = threadIdx.x; c < d; c += 256) {
+    float mk[SLICE_MAX], zk[SLICE_MAX], ak[SLICE_MAX];
+#pragma unroll
+    for (int k = 0; k < SLICE_MAX; ++k) {
+      mk[k] = -INFINITY;
+      zk[k] = 0.f;
+      ak[k] = 0.f;
+      if (k < slices) {
+        const float *pk = all + (long)k * (d + 2);
+        mk[k] = coherent_load(pk);
+        zk[k] = coherent_load(pk + 1);
+        ak[k] = coherent_load(pk + 2 + c);
+      }
+    }
+    float MM = -INFINITY;
+#pragma unroll
+    for (int k = 0; k < SLICE_MAX; ++k) MM = fmaxf(MM, mk[k]);
+    float zz = 0.f, a = 0.f;
+#pragma unroll
+    for (int k = 0; k < SLICE_MAX; ++k) {
+      const float f = exp_or_zero(mk[k], MM);
+      zz += zk[k] * f;
+      a += ak[k] * f;
+    }
+    out[(long)bh * d + c] = (T)(zz > 0.f ? a / zz : 0.f);
   }
 }
 
@@ -223,10 +363,11 @@ int ig_launch_gather(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const voi
                      const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt,
                      void *K_sel, void *V_sel, hipStream_t s) {
   const int U = d->d * ig_elem_bytes(d->dtype) / 16;
-  dim3 grid((sel_stride + GATHER_ROWS - 1) / GATHER_ROWS, d->B * d->H), block(256);
+  const int BH = d->B * d->H;
+  dim3 grid(BH * SLICE_MAX), block(256);
   auto k = gather_rows;
   IG_LAUNCH(ctx, IG_K_GATHER, k, grid, block, s, (const u128 *)Kpool, (const u128 *)Vpool, sel_idx,
-            sel_cnt, (u128 *)K_sel, (u128 *)V_sel, (int)d->N_cap, (int)sel_stride, U);
+            sel_cnt, (u128 *)K_sel, (u128 *)V_sel, (int)d->N_cap, (int)sel_stride, U, (int)d->H, BH);
   return IG_OK;
 }
 
@@ -236,17 +377,23 @@ static int launch_attention_t(ig_ctx *ctx, const ig_desc *d, const void *q, cons
                               const int32_t *sel_cnt, int kv_rows, const void *k_new,
                               const void *v_new, void *out, hipStream_t s) {
   const int LPR = d->d * (int)sizeof(T) / 16;
-  dim3 grid(d->B * d->H), block(256);
+  const int BH = d->B * d->H;
+  int rc = ig_ensure(ctx, (void **)&ctx->attn_part, &ctx->attn_part_bytes,
+                     (size_t)BH * SLICE_MAX * (d->d + 2) * sizeof(float));
+  if (rc) return rc;
+  if ((rc = ig_ensure_zeroed(ctx, (void **)&ctx->attn_cnt, &ctx->attn_cnt_bytes, (size_t)BH * sizeof(int32_t))))
+    return rc;
+  dim3 grid(BH * SLICE_MAX), block(256);
   if (sel_idx) {
     auto k = sparse_attention<T, true>;
     IG_LAUNCH(ctx, IG_K_ATTENTION, k, grid, block, s, (const T *)q, (const u128 *)K, (const u128 *)V,
               sel_idx, sel_cnt, (int)sel_stride, kv_rows, LPR, (const T *)k_new, (const T *)v_new,
-              (T *)out, (float)d->scale, (int)d->d);
+              (T *)out, (float)d->scale, (int)d->d, ctx->attn_part, ctx->attn_cnt, (int)d->H, BH);
   } else {
     auto k = sparse_attention<T, false>;
     IG_LAUNCH(ctx, IG_K_ATTENTION, k, grid, block, s, (const T *)q, (const u128 *)K, (const u128 *)V,
               sel_idx, sel_cnt, (int)sel_stride, kv_rows, LPR, (const T *)k_new, (const T *)v_new,
-              (T *)out, (float)d->scale, (int)d->d);
+              (T *)out, (float)d->scale, (int)d->d, ctx->attn_part, ctx->attn_cnt, (int)d->H, BH);
   }
   return IG_OK;
 }

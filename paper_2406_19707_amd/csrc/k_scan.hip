@@ -32,8 +32,9 @@ struct ScanArgs {
 // Partial query of (b,h) into LDS, scaled, zero-padded to `padded` entries.
 // value(j) = scale * (bias[h*r+j] + sum_s qsrc[s*ks_stride + b*b_stride + h*r + j]); the partial
 // sums are loaded up front (independent loads) and added in a fixed order.
-__device__ __forceinline__ void stage_query(const ScanArgs &a, int b, int h, float *q_lds, int padded) {
-  for (int j = threadIdx.x; j < padded; j += blockDim.x) {
+__device__ __forceinline__ void stage_query(const ScanArgs &a, int b, int h, float *q_lds, int padded,
+                                            int lane) {
+  for (int j = lane; j < padded; j += IG_WAVE) {
     float v = 0.f;
     if (j < a.r) {
       const float *p = a.qsrc + (long)b * a.b_stride + (long)h * a.r + j;
@@ -73,23 +74,27 @@ __device__ __forceinline__ void fma_block(const typename Elem<T>::vec (&v)[CH], 
   }
 }
 
-// Threshold + ordered compaction of the scores a block holds in registers.  Wave w holds the
-// scores of tokens t0 + lane*TPL + e (e < TPL); waves are in ascending token order.  `base`
-// is the number of tokens already emitted for this (b,h).  Returns the block's total.
+// Threshold + ordered compaction of the scores a block holds in registers.  Wave w (< NW) holds
+// the scores of tokens t0 + lane*TPL + e (e < TPL); waves are in ascending token order; waves
+// with w >= NW hold nothing.  `base` is the number of tokens already emitted for this (b,h).
+// The slot of (lane, e) is the number of kept tokens in lower lanes -- one ballot and one
+// masked bit count per e -- plus the kept tokens of the lane's own lower e.  Returns the block's total.
 template <int TPL, int NW>
 __device__ __forceinline__ int compact_block(const float (&sc)[TPL], int t0, int N, float thr,
                                              int base, int32_t *list, int sel_stride, int *lds_cnt,
                                              int w, int lane) {
   unsigned mask = 0;
+  int below = 0, total = 0;
 #pragma unroll
   for (int e = 0; e < TPL; ++e) {
-    int t = t0 + lane * TPL + e;
-    if (t < N && sc[e] >= thr) mask |= 1u << e;
+    const int t = t0 + lane * TPL + e;
+    const bool keep = w < NW && t < N && sc[e] >= thr;
+    const unsigned long long bal = __ballot(keep);
+    below += lanes_below(bal);
+    total += __popcll(bal);
+    mask |= (keep ? 1u : 0u) << e;
   }
-  int cnt = __popc(mask);
-  int incl = wave_incl_scan(cnt, lane);
-  int total = __shfl(incl, 63, 64);
-  if (lane == 0) lds_cnt[w] = total;
+  if (lane == 0 && w < NW) lds_cnt[w] = total;
   __syncthreads();
   int before = 0, all = 0;
 #pragma unroll
@@ -98,7 +103,7 @@ __device__ __forceinline__ int compact_block(const float (&sc)[TPL], int t0, int
     before += (k < w) ? c : 0;
     all += c;
   }
-  int pos = base + before + incl - cnt;
+  int pos = base + before + below;
 #pragma unroll
   for (int e = 0; e < TPL; ++e) {
     if (mask & (1u << e)) {
@@ -110,9 +115,12 @@ __device__ __forceinline__ int compact_block(const float (&sc)[TPL], int t0, int
   return all;
 }
 
-// One workgroup per (b,h); wave w scans tile w (nTiles <= NW).  Scores never leave registers.
+// One workgroup per (b,h); wave w < NW scans tile w (nTiles <= NW) and keeps its scores in
+// registers.  One extra wave only stages the partial query into LDS: it has no slab loads
+// outstanding, so waiting for the query never waits for slab data, while the scanning waves issue
+// their loads before anything else.
 template <typename T, int CH, int NW>
-__global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
+__global__ __launch_bounds__((NW + 1) * 64) void scan_select_fused(ScanArgs a) {
   constexpr int TPL = Elem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
   __shared__ float q_lds[256 + CH];
@@ -120,7 +128,7 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
   __shared__ int lds_cnt[NW];
   const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const bool active = w < a.nTiles;
+  const bool active = w < a.nTiles;   // nTiles <= NW: the staging wave (w == NW) is never active
   const T *tile = static_cast<const T *>(a.slab) + ((long)bh * a.nTiles + (active ? w : 0)) * a.r * TILE;
   const int padded = (a.r + CH - 1) / CH * CH;
 
@@ -129,10 +137,8 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
 #pragma unroll
   for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
 
-  // query partial sums first, then the first block of slab loads, so that waiting for the query
-  // leaves the slab loads in flight
-  stage_query(a, b, h, q_lds, padded);
   if (active) load_block<T, CH>(tile, a.r, 0, lane, v);
+  if (w == NW) stage_query(a, b, h, q_lds, padded, lane);
   __syncthreads();
   if (active) {
     fma_block<T, CH>(v, q_lds, 0, acc);
@@ -157,7 +163,7 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
     }
   }
   m = wave_max(m);
-  if (lane == 0) lds_max[w] = m;
+  if (lane == 0 && w < NW) lds_max[w] = m;
   __syncthreads();
   float mm = lds_max[0];
 #pragma unroll
@@ -174,22 +180,22 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
 // Long sequences / few heads: one wave per tile, 4 tiles per workgroup; scores and per-tile maxima
 // go to a buffer, and select_scores does the threshold pass.
 template <typename T, int CH>
-__global__ __launch_bounds__(256) void scan_tiles(ScanArgs a) {
+__global__ __launch_bounds__(320) void scan_tiles(ScanArgs a) {
   constexpr int TPL = Elem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
   __shared__ float q_lds[256 + CH];
   const int bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int tileno = blockIdx.x * 4 + w;
-  const bool active = tileno < a.nTiles;
+  const bool active = w < 4 && tileno < a.nTiles;   // wave 4 only stages the query
   const T *tile = static_cast<const T *>(a.slab) + ((long)bh * a.nTiles + (active ? tileno : 0)) * a.r * TILE;
   const int padded = (a.r + CH - 1) / CH * CH;
   typename Elem<T>::vec v[CH];
   float acc[TPL];
 #pragma unroll
   for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
-  stage_query(a, b, h, q_lds, padded);
   if (active) load_block<T, CH>(tile, a.r, 0, lane, v);
+  if (w == 4) stage_query(a, b, h, q_lds, padded, lane);
   __syncthreads();
   if (!active) return;
   fma_block<T, CH>(v, q_lds, 0, acc);
@@ -259,20 +265,28 @@ int pick_ch(int r, int cap) {
 
 template <typename T, int NW>
 int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) {
-  dim3 grid(BH), block(NW * 64);
+  dim3 grid(BH), block((NW + 1) * 64);
 #define CASE(CHV)                                                              \
   case CHV: {                                                                  \
     auto k = scan_select_fused<T, CHV, NW>;                                    \
     IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                           \
     return IG_OK;                                                              \
   }
+  // registers per wave shrink as the workgroup grows: 5 waves allow 40 loads in flight, 9 waves 24,
+  // 16 waves 20
   switch (ch) {
     CASE(4) CASE(8) CASE(12) CASE(16) CASE(20)
     default: break;
   }
   if constexpr (NW <= 8) {
     switch (ch) {
-      CASE(24) CASE(28) CASE(32) CASE(36) CASE(40)
+      CASE(24)
+      default: break;
+    }
+  }
+  if constexpr (NW <= 4) {
+    switch (ch) {
+      CASE(32) CASE(36) CASE(40)
       default: break;
     }
   }
@@ -282,7 +296,7 @@ int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
 
 template <typename T>
 int launch_tiles(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) {
-  dim3 grid((a.nTiles + 3) / 4, BH), block(256);
+  dim3 grid((a.nTiles + 3) / 4, BH), block(320);
 #define CASE(CHV)                                                              \
   case CHV: {                                                                  \
     auto k = scan_tiles<T, CHV>;                                               \
@@ -305,11 +319,11 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
   const int nTiles = a.nTiles;
   // Fused when a (b,h) fits one workgroup and there are enough (b,h) pairs to fill the chip;
   // otherwise one wave per tile so that long sequences spread over all compute units.
-  const bool fused = nTiles <= 16 && (BH >= 128 || nTiles <= 4);
+  const bool fused = nTiles <= 15 && (BH >= 128 || nTiles <= 4);
   if (fused) {
     if (nTiles <= 4) return launch_fused<T, 4>(ctx, a, BH, pick_ch(d->r, 40), s);
-    if (nTiles <= 8) return launch_fused<T, 8>(ctx, a, BH, pick_ch(d->r, 40), s);
-    return launch_fused<T, 16>(ctx, a, BH, pick_ch(d->r, 20), s);
+    if (nTiles <= 8) return launch_fused<T, 8>(ctx, a, BH, pick_ch(d->r, 24), s);
+    return launch_fused<T, 15>(ctx, a, BH, pick_ch(d->r, 20), s);
   }
   size_t need_s = (size_t)BH * d->N * sizeof(float), need_m = (size_t)BH * nTiles * sizeof(float);
   float *user_scores = a.scores_out;

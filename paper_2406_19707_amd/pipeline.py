@@ -1,0 +1,175 @@
+"""Decode-step driver over the C ABI: model-level setup and the per-layer call sequence.
+
+Everything the method computes happens inside libinfinigen_hip (ig_skew_offline, ig_partial_index,
+ig_wq_build, ig_slab_build, ig_speculate, ig_gather_kv, ig_sparse_attention).  This module only
+allocates tensors, draws the synthetic model state that surrounds the path (weights, KV cache,
+layer inputs, the layer's real query) and issues the calls in the order of the paper's decode
+stage (Section 4.3, Fig. 3(d)): rehearsal of layer i+1 -> prefetch of its K/V rows -> attention.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+import torch
+
+import ig_workloads as wl
+from . import binding as ig
+
+
+def _rope_rows(q: np.ndarray, pos: np.ndarray, theta: float = 10000.0) -> np.ndarray:
+    """Model-side rotary embedding of query rows [rows, H, d] (rotate-half pairing)."""
+    rows, H, d = q.shape
+    half = d // 2
+    ang = pos.astype(np.float64)[:, None] * theta ** (-2.0 * np.arange(half) / d)[None, :]
+    c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    a, b = q[..., :half].astype(np.float64), q[..., half:].astype(np.float64)
+    return np.concatenate([a * c - b * s, b * c + a * s], -1).astype(np.float32)
+
+
+class Rehearsal:
+    """State of `layers` decoder layers of one workload and the hot-path call sequence over them."""
+
+    def __init__(self, ctx: ig.Context, w: wl.Workload, gain: float | None = None,
+                 layers: int | None = None, host_layers: int = 4, log=lambda *a: None):
+        self.ctx, self.w = ctx, w
+        self.L = layers or w.layers
+        self.gain = w.gain if gain is None else gain
+        dev = "cuda"
+        tdt = torch.float32 if w.dtype == "f32" else torch.float16
+        self.tdt = tdt
+
+        # ---- offline: skewing (Section 4.2) on the calibration queries ----
+        Wq = wl.projection_weight(w, "Wq")
+        Xcal = wl.calibration_input(w)
+        Qcal = Xcal @ Wq
+        if w.rope:
+            Qcal = _rope_rows(Qcal.reshape(w.n_cal, w.H, w.d),
+                              np.arange(w.n_cal)).reshape(w.n_cal, w.D)
+        log("weights drawn")
+        sk = ig.ig_skew_offline(Wq, None, Qcal, w.H, ctx=ctx)
+        self.A = sk["A"]
+        log("skewed")
+        # ---- prefill: partial weight index (Section 4.3), query-only ranking on Q~ = Qcal A ----
+        Qs = np.einsum("nhk,hkj->nhj", Qcal.reshape(w.n_cal, w.H, w.d), self.A).reshape(w.n_cal, w.D)
+        self.idx_host = ig.ig_partial_index(Qs, None, w.H, w.ratio, ctx=ctx)
+        self.r = self.idx_host.shape[1]
+        self.desc = ig.IgDesc(B=w.B, H=w.H, d=w.d, r=self.r, N=w.N, N_cap=w.N,
+                              dtype=ig.IG_F32 if w.dtype == "f32" else ig.IG_F16,
+                              scale=self.gain / math.sqrt(w.d), alpha=w.alpha,
+                              rope=1 if w.rope else 0)
+        self.idx = torch.from_numpy(self.idx_host).to(dev)
+        W_in = Wq if w.rope else sk["Wq_s"]
+        self.W_host = wl.quantise(W_in, w)
+        Wd = torch.from_numpy(self.W_host).to(dev)
+        self.wq = torch.empty(ig.ig_wq_bytes(self.desc), dtype=torch.uint8, device=dev)
+        ctx.ig_wq_build(self.desc, Wd, self.idx, self.wq)
+        self.A_p = self.pos = None
+        if w.rope:
+            A_p = np.stack([self.A[h][:, self.idx_host[h]] for h in range(w.H)]).astype(np.float32)
+            self.A_p = torch.from_numpy(np.ascontiguousarray(A_p)).to(dev)
+            self.pos = torch.full((w.B,), w.N, dtype=torch.int32, device=dev)
+        Wq_model = Wd                      # weight the stand-in model uses for the layer's real query
+        A_dev = torch.from_numpy(self.A).to(dev)
+        ctx.ig_reserve(self.desc)
+        log("partial weight built")
+
+        # ---- per-layer state ----
+        self.host_pool = w.pool == "host"
+        self.n_pool = min(self.L, host_layers) if self.host_pool else self.L
+        self.x, self.q, self.slab, self.K, self.V = [], [], [], [], []
+        slab_bytes = ig.ig_slab_bytes(self.desc)
+        for l in range(self.L):
+            if l == 0:
+                x = torch.from_numpy(wl.quantise(wl.attention_input(w, 0), w)).to(dev)
+                xn = torch.from_numpy(wl.next_layer_input(w, x.float().cpu().numpy(), 0)).to(dev)
+                Kn, Vn = wl.kv_cache(w, 0)          # keys are drawn directly in the skewed basis
+                K = torch.from_numpy(wl.quantise(Kn, w))
+                V = torch.from_numpy(wl.quantise(Vn, w))
+                del Kn, Vn
+                self.layer0_host = dict(x=x.cpu().numpy(), K=K.numpy(), V=V.numpy())
+                K, V = K.to(dev), V.to(dev)
+            else:
+                g = torch.Generator(device=dev).manual_seed(1000 * w.cfg + 7919 * l)
+                x = torch.randn((w.B, w.D), generator=g, device=dev).to(tdt)
+                xn = x.float() + 0.3 * torch.randn((w.B, w.D), generator=g, device=dev)
+                K = torch.randn((w.B, w.H, w.N, w.d), generator=g, device=dev, dtype=tdt)
+                V = torch.randn((w.B, w.H, w.N, w.d), generator=g, device=dev, dtype=tdt)
+                gain_rows = torch.from_numpy(wl.key_row_gain(w, l)).to(dev).to(tdt)
+                K *= gain_rows[:, None, :, None]
+            # the layer's real (skewed) query: the stand-in model's projection of its own input
+            qf = (xn.to(tdt) @ Wq_model).float().reshape(w.B, w.H, w.d)
+            if w.rope:
+                qf = torch.from_numpy(_rope_rows(qf.cpu().numpy(), np.full(w.B, w.N))).to(dev)
+                qf = torch.einsum("bhk,hkj->bhj", qf, A_dev)
+            q = qf.to(tdt).contiguous()
+            slab = torch.empty(slab_bytes, dtype=torch.uint8, device=dev)
+            ctx.ig_slab_build(self.desc, K, ig.IG_MEM_DEVICE, self.idx, slab)
+            torch.cuda.synchronize()
+            self.x.append(x)
+            self.q.append(q)
+            self.slab.append(slab)
+            if l == 0:
+                self.layer0_host["q"] = q.cpu().numpy()
+            if self.host_pool:
+                if l < self.n_pool:
+                    Kh = torch.empty(K.shape, dtype=tdt, pin_memory=True)
+                    Vh = torch.empty(V.shape, dtype=tdt, pin_memory=True)
+                    Kh.copy_(K)
+                    Vh.copy_(V)
+                    self.K.append(Kh)
+                    self.V.append(Vh)
+                del K, V
+            else:
+                self.K.append(K)
+                self.V.append(V)
+        log("layers built")
+        self.space = ig.IG_MEM_HOST_PINNED if self.host_pool else ig.IG_MEM_DEVICE
+        BH = w.B * w.H
+        self.stride = w.N
+        self.sel_idx = torch.zeros((BH, self.stride), dtype=torch.int32, device=dev)
+        self.sel_cnt = torch.zeros((BH,), dtype=torch.int32, device=dev)
+        self.K_sel = torch.zeros((BH, self.stride, w.d), dtype=tdt, device=dev)
+        self.V_sel = torch.zeros((BH, self.stride, w.d), dtype=tdt, device=dev)
+        self.out = torch.zeros((w.B, w.H, w.d), dtype=tdt, device=dev)
+
+    # ---- hot path ----
+    def speculate(self, l, scores=None):
+        self.ctx.ig_speculate(self.desc, self.x[l], self.wq, None, self.A_p, self.pos, self.slab[l],
+                              self.sel_idx, self.stride, self.sel_cnt, scores)
+
+    def gather(self, l, stream=None):
+        p = l % self.n_pool
+        self.ctx.ig_gather_kv(self.desc, self.K[p], self.V[p], self.space, self.sel_idx, self.stride,
+                              self.sel_cnt, self.K_sel, self.V_sel, stream)
+
+    def attend(self, l):
+        self.ctx.ig_sparse_attention(self.desc, self.q[l], self.K_sel, self.V_sel, self.sel_cnt,
+                                     self.stride, None, None, self.out)
+
+    def attend_indexed(self, l):
+        p = l % self.n_pool
+        self.ctx.ig_sparse_attention_indexed(self.desc, self.q[l], self.K[p], self.V[p], self.sel_idx,
+                                             self.stride, self.sel_cnt, None, None, self.out)
+
+    def layer(self, l):
+        """Rehearsal, prefetch and sparse attention of one layer on the current stream."""
+        self.speculate(l)
+        self.gather(l)
+        self.attend(l)
+
+    def step(self):
+        """One decode step: every layer once (distinct slabs, so nothing is served from cache)."""
+        for l in range(self.L):
+            self.layer(l)
+
+    def step_fused_attention(self):
+        """Variant for an HBM-resident pool: the index lists are applied inside the attention."""
+        for l in range(self.L):
+            self.speculate(l)
+            self.attend_indexed(l)
+
+    def scan_bytes(self) -> int:
+        """Algorithmic bytes of one partial-K scan: 2*B*H*N*r (elements actually needed)."""
+        w = self.w
+        return w.B * w.H * w.N * self.r * (4 if w.dtype == "f32" else 2)
