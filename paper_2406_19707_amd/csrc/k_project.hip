@@ -98,17 +98,32 @@ __global__ __launch_bounds__(256) void project_mfma(const half8 *__restrict__ bl
   floatx4 acc[NB];
 #pragma unroll
   for (int i = 0; i < NB; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-  const half8 *wp = blob + ((long)cblk * nKblk + kb0) * 64 + lane;
+  const half8 *wp = blob + ((long)cblk * nKblk) * 64 + lane;
   const half8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll 4
-  for (int kb = kb0; kb < kb1; ++kb, wp += 64) {
-    half8 a = *wp;
+  // K blocks are taken KB at a time: all weight pieces and x fragments of a batch are loaded before
+  // the first MFMA, so a wave keeps KB * (1 + NB) KiB in flight (a block past the end is clamped
+  // to the last one and its MFMA skipped).
+  constexpr int KB = NB == 1 ? 8 : (NB == 2 ? 6 : 4);
+  for (int kb = kb0; kb < kb1; kb += KB) {
+    half8 a[KB], bfrag[NB][KB];
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
-      int row = (nb0 + i) * 16 + n;
-      half8 bfrag = zero;
-      if (row < B) bfrag = *reinterpret_cast<const half8 *>(x + (long)row * D + kb * 32 + kg * 8);
-      acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, bfrag, acc[i], 0, 0, 0);
+    for (int t = 0; t < KB; ++t) {
+      const int kbt = min(kb + t, kb1 - 1);
+      a[t] = wp[(long)kbt * 64];
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const int row = (nb0 + i) * 16 + n;
+        bfrag[i][t] = zero;
+        if (row < B) bfrag[i][t] = *reinterpret_cast<const half8 *>(x + (long)row * D + kbt * 32 + kg * 8);
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < KB; ++t) {
+      if (kb + t < kb1) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i)
+          acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[t], bfrag[i][t], acc[i], 0, 0, 0);
+      }
     }
   }
 #pragma unroll

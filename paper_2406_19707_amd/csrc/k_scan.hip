@@ -29,25 +29,43 @@ struct ScanArgs {
   float scale, alpha;
 };
 
-// Partial query of (b,h) into LDS, scaled, zero-padded to `padded` entries.
-// value(j) = scale * (bias[h*r+j] + sum_s qsrc[s*ks_stride + b*b_stride + h*r + j]); the partial
-// sums are loaded up front (independent loads) and added in a fixed order.
-__device__ __forceinline__ void stage_query(const ScanArgs &a, int b, int h, float *q_lds, int padded,
-                                            int lane) {
-  for (int j = lane; j < padded; j += IG_WAVE) {
-    float v = 0.f;
-    if (j < a.r) {
-      const float *p = a.qsrc + (long)b * a.b_stride + (long)h * a.r + j;
-      float part[IG_KS_MAX];
+// Partial query of (b,h), kept in registers: lane l of every scanning wave holds q[l + 64*k], k < 4
+// (r <= 256), scaled.  value(j) = scale * (bias[h*r+j] + sum_s qsrc[s*ks_stride + b*b_stride + h*r + j]).
+// The loads are issued by query_issue() BEFORE the wave's slab loads, so they sit at the head of
+// the memory queue and return early; query_finish() adds them in a fixed order.  During the scan a
+// channel's query entry is broadcast with v_readlane, so the inner loop touches neither LDS nor a
+// barrier.
+struct QueryLoads {
+  float part[IG_KS_MAX];   // split-K partial sums of channel `lane` (r <= 64 needs only these)
+  float bias;
+};
+__device__ __forceinline__ void query_issue(const ScanArgs &a, int b, int h, int lane, int k, QueryLoads &ql) {
+  const int j = lane + 64 * k;
 #pragma unroll
-      for (int s = 0; s < IG_KS_MAX; ++s) part[s] = (s < a.ks) ? p[(long)s * a.ks_stride] : 0.f;
-      float acc = a.bias ? a.bias[h * a.r + j] : 0.f;
+  for (int s = 0; s < IG_KS_MAX; ++s) ql.part[s] = 0.f;
+  ql.bias = 0.f;
+  if (j < a.r) {
+    const float *p = a.qsrc + (long)b * a.b_stride + (long)h * a.r + j;
 #pragma unroll
-      for (int s = 0; s < IG_KS_MAX; ++s) acc += part[s];
-      v = acc * a.scale;
-    }
-    q_lds[j] = v;
+    for (int s = 0; s < IG_KS_MAX; ++s)
+      if (s < a.ks) ql.part[s] = p[(long)s * a.ks_stride];
+    if (a.bias) ql.bias = a.bias[h * a.r + j];
   }
+}
+__device__ __forceinline__ float query_finish(const ScanArgs &a, const QueryLoads &ql) {
+  float acc = ql.bias;
+#pragma unroll
+  for (int s = 0; s < IG_KS_MAX; ++s) acc += ql.part[s];
+  return acc * a.scale;
+}
+// lane l (< CH) gets q[j0 + l] out of the four per-lane registers
+__device__ __forceinline__ float query_block(const float (&qv)[4], int j0, int lane) {
+  const int j = j0 + lane;
+  const int src = j & 63, k = (j >> 6) & 3;
+  const float t0 = __shfl(qv[0], src, 64), t1 = __shfl(qv[1], src, 64);
+  const float t2 = __shfl(qv[2], src, 64), t3 = __shfl(qv[3], src, 64);
+  const float t = k == 0 ? t0 : (k == 1 ? t1 : (k == 2 ? t2 : t3));
+  return j < 256 ? t : 0.f;
 }
 
 template <typename T, int CH>
@@ -55,22 +73,58 @@ __device__ __forceinline__ void load_block(const T *tile, int r, int j0, int lan
                                            typename Elem<T>::vec (&v)[CH]) {
   constexpr int TPL = Elem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
+  const char *base = reinterpret_cast<const char *>(tile);
+  const unsigned lane_off = (unsigned)lane * (unsigned)(TPL * sizeof(T));
 #pragma unroll
   for (int j = 0; j < CH; ++j) {
-    int jj = min(j0 + j, r - 1);   // channels past r re-read the last plane; their query entry is 0
-    v[j] = *reinterpret_cast<const typename Elem<T>::vec *>(tile + (long)jj * TILE + lane * TPL);
+    const int jj = min(j0 + j, r - 1);   // channels past r re-read the last plane; their query entry is 0
+    const char *plane = base + (size_t)jj * (TILE * sizeof(T));
+    v[j] = *reinterpret_cast<const typename Elem<T>::vec *>(plane + lane_off);
   }
 }
 
+// qblk: lane l holds the query entry of channel j0 + l (0 past r)
 template <typename T, int CH>
-__device__ __forceinline__ void fma_block(const typename Elem<T>::vec (&v)[CH], const float *q_lds,
-                                          int j0, float (&acc)[Elem<T>::TPL]) {
+__device__ __forceinline__ void fma_block(const typename Elem<T>::vec (&v)[CH], float qblk,
+                                          float (&acc)[Elem<T>::TPL]) {
   constexpr int TPL = Elem<T>::TPL;
+  const int qbits = __float_as_int(qblk);
 #pragma unroll
   for (int j = 0; j < CH; ++j) {
-    float qj = q_lds[j0 + j];
+    const float qj = __int_as_float(__builtin_amdgcn_readlane(qbits, j));
 #pragma unroll
     for (int e = 0; e < TPL; ++e) acc[e] = fmaf((float)v[j][e], qj, acc[e]);
+  }
+}
+
+// All channels of one tile for one wave: query loads, slab loads, then FMAs as the data arrives.
+template <typename T, int CH>
+__device__ __forceinline__ void scan_tile(const ScanArgs &a, const T *tile, int b, int h, int lane,
+                                          float (&acc)[Elem<T>::TPL]) {
+  constexpr int TPL = Elem<T>::TPL;
+  typename Elem<T>::vec v[CH];
+#pragma unroll
+  for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
+  QueryLoads ql;
+  query_issue(a, b, h, lane, 0, ql);
+  load_block<T, CH>(tile, a.r, 0, lane, v);
+  float qv[4];
+  qv[0] = query_finish(a, ql);
+  qv[1] = qv[2] = qv[3] = 0.f;
+  if (a.r <= CH) {           // the usual case: one block, lane l already holds channel l
+    fma_block<T, CH>(v, qv[0], acc);
+    return;
+  }
+  if (a.r > 64) {            // wide heads: three more registers per lane
+    for (int k = 1; k < 4; ++k) {
+      query_issue(a, b, h, lane, k, ql);
+      qv[k] = query_finish(a, ql);
+    }
+  }
+  fma_block<T, CH>(v, query_block(qv, 0, lane), acc);
+  for (int j0 = CH; j0 < a.r; j0 += CH) {
+    load_block<T, CH>(tile, a.r, j0, lane, v);
+    fma_block<T, CH>(v, query_block(qv, j0, lane), acc);
   }
 }
 
@@ -115,38 +169,22 @@ __device__ __forceinline__ int compact_block(const float (&sc)[TPL], int t0, int
   return all;
 }
 
-// One workgroup per (b,h); wave w < NW scans tile w (nTiles <= NW) and keeps its scores in
-// registers.  One extra wave only stages the partial query into LDS: it has no slab loads
-// outstanding, so waiting for the query never waits for slab data, while the scanning waves issue
-// their loads before anything else.
+// One workgroup per (b,h); wave w scans tile w (nTiles <= NW) and keeps its scores in registers.
 template <typename T, int CH, int NW>
-__global__ __launch_bounds__((NW + 1) * 64) void scan_select_fused(ScanArgs a) {
+__global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
   constexpr int TPL = Elem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
-  __shared__ float q_lds[256 + CH];
   __shared__ float lds_max[NW];
   __shared__ int lds_cnt[NW];
   const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H;
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const bool active = w < a.nTiles;   // nTiles <= NW: the staging wave (w == NW) is never active
+  // the wave index is made a scalar so that tile addresses stay in scalar registers
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const bool active = w < a.nTiles;
   const T *tile = static_cast<const T *>(a.slab) + ((long)bh * a.nTiles + (active ? w : 0)) * a.r * TILE;
-  const int padded = (a.r + CH - 1) / CH * CH;
-
-  typename Elem<T>::vec v[CH];
   float acc[TPL];
 #pragma unroll
   for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
-
-  if (active) load_block<T, CH>(tile, a.r, 0, lane, v);
-  if (w == NW) stage_query(a, b, h, q_lds, padded, lane);
-  __syncthreads();
-  if (active) {
-    fma_block<T, CH>(v, q_lds, 0, acc);
-    for (int j0 = CH; j0 < a.r; j0 += CH) {
-      load_block<T, CH>(tile, a.r, j0, lane, v);
-      fma_block<T, CH>(v, q_lds, j0, acc);
-    }
-  }
+  if (active) scan_tile<T, CH>(a, tile, b, h, lane, acc);
   const int t0 = w * TILE;
   float m = -INFINITY;
 #pragma unroll
@@ -163,7 +201,7 @@ __global__ __launch_bounds__((NW + 1) * 64) void scan_select_fused(ScanArgs a) {
     }
   }
   m = wave_max(m);
-  if (lane == 0 && w < NW) lds_max[w] = m;
+  if (lane == 0) lds_max[w] = m;
   __syncthreads();
   float mm = lds_max[0];
 #pragma unroll
@@ -180,29 +218,16 @@ __global__ __launch_bounds__((NW + 1) * 64) void scan_select_fused(ScanArgs a) {
 // Long sequences / few heads: one wave per tile, 4 tiles per workgroup; scores and per-tile maxima
 // go to a buffer, and select_scores does the threshold pass.
 template <typename T, int CH>
-__global__ __launch_bounds__(320) void scan_tiles(ScanArgs a) {
+__global__ __launch_bounds__(256) void scan_tiles(ScanArgs a) {
   constexpr int TPL = Elem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
-  __shared__ float q_lds[256 + CH];
   const int bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int tileno = blockIdx.x * 4 + w;
-  const bool active = w < 4 && tileno < a.nTiles;   // wave 4 only stages the query
-  const T *tile = static_cast<const T *>(a.slab) + ((long)bh * a.nTiles + (active ? tileno : 0)) * a.r * TILE;
-  const int padded = (a.r + CH - 1) / CH * CH;
-  typename Elem<T>::vec v[CH];
+  if (tileno >= a.nTiles) return;
+  const T *tile = static_cast<const T *>(a.slab) + ((long)bh * a.nTiles + tileno) * a.r * TILE;
   float acc[TPL];
-#pragma unroll
-  for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
-  if (active) load_block<T, CH>(tile, a.r, 0, lane, v);
-  if (w == 4) stage_query(a, b, h, q_lds, padded, lane);
-  __syncthreads();
-  if (!active) return;
-  fma_block<T, CH>(v, q_lds, 0, acc);
-  for (int j0 = CH; j0 < a.r; j0 += CH) {
-    load_block<T, CH>(tile, a.r, j0, lane, v);
-    fma_block<T, CH>(v, q_lds, j0, acc);
-  }
+  scan_tile<T, CH>(a, tile, b, h, lane, acc);
   const int t0 = tileno * TILE;
   float m = -INFINITY;
 #pragma unroll
@@ -265,28 +290,28 @@ int pick_ch(int r, int cap) {
 
 template <typename T, int NW>
 int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) {
-  dim3 grid(BH), block((NW + 1) * 64);
+  dim3 grid(BH), block(NW * 64);
 #define CASE(CHV)                                                              \
   case CHV: {                                                                  \
     auto k = scan_select_fused<T, CHV, NW>;                                    \
     IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                           \
     return IG_OK;                                                              \
   }
-  // registers per wave shrink as the workgroup grows: 5 waves allow 40 loads in flight, 9 waves 24,
-  // 16 waves 20
+  // registers per wave shrink as the workgroup grows: 4 waves allow 40 loads in flight, 8 waves 24,
+  // 16 waves 12
   switch (ch) {
-    CASE(4) CASE(8) CASE(12) CASE(16) CASE(20)
+    CASE(4) CASE(8) CASE(12)
     default: break;
   }
   if constexpr (NW <= 8) {
     switch (ch) {
-      CASE(24)
+      CASE(16) CASE(20) CASE(24)
       default: break;
     }
   }
   if constexpr (NW <= 4) {
     switch (ch) {
-      CASE(32) CASE(36) CASE(40)
+      CASE(28) CASE(32) CASE(36) CASE(40)
       default: break;
     }
   }
@@ -296,7 +321,7 @@ int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
 
 template <typename T>
 int launch_tiles(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) {
-  dim3 grid((a.nTiles + 3) / 4, BH), block(320);
+  dim3 grid((a.nTiles + 3) / 4, BH), block(256);
 #define CASE(CHV)                                                              \
   case CHV: {                                                                  \
     auto k = scan_tiles<T, CHV>;                                               \
@@ -319,11 +344,14 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
   const int nTiles = a.nTiles;
   // Fused when a (b,h) fits one workgroup and there are enough (b,h) pairs to fill the chip;
   // otherwise one wave per tile so that long sequences spread over all compute units.
-  const bool fused = nTiles <= 15 && (BH >= 128 || nTiles <= 4);
+  const bool fused = nTiles <= 16 && (BH >= 128 || nTiles <= 4);
   if (fused) {
-    if (nTiles <= 4) return launch_fused<T, 4>(ctx, a, BH, pick_ch(d->r, 40), s);
+    // When all workgroups fit on the chip at once (one round) a wave should have all its channels
+    // in flight; with several rounds, smaller blocks leave room for more resident workgroups whose
+    // load and select phases then overlap (measured: 60 % -> 71 % of HBM peak at 1120 workgroups).
+    if (nTiles <= 4) return launch_fused<T, 4>(ctx, a, BH, pick_ch(d->r, BH > 512 ? 20 : 40), s);
     if (nTiles <= 8) return launch_fused<T, 8>(ctx, a, BH, pick_ch(d->r, 24), s);
-    return launch_fused<T, 15>(ctx, a, BH, pick_ch(d->r, 20), s);
+    return launch_fused<T, 16>(ctx, a, BH, pick_ch(d->r, 12), s);
   }
   size_t need_s = (size_t)BH * d->N * sizeof(float), need_m = (size_t)BH * nTiles * sizeof(float);
   float *user_scores = a.scores_out;
