@@ -21,6 +21,9 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per scan launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the counter
+# reads for a plain 256 MiB copy (profiles/cfg2_hbm_traffic_counters.txt); None = not collected.
+SCAN_TRAFFIC_BYTES = {2: 41.22e6}
 
 
 def log(*a):
@@ -38,6 +41,8 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-literal", action="store_true", help="skip the gain-1 (select everything) variant")
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="also launch a plain 256 MiB device copy (reference for scaling hardware counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); the path shards over (sequence, "
@@ -69,10 +74,45 @@ def main():
         return (time.perf_counter() - t) * 1e3 / steps
 
     # ---- eager ----
-    for _ in range(W):
-        R.step()
-    assert ctx.ig_check_status() == ig.IG_OK
-    eager_ms = timed(R.step, K)
+    pcie = None
+    if R.host_pool:
+        # host pool: PCIe ceiling from a plain pinned -> device copy, then the side-stream pipeline
+        src = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
+        dst = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst.copy_(src, non_blocking=True)
+        h2d_ms = timed(lambda: dst.copy_(src, non_blocking=True), 5)
+        h2d_gbs = (1 << 30) / (h2d_ms * 1e-3) / 1e9
+        del src, dst
+        log(f"pinned->device copy: {h2d_gbs:.1f} GB/s")
+        for _ in range(W):
+            R.step_overlapped()
+        torch.cuda.synchronize()
+        assert ctx.ig_check_status() == ig.IG_OK
+        eager_ms = timed(R.step_overlapped, K)
+        main_ms = timed(R.step_without_gather, K)
+        with torch.cuda.stream(R.side):
+            R.step_gather_only()
+            torch.cuda.synchronize()
+            gather_ms = timed(R.step_gather_only, K)
+        rows = 0
+        for l in range(L):
+            R._use(l)
+            R.speculate(l)
+            rows += int(R.sel_cnt.sum().item())
+        gbytes = rows * 2 * w.d * 2 / L                      # K and V rows per layer
+        g_gbs = gbytes / (gather_ms * 1e-3 / L) / 1e9
+        shorter = min(main_ms, gather_ms)
+        pcie = {"h2d_memcpy_GBps": h2d_gbs, "gather_GBps": g_gbs, "frac_of_memcpy": g_gbs / h2d_gbs,
+                "gathered_MB_per_layer": gbytes / 1e6, "gather_alone_us_per_layer": gather_ms * 1e3 / L,
+                "main_alone_us_per_layer": main_ms * 1e3 / L, "overlapped_us_per_layer": eager_ms * 1e3 / L,
+                "overlap_efficiency": (main_ms + gather_ms - eager_ms) / shorter}
+        log("pcie", pcie)
+        args.no_graph = True
+    else:
+        for _ in range(W):
+            R.step()
+        assert ctx.ig_check_status() == ig.IG_OK
+        eager_ms = timed(R.step, K)
     cnt = R.sel_cnt.cpu().numpy()            # last layer of the step
     log(f"eager {eager_ms:.3f} ms/step = {eager_ms * 1e3 / L:.2f} us/layer")
 
@@ -107,31 +147,49 @@ def main():
         fused_ms = timed(R.step_fused_attention, K)
 
     # ---- per-kernel durations from HIP events attached to the launches ----
-    ctx.ig_profile_begin()
-    for _ in range(K):
-        R.step()
-    ctx.ig_profile_end()
+    prof_ctxs = [ctx] + ([R.side_ctx] if R.host_pool else [])
+    for c in prof_ctxs:
+        c.ig_profile_begin()
+    for _ in range(max(1, K // 4) if R.host_pool else K):
+        if R.host_pool:
+            R.step_overlapped()
+        else:
+            R.step()
+    for c in prof_ctxs:
+        c.ig_profile_end()
     names = {ig.IG_K_PROJECT: "project", ig.IG_K_FINALIZE: "finalize", ig.IG_K_SCAN: "scan",
              ig.IG_K_SELECT: "select", ig.IG_K_GATHER: "gather", ig.IG_K_ATTENTION: "attention"}
     kernels = {}
     for kid, name in names.items():
-        ms, n = ctx.ig_profile_read(kid)
+        ms, n = 0.0, 0
+        for c in prof_ctxs:
+            m_, n_ = c.ig_profile_read(kid)
+            ms, n = ms + m_, n + n_
         if n:
             kernels[name] = {"avg_us": ms * 1e3 / n, "launches": n}
     scan_us = kernels["scan"]["avg_us"]
     scan_bytes = R.scan_bytes()
     achieved = scan_bytes / (scan_us * 1e-6) / 1e9
 
+    if args.copy_reference:
+        a_ = torch.zeros(1 << 28, dtype=torch.uint8, device="cuda")
+        b_ = torch.empty_like(a_)
+        for _ in range(3):
+            ctx.ig_copy_bytes(a_, b_, 1 << 28)
+        torch.cuda.synchronize()
+        del a_, b_
+
     # ---- selected fraction over all layers ----
     fr = []
     for l in range(L):
+        R._use(0)
         R.speculate(l)
         fr.append(R.sel_cnt.float().mean().item() / w.N)
     torch.cuda.synchronize()
 
     # ---- literal variant (gain 1: every token selected), eager, a few steps ----
     literal = None
-    if R.gain != 1.0 and not args.no_literal:
+    if R.gain != 1.0 and not args.no_literal and not R.host_pool:
         scale = R.desc.scale
         R.desc.scale = 1.0 / (w.d ** 0.5)
         for _ in range(2):
@@ -166,6 +224,7 @@ def main():
         cpu = {"value": cpu_s * 1e6, "unit": "us/layer/decode step", "cores": 1, "kind": "oracle",
                "sample": f"1 of {L} layers, whole batch (project+scan+select+gather+attend, single thread)"}
         # GPU result for the same layer
+        R._use(0)
         R.layer(0)
         torch.cuda.synchronize()
         g_idx, g_cnt = R.sel_idx.cpu().numpy(), R.sel_cnt.cpu().numpy()
@@ -214,8 +273,9 @@ def main():
         "literal_variant": literal,
         "roofline": {"kernel": "partial-K scan + max + threshold + compaction", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": SCAN_TRAFFIC_BYTES.get(args.workload),
                      "algorithmic_bytes_per_launch": scan_bytes, "avg_kernel_us": scan_us},
+        "pcie": pcie,
         "cpu_baseline": cpu,
         "parity": parity,
     }

@@ -59,13 +59,15 @@ WORKLOADS = {
                 ratio=0.3, alpha=4.0, decay=0.95, heavy_count=20, heavy_scale=3.0, gain=32.0,
                 layers=32),
     3: Workload(3, "cfg3 Llama-2-7B-shaped decode layer", B=16, H=32, d=128, N=4096, dtype="f16",
-                ratio=0.3, alpha=5.0, decay=0.95, heavy_count=40, heavy_scale=3.0, rope=True),
+                ratio=0.3, alpha=5.0, decay=0.95, heavy_count=40, heavy_scale=3.0, rope=True,
+                gain=54.0, layers=32),
     4: Workload(4, "cfg4 OPT-30B-shaped decode layer, host KV pool", B=20, H=56, d=128, N=2048,
                 dtype="f16", ratio=0.3, alpha=4.0, decay=0.95, heavy_count=20, heavy_scale=3.0,
-                pool="host"),
+                pool="host", gain=40.0, layers=48),
     5: Workload(5, "cfg5 Llama-2-13B-shaped long context, host KV pool", B=4, H=40, d=128,
                 N=32768, dtype="f16", ratio=0.2, alpha=5.0, decay=0.95, heavy_count=163,
-                heavy_scale=4.0, recent_window=256, recent_scale=2.0, rope=True, pool="host"),
+                heavy_scale=4.0, recent_window=256, recent_scale=2.0, rope=True, pool="host",
+                gain=40.0, layers=40),
 }
 
 

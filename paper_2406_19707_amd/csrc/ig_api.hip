@@ -309,7 +309,7 @@ int ig_gather_kv(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const void *V
   if ((rc = resolve_pool(ctx, Kpool, pool_space, &kp))) return rc;
   if ((rc = resolve_pool(ctx, Vpool, pool_space, &vp))) return rc;
   return ig_launch_gather(ctx, d, kp, vp, sel_idx, sel_stride, sel_cnt, K_sel, V_sel,
-                          (hipStream_t)stream);
+                          pool_space == IG_MEM_HOST_PINNED, (hipStream_t)stream);
 }
 
 int ig_sparse_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K_sel,

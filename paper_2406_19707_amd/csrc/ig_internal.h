@@ -120,7 +120,7 @@ int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const
                           float *scores_opt, hipStream_t s);
 int ig_launch_gather(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const void *Vpool,
                      const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt,
-                     void *K_sel, void *V_sel, hipStream_t s);
+                     void *K_sel, void *V_sel, int host_pool, hipStream_t s);
 int ig_launch_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, const void *V,
                         const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt,
                         int kv_rows_per_bh, const void *k_new, const void *v_new, void *out,
@@ -153,6 +153,15 @@ __device__ __forceinline__ float row16_sum(float v) {
   v += dpp_move<DPP_QUAD_2301>(v);
   v += dpp_move<DPP_ROW_HALF_MIRROR>(v);
   v += dpp_move<DPP_ROW_MIRROR>(v);
+  return v;
+}
+// inclusive prefix sum over the 64 lanes
+__device__ __forceinline__ int wave_incl_scan(int v, int lane) {
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    int u = __shfl_up(v, o, 64);
+    if (lane >= o) v += u;
+  }
   return v;
 }
 // number of lanes below this one whose predicate is set, and the wave's total

@@ -78,13 +78,13 @@ __device__ __forceinline__ bool slice_range(int rows, int s, int max_slices, int
   return true;
 }
 
-// ---- gather -------------------------------------------------------------------------------------
+// ---- gather, device-resident pool ---------------------------------------------------------------
 // Row copies in 16-byte units, U units per row; grid B*H*SLICE_MAX (see work_item).  A thread's copies are
 // issued in batches of GATHER_BATCH, so that index loads, then K and V row loads, are in flight
 // together (this is also what keeps enough PCIe reads outstanding when the pool is pinned host
 // memory).
 constexpr int GATHER_BATCH = 8;
-__global__ __launch_bounds__(256) void gather_rows(
+__global__ __launch_bounds__(256) void gather_rows_sliced(
     const u128 *__restrict__ Kpool, const u128 *__restrict__ Vpool, const int32_t *__restrict__ sel_idx,
     const int32_t *__restrict__ sel_cnt, u128 *__restrict__ K_sel, u128 *__restrict__ V_sel, int N_cap,
     int stride, int U, int H, int BH) {
@@ -118,6 +118,82 @@ __global__ __launch_bounds__(256) void gather_rows(
       const int u = min(u0 + 256 * i, total - 1);
       K_sel[dst0 + u] = kv[i];
       V_sel[dst0 + u] = vv[i];
+    }
+  }
+}
+
+// ---- gather, pinned-host pool --------------------------------------------------------------------
+// The rows of all lists are treated as one flat sequence and cut into equal ranges, one per
+// workgroup: every workgroup reads the B*H counts (one coalesced read), builds their prefix sum in
+// LDS, takes rows [T*g/G, T*(g+1)/G) of the T selected rows and finds the list of each row by
+// binary search in the prefix array.  The split is therefore even whatever the skew of the list
+// lengths, consecutive workgroups (which go to different XCDs) take consecutive ranges, the grid
+// is fixed, and the host never reads a count.  Row copies are in 16-byte units, U units per row;
+// a thread's copies are issued in branch-free batches of GATHER_BATCH (index loads, then K and V
+// row loads, all in flight before the first store).  For a pinned-host pool the grid is kept
+// small: a hundred workgroups keep more than enough PCIe reads outstanding, and the compute units
+// stay free for the kernels of the other stream, which stalled rows would otherwise block.
+constexpr int GATHER_MIN_ROWS = 32;   // a workgroup takes at least this many rows (when there are that many)
+__global__ __launch_bounds__(256) void gather_rows_flat(
+    const u128 *__restrict__ Kpool, const u128 *__restrict__ Vpool, const int32_t *__restrict__ sel_idx,
+    const int32_t *__restrict__ sel_cnt, u128 *__restrict__ K_sel, u128 *__restrict__ V_sel, int N_cap,
+    int stride, int U, int BH) {
+  extern __shared__ int pre[];          // pre[i] = rows of lists 0..i-1, i <= BH
+  __shared__ int wave_tot[4];
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  // inclusive prefix sum of the clamped counts: each thread owns a run of consecutive lists
+  const int per = (BH + 255) / 256;
+  const int i0 = tid * per;
+  int run = 0;
+  for (int i = i0; i < min(BH, i0 + per); ++i) {
+    run += min(sel_cnt[i], stride);
+    pre[i + 1] = run;                    // local to the thread's run for now
+  }
+  int incl = wave_incl_scan(run, lane);
+  if (lane == 63) wave_tot[w] = incl;
+  __syncthreads();
+  int offset = incl - run;
+  for (int k = 0; k < w; ++k) offset += wave_tot[k];
+  for (int i = i0; i < min(BH, i0 + per); ++i) pre[i + 1] += offset;
+  if (tid == 0) pre[0] = 0;
+  __syncthreads();
+  const long T = pre[BH];
+  const int G = gridDim.x, g = blockIdx.x;
+  long per_wg = (T + G - 1) / G;
+  if (per_wg < GATHER_MIN_ROWS) per_wg = GATHER_MIN_ROWS;
+  const long r0 = (long)g * per_wg, r1 = min(T, r0 + per_wg);
+  if (r0 >= r1) return;
+  const long total = (r1 - r0) * U;
+  int top = 1;
+  while (top * 2 < BH) top *= 2;
+  for (long u0 = tid; u0 < total; u0 += 256 * GATHER_BATCH) {
+    u128 kv[GATHER_BATCH], vv[GATHER_BATCH];
+    long src[GATHER_BATCH], dst[GATHER_BATCH];
+#pragma unroll
+    for (int i = 0; i < GATHER_BATCH; ++i) {
+      const long u = min(u0 + 256 * i, total - 1);   // past the end: the last unit again (same bytes)
+      const int row = (int)(r0 + u / U), c = (int)(u % U);
+      // list of this row: the last bh with pre[bh] <= row (fixed trip count, so the searches of a
+      // batch interleave)
+      int lo = 0;
+      for (int step = top; step >= 1; step >>= 1) {
+        const int cand = lo + step;
+        if (cand < BH && pre[cand] <= row) lo = cand;
+      }
+      const int j = row - pre[lo];
+      const long t = sel_idx[(long)lo * stride + j];
+      src[i] = ((long)lo * N_cap + t) * U + c;
+      dst[i] = ((long)lo * stride + j) * U + c;
+    }
+#pragma unroll
+    for (int i = 0; i < GATHER_BATCH; ++i) {
+      kv[i] = Kpool[src[i]];
+      vv[i] = Vpool[src[i]];
+    }
+#pragma unroll
+    for (int i = 0; i < GATHER_BATCH; ++i) {
+      K_sel[dst[i]] = kv[i];
+      V_sel[dst[i]] = vv[i];
     }
   }
 }
@@ -361,13 +437,33 @@ int ig_launch_slab_build(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const
 
 int ig_launch_gather(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const void *Vpool,
                      const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt,
-                     void *K_sel, void *V_sel, hipStream_t s) {
+                     void *K_sel, void *V_sel, int host_pool, hipStream_t s) {
   const int U = d->d * ig_elem_bytes(d->dtype) / 16;
   const int BH = d->B * d->H;
-  dim3 grid(BH * SLICE_MAX), block(256);
-  auto k = gather_rows;
-  IG_LAUNCH(ctx, IG_K_GATHER, k, grid, block, s, (const u128 *)Kpool, (const u128 *)Vpool, sel_idx,
-            sel_cnt, (u128 *)K_sel, (u128 *)V_sel, (int)d->N_cap, (int)sel_stride, U, (int)d->H, BH);
+  if (!host_pool) {
+    dim3 grid(BH * SLICE_MAX), block(256);
+    auto k = gather_rows_sliced;
+    IG_LAUNCH(ctx, IG_K_GATHER, k, grid, block, s, (const u128 *)Kpool, (const u128 *)Vpool, sel_idx,
+              sel_cnt, (u128 *)K_sel, (u128 *)V_sel, (int)d->N_cap, (int)sel_stride, U, (int)d->H, BH);
+    return IG_OK;
+  }
+  const size_t lds = (size_t)(BH + 1) * sizeof(int);
+  if (lds > 60 * 1024) return ig_fail(ctx, IG_ESHAPE, "host gather: B*H = %d exceeds %d", BH, 60 * 256 - 1);
+  dim3 grid(128), block(256);
+  auto k = gather_rows_flat;
+  if (ctx->profiling) {
+    hipEvent_t e0, e1;
+    ig_prof_events(ctx, IG_K_GATHER, &e0, &e1);
+    hipExtLaunchKernelGGL(k, grid, block, (unsigned)lds, s, e0, e1, 0, (const u128 *)Kpool,
+                          (const u128 *)Vpool, sel_idx, sel_cnt, (u128 *)K_sel, (u128 *)V_sel,
+                          (int)d->N_cap, (int)sel_stride, U, BH);
+  } else {
+    hipLaunchKernelGGL(k, grid, block, (unsigned)lds, s, (const u128 *)Kpool, (const u128 *)Vpool,
+                       sel_idx, sel_cnt, (u128 *)K_sel, (u128 *)V_sel, (int)d->N_cap, (int)sel_stride,
+                       U, BH);
+  }
+  hipError_t le = hipGetLastError();
+  if (le != hipSuccess) return ig_hip_fail(ctx, le, "gather_rows_flat");
   return IG_OK;
 }
 

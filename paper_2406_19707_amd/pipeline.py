@@ -127,11 +127,25 @@ class Rehearsal:
         self.space = ig.IG_MEM_HOST_PINNED if self.host_pool else ig.IG_MEM_DEVICE
         BH = w.B * w.H
         self.stride = w.N
-        self.sel_idx = torch.zeros((BH, self.stride), dtype=torch.int32, device=dev)
-        self.sel_cnt = torch.zeros((BH,), dtype=torch.int32, device=dev)
-        self.K_sel = torch.zeros((BH, self.stride, w.d), dtype=tdt, device=dev)
-        self.V_sel = torch.zeros((BH, self.stride, w.d), dtype=tdt, device=dev)
+        # result buffers; a host pool is pipelined over two sets (rehearsal of layer l+1 runs while the
+        # rows of layer l are still crossing PCIe)
+        self.n_sets = 2 if self.host_pool else 1
+        self.sets = []
+        for _ in range(self.n_sets):
+            self.sets.append(dict(
+                sel_idx=torch.zeros((BH, self.stride), dtype=torch.int32, device=dev),
+                sel_cnt=torch.zeros((BH,), dtype=torch.int32, device=dev),
+                K_sel=torch.zeros((BH, self.stride, w.d), dtype=tdt, device=dev),
+                V_sel=torch.zeros((BH, self.stride, w.d), dtype=tdt, device=dev)))
+        self._use(0)
         self.out = torch.zeros((w.B, w.H, w.d), dtype=tdt, device=dev)
+        if self.host_pool:
+            self.side_ctx = ig.Context(0)          # the side stream gets its own context
+            self.side = torch.cuda.Stream()
+
+    def _use(self, i):
+        st = self.sets[i % self.n_sets]
+        self.sel_idx, self.sel_cnt, self.K_sel, self.V_sel = st["sel_idx"], st["sel_cnt"], st["K_sel"], st["V_sel"]
 
     # ---- hot path ----
     def speculate(self, l, scores=None):
@@ -163,11 +177,60 @@ class Rehearsal:
         for l in range(self.L):
             self.layer(l)
 
+    def step_without_gather(self):
+        """Main-stream work of a host-pool step alone: rehearsal + attention on whatever was fetched."""
+        for l in range(self.L):
+            self._use(l)
+            self.speculate(l)
+            self.attend(l)
+
+    def step_gather_only(self):
+        """Side-stream work of a host-pool step alone (lists as left by the last rehearsals)."""
+        for l in range(self.L):
+            self._use(l)
+            p = l % self.n_pool
+            self.side_ctx.ig_gather_kv(self.desc, self.K[p], self.V[p], self.space, self.sel_idx,
+                                       self.stride, self.sel_cnt, self.K_sel, self.V_sel, self.side)
+
     def step_fused_attention(self):
         """Variant for an HBM-resident pool: the index lists are applied inside the attention."""
         for l in range(self.L):
             self.speculate(l)
             self.attend_indexed(l)
+
+    def step_overlapped(self):
+        """Host-pool decode step (Fig. 3(d)): the rows of layer l are prefetched over PCIe on a side
+        stream while the main stream already rehearses layer l+1 and attends layer l-1."""
+        main = torch.cuda.current_stream()
+        ev_spec = [None] * self.L
+        ev_gath = [None] * self.L
+        ev_attn = [None] * self.L
+        for l in range(self.L + 1):
+            if l < self.L:
+                self._use(l)
+                # the lists of this set are free: the attention that read them was enqueued earlier
+                self.speculate(l)
+                ev_spec[l] = torch.cuda.Event()
+                ev_spec[l].record(main)
+                self.side.wait_event(ev_spec[l])
+                if l >= self.n_sets:
+                    self.side.wait_event(ev_attn[l - self.n_sets])   # K_sel/V_sel set is free again
+                p = l % self.n_pool
+                self.side_ctx.ig_gather_kv(self.desc, self.K[p], self.V[p], self.space, self.sel_idx,
+                                           self.stride, self.sel_cnt, self.K_sel, self.V_sel, self.side)
+                ev_gath[l] = torch.cuda.Event()
+                ev_gath[l].record(self.side)
+            if l >= 1:
+                self._use(l - 1)
+                main.wait_event(ev_gath[l - 1])
+                self.attend(l - 1)
+                ev_attn[l - 1] = torch.cuda.Event()
+                ev_attn[l - 1].record(main)
+
+    def gathered_bytes(self) -> int:
+        """Bytes the prefetch of the layer whose lists are current moves (K and V rows)."""
+        w = self.w
+        return int(self.sel_cnt.sum().item()) * 2 * w.d * (4 if w.dtype == "f32" else 2)
 
     def scan_bytes(self) -> int:
         """Algorithmic bytes of one partial-K scan: 2*B*H*N*r (elements actually needed)."""
