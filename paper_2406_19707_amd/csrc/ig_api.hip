@@ -119,6 +119,9 @@ int reserve_for(ig_ctx *ctx, const ig_desc *d, bool scores) {
     if (rc) return rc;
     rc = ig_ensure(ctx, (void **)&ctx->tmax, &ctx->tmax_bytes, (size_t)d->B * d->H * nTiles * sizeof(float));
     if (rc) return rc;
+    rc = ig_ensure(ctx, (void **)&ctx->pcount, &ctx->pcount_bytes,
+                   (size_t)d->B * d->H * ((d->N + 4095) / 4096) * sizeof(int32_t));
+    if (rc) return rc;
     rc = ig_ensure(ctx, (void **)&ctx->attn_part, &ctx->attn_part_bytes,
                    (size_t)d->B * d->H * IG_SLICE_MAX * (d->d + 2) * sizeof(float));
     if (rc) return rc;
@@ -143,6 +146,8 @@ int ig_create(int device, ig_ctx **out) {
   ctx->err[0] = 0;
   ctx->part = ctx->qp = ctx->scores = ctx->tmax = ctx->attn_part = nullptr;
   ctx->attn_cnt = nullptr;
+  ctx->pcount = nullptr;
+  ctx->pcount_bytes = 0;
   ctx->attn_part_bytes = ctx->attn_cnt_bytes = 0;
   ctx->part_bytes = ctx->qp_bytes = ctx->scores_bytes = ctx->tmax_bytes = 0;
   ctx->status = nullptr;
@@ -171,6 +176,7 @@ int ig_destroy(ig_ctx *ctx) {
   if (ctx->qp) (void)hipFree(ctx->qp);
   if (ctx->scores) (void)hipFree(ctx->scores);
   if (ctx->tmax) (void)hipFree(ctx->tmax);
+  if (ctx->pcount) (void)hipFree(ctx->pcount);
   if (ctx->attn_part) (void)hipFree(ctx->attn_part);
   if (ctx->attn_cnt) (void)hipFree(ctx->attn_cnt);
   if (ctx->status) (void)hipFree(ctx->status);

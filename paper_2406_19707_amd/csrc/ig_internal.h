@@ -60,6 +60,7 @@ struct ig_ctx {
   float *qp;        size_t qp_bytes;      // finalised partial queries [B,H,r]
   float *scores;    size_t scores_bytes;  // long-sequence path: s [B*H, N]
   float *tmax;      size_t tmax_bytes;    // long-sequence path: per-tile maxima [B*H, nTiles]
+  int32_t *pcount;  size_t pcount_bytes;  // long-sequence path: kept tokens per 4096-token part
   float *attn_part; size_t attn_part_bytes;  // attention: per-slice softmax states [B*H][16][d+2]
   int32_t *attn_cnt; size_t attn_cnt_bytes;  // attention: per-(b,h) arrival counters, zero between calls
   int32_t *status;                        // device status word (sticky flags)
@@ -162,6 +163,12 @@ __device__ __forceinline__ int wave_incl_scan(int v, int lane) {
     int u = __shfl_up(v, o, 64);
     if (lane >= o) v += u;
   }
+  return v;
+}
+// sum over the 64 lanes, returned in every lane
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) v += __shfl_xor(v, o, 64);
   return v;
 }
 // number of lanes below this one whose predicate is set, and the wave's total

@@ -176,24 +176,25 @@ __global__ __launch_bounds__(256) void finalize_query(const float *__restrict__ 
                                                       float theta) {
   __shared__ float q[512];
   __shared__ float qr[512];
+  __shared__ float psum[256];
   const int bh = blockIdx.x, b = bh / H, h = bh % H;
   const int t = threadIdx.x;
-  if (!rope) {
-    for (int j = t; j < r; j += blockDim.x) {
-      float acc = bias ? bias[h * r + j] : 0.f;
-      for (int s = 0; s < KS; ++s) acc += part[s * ks_stride + (long)b * Cpad + h * r + j];
-      q_p[(long)bh * r + j] = acc;
-    }
-    return;
+  const int width = rope ? d : r;          // columns of this head in the partial-sum buffer
+  // split-K partial sums: all loads of a column issued together, added in a fixed order
+  for (int c = t; c < width; c += 256) {
+    const float *p = part + (long)b * Cpad + (long)h * width + c;
+    float v[IG_KS_MAX];
+#pragma unroll
+    for (int s = 0; s < IG_KS_MAX; ++s) v[s] = (s < KS) ? p[s * ks_stride] : 0.f;
+    float acc = bias ? bias[h * width + c] : 0.f;
+#pragma unroll
+    for (int s = 0; s < IG_KS_MAX; ++s) acc += v[s];
+    if (rope) q[c] = acc; else q_p[(long)bh * r + c] = acc;
   }
-  for (int c = t; c < d; c += blockDim.x) {
-    float acc = bias ? bias[h * d + c] : 0.f;
-    for (int s = 0; s < KS; ++s) acc += part[s * ks_stride + (long)b * Cpad + h * d + c];
-    q[c] = acc;
-  }
+  if (!rope) return;
   __syncthreads();
   const int half = d / 2;
-  for (int c = t; c < half; c += blockDim.x) {
+  for (int c = t; c < half; c += 256) {
     double ang = (double)pos[b] * exp2(-2.0 * (double)c / (double)d * log2((double)theta));
     double sn, cs;
     sincos(ang, &sn, &cs);
@@ -202,11 +203,25 @@ __global__ __launch_bounds__(256) void finalize_query(const float *__restrict__ 
     qr[c + half] = (float)((double)bb * cs + (double)a * sn);
   }
   __syncthreads();
-  for (int k = t; k < r; k += blockDim.x) {
-    float acc = 0.f;
+  // q_p[k] = sum_c qr[c] * A_p[h][c][k]: the 256 threads are G groups of RK; group g sums its share
+  // of the rows c for output k (reads of A_p coalesce over k), then the groups are added in order
+  const int RK = r <= 64 ? 64 : (r <= 128 ? 128 : 256);
+  const int G = 256 / RK;
+  const int k = t % RK, g = t / RK;
+  const int per = (d + G - 1) / G;
+  float acc = 0.f;
+  if (k < r) {
     const float *ap = A_p + (long)h * d * r + k;
-    for (int c = 0; c < d; ++c) acc = fmaf(qr[c], ap[(long)c * r], acc);
-    q_p[(long)bh * r + k] = acc;
+    const int c1 = min(d, (g + 1) * per);
+#pragma unroll 8
+    for (int c = g * per; c < c1; ++c) acc = fmaf(qr[c], ap[(long)c * r], acc);
+  }
+  psum[t] = acc;
+  __syncthreads();
+  if (t < r) {
+    float tot = 0.f;
+    for (int gg = 0; gg < G; ++gg) tot += psum[gg * RK + t];
+    q_p[(long)bh * r + t] = tot;
   }
 }
 

@@ -216,7 +216,7 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
 }
 
 // Long sequences / few heads: one wave per tile, 4 tiles per workgroup; scores and per-tile maxima
-// go to a buffer, and select_scores does the threshold pass.
+// go to a buffer, and select_count / select_write do the threshold pass.
 template <typename T, int CH>
 __global__ __launch_bounds__(256) void scan_tiles(ScanArgs a) {
   constexpr int TPL = Elem<T>::TPL;
@@ -242,13 +242,14 @@ __global__ __launch_bounds__(256) void scan_tiles(ScanArgs a) {
   if (lane == 0) a.tmax[(long)bh * a.nTiles + tileno] = m;
 }
 
-// Threshold + compaction from the score buffer: one workgroup of 16 waves per (b,h).
-__global__ __launch_bounds__(1024) void select_scores(ScanArgs a) {
-  constexpr int NW = 16, TPL = 4;
-  __shared__ float lds_max[NW];
-  __shared__ int lds_cnt[NW];
-  const int bh = blockIdx.x;
-  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+// Threshold + compaction from the score buffer, for sequences too long for one workgroup.  The
+// tokens of a (b,h) are cut into parts of SELECT_PART tokens, one workgroup of 16 waves each, so
+// that a long sequence is spread over many compute units.  select_count computes the threshold
+// from the per-tile maxima and counts the kept tokens of each part; select_write adds up the
+// counts of the preceding parts (a handful of values) and writes its part of the ascending list.
+constexpr int SELECT_PART = 4096;   // 1024 threads x 4 tokens
+
+__device__ __forceinline__ float select_threshold(const ScanArgs &a, int bh, float *lds_max, int w, int lane) {
   float m = -INFINITY;
   for (int k = threadIdx.x; k < a.nTiles; k += 1024) m = fmaxf(m, a.tmax[(long)bh * a.nTiles + k]);
   m = wave_max(m);
@@ -256,24 +257,66 @@ __global__ __launch_bounds__(1024) void select_scores(ScanArgs a) {
   __syncthreads();
   float mm = lds_max[0];
 #pragma unroll
-  for (int k = 1; k < NW; ++k) mm = fmaxf(mm, lds_max[k]);
-  const float thr = mm - a.alpha;
+  for (int k = 1; k < 16; ++k) mm = fmaxf(mm, lds_max[k]);
+  return mm - a.alpha;
+}
+
+__device__ __forceinline__ void select_load(const ScanArgs &a, int bh, int t0, int lane, float (&sc)[4]) {
   const float *s = a.scores_out + (long)bh * a.N;
-  int base = 0;
-  for (int c0 = 0; c0 < a.N; c0 += 1024 * TPL) {
-    const int t0 = c0 + w * 64 * TPL;
-    float sc[TPL];
+  const int t = t0 + lane * 4;
+  if (t + 3 < a.N && (((long)bh * a.N + t) & 3) == 0) {
+    const floatx4 v = *reinterpret_cast<const floatx4 *>(s + t);
 #pragma unroll
-    for (int e = 0; e < TPL; ++e) {
-      int t = t0 + lane * TPL + e;
-      sc[e] = (t < a.N) ? s[t] : -INFINITY;
-    }
-    base += compact_block<TPL, NW>(sc, t0, a.N, thr, base, a.sel_idx + (long)bh * a.sel_stride,
-                                   a.sel_stride, lds_cnt, w, lane);
+    for (int e = 0; e < 4; ++e) sc[e] = v[e];
+  } else {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) sc[e] = (t + e < a.N) ? s[t + e] : -INFINITY;
   }
+}
+
+__global__ __launch_bounds__(1024) void select_count(ScanArgs a, int32_t *pcount, int nParts) {
+  __shared__ float lds_max[16];
+  __shared__ int lds_cnt[16];
+  const int part = blockIdx.x, bh = blockIdx.y;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int t0 = part * SELECT_PART + w * 256;
+  float sc[4];
+  select_load(a, bh, t0, lane, sc);
+  const float thr = select_threshold(a, bh, lds_max, w, lane);
+  int total = 0;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const int t = t0 + lane * 4 + e;
+    total += __popcll(__ballot(t < a.N && sc[e] >= thr));
+  }
+  if (lane == 0) lds_cnt[w] = total;
+  __syncthreads();
   if (threadIdx.x == 0) {
-    a.sel_cnt[bh] = min(base, a.sel_stride);
-    if (base > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
+    int all = 0;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) all += lds_cnt[k];
+    pcount[(long)bh * nParts + part] = all;
+  }
+}
+
+__global__ __launch_bounds__(1024) void select_write(ScanArgs a, const int32_t *pcount, int nParts) {
+  __shared__ float lds_max[16];
+  __shared__ int lds_cnt[16];
+  const int part = blockIdx.x, bh = blockIdx.y;
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int t0 = part * SELECT_PART + w * 256;
+  float sc[4];
+  select_load(a, bh, t0, lane, sc);
+  int base = 0;
+  for (int p = lane; p < part; p += 64) base += pcount[(long)bh * nParts + p];
+  base = wave_sum(base);
+  const float thr = select_threshold(a, bh, lds_max, w, lane);
+  const int mine = compact_block<4, 16>(sc, t0, a.N, thr, base, a.sel_idx + (long)bh * a.sel_stride,
+                                        a.sel_stride, lds_cnt, w, lane);
+  if (part == nParts - 1 && threadIdx.x == 0) {
+    const int all = base + mine;
+    a.sel_cnt[bh] = min(all, a.sel_stride);
+    if (all > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
   }
 }
 
@@ -333,8 +376,13 @@ int launch_tiles(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
     default: return ig_fail(ctx, IG_ESHAPE, "scan: unsupported channel block %d", ch);
   }
 #undef CASE
-  auto k2 = select_scores;
-  IG_LAUNCH(ctx, IG_K_SELECT, k2, dim3(BH), dim3(1024), s, a);
+  const int nParts = (a.N + SELECT_PART - 1) / SELECT_PART;
+  int rc = ig_ensure(ctx, (void **)&ctx->pcount, &ctx->pcount_bytes, (size_t)BH * nParts * sizeof(int32_t));
+  if (rc) return rc;
+  auto k2 = select_count;
+  IG_LAUNCH(ctx, IG_K_SELECT, k2, dim3(nParts, BH), dim3(1024), s, a, ctx->pcount, nParts);
+  auto k3 = select_write;
+  IG_LAUNCH(ctx, IG_K_SELECT, k3, dim3(nParts, BH), dim3(1024), s, a, (const int32_t *)ctx->pcount, nParts);
   return IG_OK;
 }
 
@@ -344,13 +392,22 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
   const int nTiles = a.nTiles;
   // Fused when a (b,h) fits one workgroup and there are enough (b,h) pairs to fill the chip;
   // otherwise one wave per tile so that long sequences spread over all compute units.
-  const bool fused = nTiles <= 16 && (BH >= 128 || nTiles <= 4);
+  bool fused = nTiles <= 16 && (BH >= 128 || nTiles <= 4);
+#ifdef IG_EXPERIMENT
+  const int cap_o = getenv("IG_CAP") ? atoi(getenv("IG_CAP")) : 0;
+  if (getenv("IG_FORCE_TILED")) fused = false;
+  if (fused && cap_o) {
+    if (nTiles <= 4) return launch_fused<T, 4>(ctx, a, BH, pick_ch(d->r, cap_o), s);
+    if (nTiles <= 8) return launch_fused<T, 8>(ctx, a, BH, pick_ch(d->r, cap_o), s);
+    return launch_fused<T, 16>(ctx, a, BH, pick_ch(d->r, cap_o), s);
+  }
+#endif
   if (fused) {
     // When all workgroups fit on the chip at once (one round) a wave should have all its channels
     // in flight; with several rounds, smaller blocks leave room for more resident workgroups whose
     // load and select phases then overlap (measured: 60 % -> 71 % of HBM peak at 1120 workgroups).
     if (nTiles <= 4) return launch_fused<T, 4>(ctx, a, BH, pick_ch(d->r, BH > 512 ? 20 : 40), s);
-    if (nTiles <= 8) return launch_fused<T, 8>(ctx, a, BH, pick_ch(d->r, 24), s);
+    if (nTiles <= 8) return launch_fused<T, 8>(ctx, a, BH, pick_ch(d->r, 16), s);
     return launch_fused<T, 16>(ctx, a, BH, pick_ch(d->r, 12), s);
   }
   size_t need_s = (size_t)BH * d->N * sizeof(float), need_m = (size_t)BH * nTiles * sizeof(float);
@@ -363,6 +420,9 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
   int rc = ig_ensure(ctx, (void **)&ctx->tmax, &ctx->tmax_bytes, need_m);
   if (rc) return rc;
   a.tmax = ctx->tmax;
+#ifdef IG_EXPERIMENT
+  if (cap_o) return launch_tiles<T>(ctx, a, BH, pick_ch(d->r, cap_o), s);
+#endif
   return launch_tiles<T>(ctx, a, BH, pick_ch(d->r, 40), s);
 }
 

@@ -1,0 +1,100 @@
+"""GPU parity at the benchmark's full size (configs[1]: B8 H32 d128 N2048 r38, f16 KV, HBM pool), in
+the launch configuration bench.py times: the oracle checks sampled (sequence, head) pairs one by
+one, and properties that hold at any size are checked on every pair."""
+import numpy as np
+import pytest
+import torch
+
+import ig_workloads as wl
+from oracle import ig_oracle as o
+
+pytestmark = pytest.mark.gpu
+
+
+def test_cfg2_full_size_sampled_pairs_and_properties():
+    import paper_2406_19707_amd as ig
+    w = wl.WORKLOADS[2]
+    print(f"full-size case {w.name}: B{w.B} H{w.H} d{w.d} N{w.N}", flush=True)
+    # ---- setup on the oracle side (inputs flow oracle -> HIP path) ----
+    Wq = wl.projection_weight(w, "Wq")
+    Xcal = wl.calibration_input(w)
+    Qcal = Xcal @ Wq
+    sk = o.skew(Wq, None, Qcal, w.H)
+    idx = o.partial_index(o.apply_skew(Qcal, sk["A"]), None, w.H, w.ratio)
+    r = idx.shape[1]
+    W16 = wl.quantise(sk["Wq_s"], w)
+    x16 = wl.quantise(wl.attention_input(w), w)
+    K, V = wl.kv_cache(w)                          # keys drawn directly in the skewed basis
+    K16, V16 = wl.quantise(K, w), wl.quantise(V, w)
+    del K, V
+    xn = wl.next_layer_input(w, x16.astype(np.float32))
+    q16 = wl.quantise((xn @ W16.astype(np.float32)).reshape(w.B, w.H, w.d), w)
+    scale = w.gain / np.sqrt(w.d)
+    print("  oracle setup done", flush=True)
+
+    # ---- HIP path, as the benchmark launches it ----
+    ctx = ig.Context(0)
+    d = ig.IgDesc(B=w.B, H=w.H, d=w.d, r=r, N=w.N, dtype=ig.IG_F16, scale=scale, alpha=w.alpha)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()   # noqa: E731
+    x, W, idxd, Kd, Vd, qd = dev(x16), dev(W16), dev(idx), dev(K16), dev(V16), dev(q16)
+    wq = torch.empty(ig.ig_wq_bytes(d), dtype=torch.uint8, device="cuda")
+    slab = torch.empty(ig.ig_slab_bytes(d), dtype=torch.uint8, device="cuda")
+    ctx.ig_wq_build(d, W, idxd, wq)
+    ctx.ig_slab_build(d, Kd, ig.IG_MEM_DEVICE, idxd, slab)
+    BH = w.B * w.H
+    sel_idx = torch.full((BH, w.N), -1, dtype=torch.int32, device="cuda")
+    sel_cnt = torch.zeros(BH, dtype=torch.int32, device="cuda")
+    scores = torch.zeros((w.B, w.H, w.N), device="cuda")
+    K_sel = torch.zeros((BH, w.N, w.d), dtype=torch.float16, device="cuda")
+    V_sel = torch.zeros_like(K_sel)
+    out = torch.zeros((w.B, w.H, w.d), dtype=torch.float16, device="cuda")
+    out_idx = torch.zeros_like(out)
+    ctx.ig_speculate(d, x, wq, None, None, None, slab, sel_idx, w.N, sel_cnt, scores)
+    ctx.ig_gather_kv(d, Kd, Vd, ig.IG_MEM_DEVICE, sel_idx, w.N, sel_cnt, K_sel, V_sel)
+    ctx.ig_sparse_attention(d, qd, K_sel, V_sel, sel_cnt, w.N, None, None, out)
+    ctx.ig_sparse_attention_indexed(d, qd, Kd, Vd, sel_idx, w.N, sel_cnt, None, None, out_idx)
+    torch.cuda.synchronize()
+    assert ctx.ig_check_status() == ig.IG_OK
+    g_idx, g_cnt = sel_idx.cpu().numpy(), sel_cnt.cpu().numpy()
+    g_s = scores.cpu().numpy().reshape(BH, w.N)
+    g_out = out.float().cpu().numpy().reshape(BH, w.d)
+    g_out_idx = out_idx.float().cpu().numpy().reshape(BH, w.d)
+    g_K = K_sel.cpu().numpy()
+    print(f"  GPU done: selected fraction {g_cnt.mean() / w.N:.4f}, max list {g_cnt.max()}", flush=True)
+
+    # ---- properties on every pair ----
+    K2 = K16.reshape(BH, w.N, w.d)
+    for i in range(BH):
+        n = g_cnt[i]
+        lst = g_idx[i, :n]
+        assert n >= 1 and np.all(np.diff(lst) > 0) and lst[0] >= 0 and lst[-1] < w.N
+        thr = np.float32(g_s[i].max()) - np.float32(w.alpha)
+        keep = np.zeros(w.N, bool)
+        keep[lst] = True
+        assert int(np.argmax(g_s[i])) in lst                      # the argmax is always kept
+        assert np.all(g_s[i][keep] >= thr) and np.all(g_s[i][~keep] < thr)   # exactly the threshold set
+        assert np.array_equal(g_K[i, :n], K2[i, lst])             # gathered rows are bit-exact copies
+    assert np.all(np.abs(g_out - g_out_idx) <= 2e-3 + 1e-2 * np.abs(g_out))   # both attention forms agree
+
+    # ---- oracle on sampled pairs ----
+    q_p = o.project(x16.astype(np.float32), W16.astype(np.float32), idx)
+    rng = np.random.default_rng(5)
+    heavy = np.argsort(g_cnt)[-3:]                                  # the longest lists, plus random pairs
+    sample = sorted(set(heavy.tolist()) | set(rng.choice(BH, 9, replace=False).tolist()))
+    for i in sample:
+        b, h = divmod(i, w.H)
+        Kt = K16[b, h].astype(np.float32)[None, None]
+        Vt = V16[b, h].astype(np.float32)[None, None]
+        s = o.scan(q_p[b:b + 1, h:h + 1], Kt, idx[h:h + 1], scale)
+        assert np.abs(s[0, 0] - g_s[i]).max() <= 1e-4 * max(1.0, np.abs(s).max())
+        r_idx, r_cnt = o.select(s, w.alpha)
+        diff = np.setxor1d(g_idx[i, :g_cnt[i]], r_idx[0, :r_cnt[0]])
+        if diff.size:
+            thr = np.float32(s.max()) - np.float32(w.alpha)
+            assert np.all(np.abs(s[0, 0, diff] - thr) <= 1e-3), (i, diff)
+            continue
+        Ks, Vs = o.gather(Kt, r_idx, r_cnt), o.gather(Vt, r_idx, r_cnt)
+        ref = o.attend(q16[b, h].astype(np.float32)[None], Ks, Vs, r_cnt, scale)[0]
+        assert np.all(np.abs(g_out[i] - ref) <= 2e-2 + 1e-2 * np.abs(ref)), (i, np.abs(g_out[i] - ref).max())
+    print(f"  oracle agrees on pairs {sample}", flush=True)
+    ctx.close()
