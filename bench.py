@@ -147,26 +147,39 @@ def main():
         fused_ms = timed(R.step_fused_attention, K)
 
     # ---- per-kernel durations from HIP events attached to the launches ----
-    prof_ctxs = [ctx] + ([R.side_ctx] if R.host_pool else [])
-    for c in prof_ctxs:
-        c.ig_profile_begin()
-    for _ in range(max(1, K // 4) if R.host_pool else K):
-        if R.host_pool:
-            R.step_overlapped()
-        else:
-            R.step()
-    for c in prof_ctxs:
-        c.ig_profile_end()
     names = {ig.IG_K_PROJECT: "project", ig.IG_K_FINALIZE: "finalize", ig.IG_K_SCAN: "scan",
              ig.IG_K_SELECT: "select", ig.IG_K_GATHER: "gather", ig.IG_K_ATTENTION: "attention"}
-    kernels = {}
-    for kid, name in names.items():
-        ms, n = 0.0, 0
-        for c in prof_ctxs:
-            m_, n_ = c.ig_profile_read(kid)
-            ms, n = ms + m_, n + n_
-        if n:
-            kernels[name] = {"avg_us": ms * 1e3 / n, "launches": n}
+
+    def profiled(fns, steps):
+        ctxs = [ctx] + ([R.side_ctx] if R.host_pool else [])
+        for c in ctxs:
+            c.ig_profile_begin()
+        for _ in range(steps):
+            for fn in fns:
+                fn()
+                torch.cuda.synchronize()   # one stream's work at a time
+        for c in ctxs:
+            c.ig_profile_end()
+        out = {}
+        for kid, name in names.items():
+            ms, n = 0.0, 0
+            for c in ctxs:
+                m_, n_ = c.ig_profile_read(kid)
+                ms, n = ms + m_, n + n_
+            if n:
+                out[name] = {"avg_us": ms * 1e3 / n, "launches": n}
+        return out
+
+    kernels_overlapped = None
+    if R.host_pool:
+        # each stream's kernels on their own (the roofline figures), then the overlapped pipeline
+        def gather_only():
+            with torch.cuda.stream(R.side):
+                R.step_gather_only()
+        kernels = profiled([R.step_without_gather, gather_only], max(1, K // 2))
+        kernels_overlapped = profiled([R.step_overlapped], max(1, K // 2))
+    else:
+        kernels = profiled([R.step], K)
     scan_us = kernels["scan"]["avg_us"]
     scan_bytes = R.scan_bytes()
     achieved = scan_bytes / (scan_us * 1e-6) / 1e9
@@ -270,6 +283,7 @@ def main():
         "fused_attention_eager_us_per_layer": None if fused_ms is None else fused_ms * 1e3 / L,
         "scan_GBps": achieved,
         "kernels": kernels,
+        "kernels_while_overlapped": kernels_overlapped,
         "literal_variant": literal,
         "roofline": {"kernel": "partial-K scan + max + threshold + compaction", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
