@@ -185,6 +185,15 @@ int ig_sparse_attention_indexed(ig_ctx *ctx, const ig_desc *desc, const void *q,
                                 const int32_t *sel_cnt, const void *k_new, const void *v_new,
                                 void *out, void *stream);
 
+/* Prefetch and attention in one pass over a device-resident pool (Section 4.1: the fetched rows
+ * are exactly the rows attention reads): every selected row is read from the pool once, written
+ * to K_sel / V_sel as ig_gather_kv would (same layout, rows j >= sel_cnt untouched) and used for
+ * the attention of ig_sparse_attention_indexed.  All pointers device memory. */
+int ig_gather_attention(ig_ctx *ctx, const ig_desc *desc, const void *q, const void *Kpool,
+                        const void *Vpool, const int32_t *sel_idx, int32_t sel_stride,
+                        const int32_t *sel_cnt, void *K_sel, void *V_sel, const void *k_new,
+                        const void *v_new, void *out, void *stream);
+
 /* ---- measurement --------------------------------------------------------------------------- */
 
 /* Between ig_profile_begin and ig_profile_end every kernel the context launches carries a pair of

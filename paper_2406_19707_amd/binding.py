@@ -31,7 +31,7 @@ EXPORTS = [
     "ig_create", "ig_destroy", "ig_last_error", "ig_reserve", "ig_check_status", "ig_skew_offline",
     "ig_partial_index", "ig_wq_bytes", "ig_wq_build", "ig_slab_bytes", "ig_slab_build",
     "ig_speculate", "ig_project", "ig_scan_select", "ig_gather_kv", "ig_sparse_attention",
-    "ig_sparse_attention_indexed", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
+    "ig_sparse_attention_indexed", "ig_gather_attention", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
     "ig_copy_bytes",
 ]
 
@@ -91,6 +91,7 @@ def lib():
             "ig_gather_kv": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_int, _vp, _i32, _vp, _vp, _vp, _vp]),
             "ig_sparse_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
             "ig_sparse_attention_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
+            "ig_gather_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
             "ig_profile_begin": (ctypes.c_int, [_vp]),
             "ig_profile_end": (ctypes.c_int, [_vp]),
             "ig_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
@@ -253,6 +254,13 @@ class Context:
                                                    _ptr(Kpool), _ptr(Vpool), _ptr(sel_idx),
                                                    sel_stride, _ptr(sel_cnt), _ptr(k_new),
                                                    _ptr(v_new), _ptr(out), _stream(stream)))
+
+    def ig_gather_attention(self, desc, q, Kpool, Vpool, sel_idx, sel_stride, sel_cnt, K_sel, V_sel,
+                            k_new, v_new, out, stream=None):
+        self._ck(lib().ig_gather_attention(self._h, ctypes.byref(desc), _ptr(q), _ptr(Kpool),
+                                           _ptr(Vpool), _ptr(sel_idx), sel_stride, _ptr(sel_cnt),
+                                           _ptr(K_sel), _ptr(V_sel), _ptr(k_new), _ptr(v_new),
+                                           _ptr(out), _stream(stream)))
 
     def ig_profile_begin(self):
         self._ck(lib().ig_profile_begin(self._h))

@@ -328,7 +328,7 @@ int ig_sparse_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
   if (sel_stride < 1) return ig_fail(ctx, IG_ESHAPE, "sel_stride = %d", sel_stride);
   if ((rc = set_device(ctx))) return rc;
   return ig_launch_attention(ctx, d, q, K_sel, V_sel, nullptr, sel_stride, sel_cnt, sel_stride, k_new,
-                             v_new, out, (hipStream_t)stream);
+                             v_new, out, nullptr, nullptr, (hipStream_t)stream);
 }
 
 int ig_sparse_attention_indexed(ig_ctx *ctx, const ig_desc *d, const void *q, const void *Kpool,
@@ -342,7 +342,22 @@ int ig_sparse_attention_indexed(ig_ctx *ctx, const ig_desc *d, const void *q, co
   if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
   if ((rc = set_device(ctx))) return rc;
   return ig_launch_attention(ctx, d, q, Kpool, Vpool, sel_idx, sel_stride, sel_cnt, d->N_cap, k_new,
-                             v_new, out, (hipStream_t)stream);
+                             v_new, out, nullptr, nullptr, (hipStream_t)stream);
+}
+
+int ig_gather_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void *Kpool,
+                        const void *Vpool, const int32_t *sel_idx, int32_t sel_stride,
+                        const int32_t *sel_cnt, void *K_sel, void *V_sel, const void *k_new,
+                        const void *v_new, void *out, void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!q || !Kpool || !Vpool || !K_sel || !V_sel || !out)
+    return ig_fail(ctx, IG_EINVAL, "ig_gather_attention: NULL argument");
+  if ((k_new == nullptr) != (v_new == nullptr)) return ig_fail(ctx, IG_EINVAL, "k_new and v_new go together");
+  if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
+  if ((rc = set_device(ctx))) return rc;
+  return ig_launch_attention(ctx, d, q, Kpool, Vpool, sel_idx, sel_stride, sel_cnt, d->N_cap, k_new,
+                             v_new, out, K_sel, V_sel, (hipStream_t)stream);
 }
 
 int ig_profile_begin(ig_ctx *ctx) {

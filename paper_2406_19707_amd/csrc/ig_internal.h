@@ -125,7 +125,7 @@ int ig_launch_gather(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const voi
 int ig_launch_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, const void *V,
                         const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt,
                         int kv_rows_per_bh, const void *k_new, const void *v_new, void *out,
-                        hipStream_t s);
+                        void *K_out, void *V_out, hipStream_t s);
 int ig_launch_copy(ig_ctx *ctx, const void *src, void *dst, size_t bytes, hipStream_t s);
 
 // ---- wave helpers -------------------------------------------------------------------------------

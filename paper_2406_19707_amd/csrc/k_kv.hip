@@ -134,15 +134,17 @@ __global__ __launch_bounds__(256) void gather_rows_sliced(
 // small: a hundred workgroups keep more than enough PCIe reads outstanding, and the compute units
 // stay free for the kernels of the other stream, which stalled rows would otherwise block.
 constexpr int GATHER_MIN_ROWS = 32;   // a workgroup takes at least this many rows (when there are that many)
-__global__ __launch_bounds__(256) void gather_rows_flat(
+template <int THREADS, int BATCH>
+__global__ __launch_bounds__(THREADS) void gather_rows_flat(
     const u128 *__restrict__ Kpool, const u128 *__restrict__ Vpool, const int32_t *__restrict__ sel_idx,
     const int32_t *__restrict__ sel_cnt, u128 *__restrict__ K_sel, u128 *__restrict__ V_sel, int N_cap,
     int stride, int U, int BH) {
   extern __shared__ int pre[];          // pre[i] = rows of lists 0..i-1, i <= BH
-  __shared__ int wave_tot[4];
+  constexpr int WAVES = THREADS / 64;
+  __shared__ int wave_tot[WAVES];
   const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
   // inclusive prefix sum of the clamped counts: each thread owns a run of consecutive lists
-  const int per = (BH + 255) / 256;
+  const int per = (BH + THREADS - 1) / THREADS;
   const int i0 = tid * per;
   int run = 0;
   for (int i = i0; i < min(BH, i0 + per); ++i) {
@@ -166,12 +168,12 @@ __global__ __launch_bounds__(256) void gather_rows_flat(
   const long total = (r1 - r0) * U;
   int top = 1;
   while (top * 2 < BH) top *= 2;
-  for (long u0 = tid; u0 < total; u0 += 256 * GATHER_BATCH) {
-    u128 kv[GATHER_BATCH], vv[GATHER_BATCH];
-    long src[GATHER_BATCH], dst[GATHER_BATCH];
+  for (long u0 = tid; u0 < total; u0 += THREADS * BATCH) {
+    u128 kv[BATCH], vv[BATCH];
+    long src[BATCH], dst[BATCH];
 #pragma unroll
-    for (int i = 0; i < GATHER_BATCH; ++i) {
-      const long u = min(u0 + 256 * i, total - 1);   // past the end: the last unit again (same bytes)
+    for (int i = 0; i < BATCH; ++i) {
+      const long u = min(u0 + THREADS * i, total - 1);   // past the end: the last unit again (same bytes)
       const int row = (int)(r0 + u / U), c = (int)(u % U);
       // list of this row: the last bh with pre[bh] <= row (fixed trip count, so the searches of a
       // batch interleave)
@@ -186,12 +188,12 @@ __global__ __launch_bounds__(256) void gather_rows_flat(
       dst[i] = ((long)lo * stride + j) * U + c;
     }
 #pragma unroll
-    for (int i = 0; i < GATHER_BATCH; ++i) {
+    for (int i = 0; i < BATCH; ++i) {
       kv[i] = Kpool[src[i]];
       vv[i] = Vpool[src[i]];
     }
 #pragma unroll
-    for (int i = 0; i < GATHER_BATCH; ++i) {
+    for (int i = 0; i < BATCH; ++i) {
       K_sel[dst[i]] = kv[i];
       V_sel[dst[i]] = vv[i];
     }
@@ -239,7 +241,8 @@ __global__ __launch_bounds__(256) void sparse_attention(
     const T *__restrict__ q, const u128 *__restrict__ K, const u128 *__restrict__ V,
     const int32_t *__restrict__ sel_idx, const int32_t *__restrict__ sel_cnt, int stride, int kv_rows,
     int LPR, const T *__restrict__ k_new, const T *__restrict__ v_new, T *__restrict__ out, float scale,
-    int d, float *part, int32_t *counters, int H, int BH) {
+    int d, float *part, int32_t *counters, int H, int BH, u128 *__restrict__ K_out,
+    u128 *__restrict__ V_out) {
   constexpr int TPL = Elem<T>::TPL;
   __shared__ float sm[4], sz[4];
   __shared__ float sacc[4][512];
@@ -291,6 +294,18 @@ __global__ __launch_bounds__(256) void sparse_attention(
       const u128 *vp = cached ? V + base + rowoff[i] * LPR + li : reinterpret_cast<const u128 *>(v_new + (long)bh * d) + li;
       kr[i] = *kp;
       vr[i] = *vp;
+    }
+    if (INDEXED && K_out) {
+      // fused prefetch: the rows just read from the pool are also the rows ig_gather_kv would copy
+#pragma unroll
+      for (int i = 0; i < ATT_BATCH; ++i) {
+        const int j = r0 + (i * 4 + w) * RPW + sub;
+        if (j < row1 && j < n) {
+          const long o = ((long)bh * stride + j) * LPR + li;
+          K_out[o] = kr[i];
+          V_out[o] = vr[i];
+        }
+      }
     }
     float l[ATT_BATCH];
     float bm = m;
@@ -449,29 +464,45 @@ int ig_launch_gather(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const voi
   }
   const size_t lds = (size_t)(BH + 1) * sizeof(int);
   if (lds > 60 * 1024) return ig_fail(ctx, IG_ESHAPE, "host gather: B*H = %d exceeds %d", BH, 60 * 256 - 1);
-  dim3 grid(128), block(256);
-  auto k = gather_rows_flat;
-  if (ctx->profiling) {
-    hipEvent_t e0, e1;
-    ig_prof_events(ctx, IG_K_GATHER, &e0, &e1);
-    hipExtLaunchKernelGGL(k, grid, block, (unsigned)lds, s, e0, e1, 0, (const u128 *)Kpool,
-                          (const u128 *)Vpool, sel_idx, sel_cnt, (u128 *)K_sel, (u128 *)V_sel,
-                          (int)d->N_cap, (int)sel_stride, U, BH);
-  } else {
-    hipLaunchKernelGGL(k, grid, block, (unsigned)lds, s, (const u128 *)Kpool, (const u128 *)Vpool,
-                       sel_idx, sel_cnt, (u128 *)K_sel, (u128 *)V_sel, (int)d->N_cap, (int)sel_stride,
-                       U, BH);
+  int wgs = 128, threads = 256, batch = 8;
+#ifdef IG_EXPERIMENT
+  if (getenv("IG_HG_WGS")) wgs = atoi(getenv("IG_HG_WGS"));
+  if (getenv("IG_HG_THREADS")) threads = atoi(getenv("IG_HG_THREADS"));
+  if (getenv("IG_HG_BATCH")) batch = atoi(getenv("IG_HG_BATCH"));
+#endif
+  dim3 grid(wgs), block(threads);
+#define HG_CASE(TH, BA)                                                                              \
+  if (threads == TH && batch == BA) {                                                               \
+    auto k = gather_rows_flat<TH, BA>;                                                              \
+    if (ctx->profiling) {                                                                           \
+      hipEvent_t e0, e1;                                                                            \
+      ig_prof_events(ctx, IG_K_GATHER, &e0, &e1);                                                   \
+      hipExtLaunchKernelGGL(k, grid, block, (unsigned)lds, s, e0, e1, 0, (const u128 *)Kpool,       \
+                            (const u128 *)Vpool, sel_idx, sel_cnt, (u128 *)K_sel, (u128 *)V_sel,   \
+                            (int)d->N_cap, (int)sel_stride, U, BH);                                 \
+    } else {                                                                                        \
+      hipLaunchKernelGGL(k, grid, block, (unsigned)lds, s, (const u128 *)Kpool, (const u128 *)Vpool, \
+                         sel_idx, sel_cnt, (u128 *)K_sel, (u128 *)V_sel, (int)d->N_cap,             \
+                         (int)sel_stride, U, BH);                                                   \
+    }                                                                                               \
+    hipError_t le = hipGetLastError();                                                              \
+    if (le != hipSuccess) return ig_hip_fail(ctx, le, "gather_rows_flat");                          \
+    return IG_OK;                                                                                   \
   }
-  hipError_t le = hipGetLastError();
-  if (le != hipSuccess) return ig_hip_fail(ctx, le, "gather_rows_flat");
-  return IG_OK;
+  HG_CASE(256, 8)
+#ifdef IG_EXPERIMENT
+  HG_CASE(256, 4) HG_CASE(256, 2) HG_CASE(256, 1)
+  HG_CASE(64, 8) HG_CASE(64, 4) HG_CASE(64, 2) HG_CASE(64, 1)
+#endif
+#undef HG_CASE
+  return ig_fail(ctx, IG_ESHAPE, "host gather: unsupported launch shape");
 }
 
 template <typename T>
 static int launch_attention_t(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K,
                               const void *V, const int32_t *sel_idx, int32_t sel_stride,
                               const int32_t *sel_cnt, int kv_rows, const void *k_new,
-                              const void *v_new, void *out, hipStream_t s) {
+                              const void *v_new, void *out, void *K_out, void *V_out, hipStream_t s) {
   const int LPR = d->d * (int)sizeof(T) / 16;
   const int BH = d->B * d->H;
   int rc = ig_ensure(ctx, (void **)&ctx->attn_part, &ctx->attn_part_bytes,
@@ -484,12 +515,14 @@ static int launch_attention_t(ig_ctx *ctx, const ig_desc *d, const void *q, cons
     auto k = sparse_attention<T, true>;
     IG_LAUNCH(ctx, IG_K_ATTENTION, k, grid, block, s, (const T *)q, (const u128 *)K, (const u128 *)V,
               sel_idx, sel_cnt, (int)sel_stride, kv_rows, LPR, (const T *)k_new, (const T *)v_new,
-              (T *)out, (float)d->scale, (int)d->d, ctx->attn_part, ctx->attn_cnt, (int)d->H, BH);
+              (T *)out, (float)d->scale, (int)d->d, ctx->attn_part, ctx->attn_cnt, (int)d->H, BH,
+              (u128 *)K_out, (u128 *)V_out);
   } else {
     auto k = sparse_attention<T, false>;
     IG_LAUNCH(ctx, IG_K_ATTENTION, k, grid, block, s, (const T *)q, (const u128 *)K, (const u128 *)V,
               sel_idx, sel_cnt, (int)sel_stride, kv_rows, LPR, (const T *)k_new, (const T *)v_new,
-              (T *)out, (float)d->scale, (int)d->d, ctx->attn_part, ctx->attn_cnt, (int)d->H, BH);
+              (T *)out, (float)d->scale, (int)d->d, ctx->attn_part, ctx->attn_cnt, (int)d->H, BH,
+              (u128 *)nullptr, (u128 *)nullptr);
   }
   return IG_OK;
 }
@@ -497,7 +530,7 @@ static int launch_attention_t(ig_ctx *ctx, const ig_desc *d, const void *q, cons
 int ig_launch_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, const void *V,
                         const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt,
                         int kv_rows_per_bh, const void *k_new, const void *v_new, void *out,
-                        hipStream_t s) {
+                        void *K_out, void *V_out, hipStream_t s) {
   const int row_bytes = d->d * ig_elem_bytes(d->dtype);
   const int LPR = row_bytes / 16;
   if (row_bytes % 16 || LPR < 1 || LPR > 64 || (LPR & (LPR - 1)))
@@ -505,9 +538,9 @@ int ig_launch_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
                    row_bytes);
   return d->dtype == IG_F16
              ? launch_attention_t<half_t>(ctx, d, q, K, V, sel_idx, sel_stride, sel_cnt,
-                                          kv_rows_per_bh, k_new, v_new, out, s)
+                                          kv_rows_per_bh, k_new, v_new, out, K_out, V_out, s)
              : launch_attention_t<float>(ctx, d, q, K, V, sel_idx, sel_stride, sel_cnt,
-                                         kv_rows_per_bh, k_new, v_new, out, s);
+                                         kv_rows_per_bh, k_new, v_new, out, K_out, V_out, s);
 }
 
 int ig_launch_copy(ig_ctx *ctx, const void *src, void *dst, size_t bytes, hipStream_t s) {

@@ -89,6 +89,14 @@ __device__ __forceinline__ void fma_block(const typename Elem<T>::vec (&v)[CH], 
                                           float (&acc)[Elem<T>::TPL]) {
   constexpr int TPL = Elem<T>::TPL;
   const int qbits = __float_as_int(qblk);
+#if defined(IG_EXPERIMENT) && defined(IGX_NOFMA)
+#pragma unroll
+  for (int j = 0; j < CH; ++j) {
+    const float qj = __int_as_float(__builtin_amdgcn_readlane(qbits, j));
+    acc[j % TPL] = fmaf((float)v[j][0], qj, acc[j % TPL]);
+  }
+  return;
+#endif
 #pragma unroll
   for (int j = 0; j < CH; ++j) {
     const float qj = __int_as_float(__builtin_amdgcn_readlane(qbits, j));
@@ -106,10 +114,16 @@ __device__ __forceinline__ void scan_tile(const ScanArgs &a, const T *tile, int 
 #pragma unroll
   for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
   QueryLoads ql;
+#if defined(IG_EXPERIMENT) && defined(IGX_NOQ)
+  load_block<T, CH>(tile, a.r, 0, lane, v);
+  float qv[4];
+  qv[0] = (lane < a.r ? 0.01f * (float)(lane - 19) : 0.f) * a.scale;
+#else
   query_issue(a, b, h, lane, 0, ql);
   load_block<T, CH>(tile, a.r, 0, lane, v);
   float qv[4];
   qv[0] = query_finish(a, ql);
+#endif
   qv[1] = qv[2] = qv[3] = 0.f;
   if (a.r <= CH) {           // the usual case: one block, lane l already holds channel l
     fma_block<T, CH>(v, qv[0], acc);
@@ -185,6 +199,16 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
 #pragma unroll
   for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
   if (active) scan_tile<T, CH>(a, tile, b, h, lane, acc);
+#if defined(IG_EXPERIMENT) && defined(IGX_STOP1)
+  {
+    float m1 = acc[0];
+#pragma unroll
+    for (int e = 1; e < TPL; ++e) m1 = fmaxf(m1, acc[e]);
+    m1 = wave_max(m1);
+    if (lane == 0) a.sel_idx[(long)bh * a.sel_stride + w] = __float_as_int(m1);
+    return;
+  }
+#endif
   const int t0 = w * TILE;
   float m = -INFINITY;
 #pragma unroll

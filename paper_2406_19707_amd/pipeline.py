@@ -129,7 +129,7 @@ class Rehearsal:
         self.stride = w.N
         # result buffers; a host pool is pipelined over two sets (rehearsal of layer l+1 runs while the
         # rows of layer l are still crossing PCIe)
-        self.n_sets = 2 if self.host_pool else 1
+        self.n_sets = 2
         self.sets = []
         for _ in range(self.n_sets):
             self.sets.append(dict(
@@ -139,9 +139,9 @@ class Rehearsal:
                 V_sel=torch.zeros((BH, self.stride, w.d), dtype=tdt, device=dev)))
         self._use(0)
         self.out = torch.zeros((w.B, w.H, w.d), dtype=tdt, device=dev)
-        if self.host_pool:
-            self.side_ctx = ig.Context(0)          # the side stream gets its own context
-            self.side = torch.cuda.Stream()
+        self.side_ctx = ig.Context(0)              # the side stream gets its own context
+        self.side_ctx.ig_reserve(self.desc)
+        self.side = torch.cuda.Stream()
 
     def _use(self, i):
         st = self.sets[i % self.n_sets]
@@ -165,6 +165,12 @@ class Rehearsal:
         p = l % self.n_pool
         self.ctx.ig_sparse_attention_indexed(self.desc, self.q[l], self.K[p], self.V[p], self.sel_idx,
                                              self.stride, self.sel_cnt, None, None, self.out)
+
+    def gather_attend(self, l):
+        p = l % self.n_pool
+        self.ctx.ig_gather_attention(self.desc, self.q[l], self.K[p], self.V[p], self.sel_idx,
+                                     self.stride, self.sel_cnt, self.K_sel, self.V_sel, None, None,
+                                     self.out)
 
     def layer(self, l):
         """Rehearsal, prefetch and sparse attention of one layer on the current stream."""
@@ -226,6 +232,40 @@ class Rehearsal:
                 self.attend(l - 1)
                 ev_attn[l - 1] = torch.cuda.Event()
                 ev_attn[l - 1].record(main)
+
+    def step_one_pass(self):
+        """HBM-pool decode step with prefetch and attention in one pass over the pool."""
+        for l in range(self.L):
+            self.speculate(l)
+            self.gather_attend(l)
+
+    def step_two_stream(self, one_pass=True):
+        """HBM-pool decode step with the rehearsal on a side stream (Fig. 3(d): the next layer is
+        speculated while the current one computes): the side stream runs ig_speculate of layer l+1
+        while the current stream gathers and attends layer l.  The index lists are double-buffered.
+        Works eagerly and under stream capture (the side stream forks from and joins the current
+        stream through events)."""
+        main = torch.cuda.current_stream()
+        side = self.side
+        side.wait_stream(main)
+        ev_attn = [None] * self.L
+        for l in range(self.L):
+            self._use(l)
+            if l >= self.n_sets:
+                side.wait_event(ev_attn[l - self.n_sets])    # this set's lists are free again
+            self.side_ctx.ig_speculate(self.desc, self.x[l], self.wq, None, self.A_p, self.pos,
+                                       self.slab[l], self.sel_idx, self.stride, self.sel_cnt, None, side)
+            ev = torch.cuda.Event()
+            ev.record(side)
+            main.wait_event(ev)
+            if one_pass:
+                self.gather_attend(l)
+            else:
+                self.gather(l)
+                self.attend(l)
+            ev_attn[l] = torch.cuda.Event()
+            ev_attn[l].record(main)
+        main.wait_stream(side)
 
     def gathered_bytes(self) -> int:
         """Bytes the prefetch of the layer whose lists are current moves (K and V rows)."""

@@ -66,8 +66,15 @@ def run_gpu(ctx, c, alpha=None, sel_stride=None, host_pool=False, want_scores=Tr
     ctx.ig_gather_kv(d, up.K, up.V, up.space, sel_idx, stride, sel_cnt, K_sel, V_sel)
     ctx.ig_sparse_attention(d, up.q, K_sel, V_sel, sel_cnt, stride, None, None, out)
     ctx.ig_sparse_attention(d, up.q, K_sel, V_sel, sel_cnt, stride, up.k_new, up.v_new, out_new)
+    out_one = torch.full_like(out, float("nan"))
+    out_one_new = torch.full_like(out, float("nan"))
+    K_one, V_one = torch.zeros_like(K_sel), torch.zeros_like(V_sel)
     if not host_pool:
         ctx.ig_sparse_attention_indexed(d, up.q, up.K, up.V, sel_idx, stride, sel_cnt, None, None, out_idx)
+        ctx.ig_gather_attention(d, up.q, up.K, up.V, sel_idx, stride, sel_cnt, K_one, V_one, None, None,
+                                out_one)
+        ctx.ig_gather_attention(d, up.q, up.K, up.V, sel_idx, stride, sel_cnt, K_one, V_one, up.k_new,
+                                up.v_new, out_one_new)
     torch.cuda.synchronize()
     status = ctx.ig_check_status()
     res = dict(q_p=q_p.cpu().numpy(), scores=None if scores is None else scores.cpu().numpy(),
@@ -76,5 +83,9 @@ def run_gpu(ctx, c, alpha=None, sel_stride=None, host_pool=False, want_scores=Tr
                out=out.float().cpu().numpy().reshape(BH, w.d),
                out_new=out_new.float().cpu().numpy().reshape(BH, w.d),
                out_idx=None if host_pool else out_idx.float().cpu().numpy().reshape(BH, w.d),
+               out_one=None if host_pool else out_one.float().cpu().numpy().reshape(BH, w.d),
+               out_one_new=None if host_pool else out_one_new.float().cpu().numpy().reshape(BH, w.d),
+               K_one=None if host_pool else K_one.cpu().numpy(),
+               V_one=None if host_pool else V_one.cpu().numpy(),
                status=status, up=up)
     return res

@@ -55,6 +55,8 @@ def check_case(ctx, c, alpha=None, host_pool=False, expect_fraction=None):
         assert np.array_equal(got["K_sel"][i, :n], Kt[i, rows])
         assert np.array_equal(got["V_sel"][i, :n], V[i, rows])
         assert not got["K_sel"][i, n:].any() and not got["V_sel"][i, n:].any()   # untouched
+    if got["K_one"] is not None:      # the one-pass prefetch + attention writes the same rows
+        assert np.array_equal(got["K_one"], got["K_sel"]) and np.array_equal(got["V_one"], got["V_sel"])
     # attention: against the oracle on the lists the GPU produced (identical to the oracle's
     # outside the band)
     if slack == 0:
@@ -65,7 +67,8 @@ def check_case(ctx, c, alpha=None, host_pool=False, expect_fraction=None):
         ref_out = o.attend(c.f32("q"), Ks, Vs, got["sel_cnt"], c.scale)
         ref_new = o.attend(c.f32("q"), Ks, Vs, got["sel_cnt"], c.scale, c.f32("k_new"), c.f32("v_new"))
     atol, rtol = (1e-4, 1e-4) if w.dtype == "f32" else (2e-2, 1e-2)
-    for name, r_ in (("out", ref_out), ("out_new", ref_new), ("out_idx", ref_out)):
+    for name, r_ in (("out", ref_out), ("out_new", ref_new), ("out_idx", ref_out),
+                     ("out_one", ref_out), ("out_one_new", ref_new)):
         if got[name] is None:
             continue
         err = np.abs(got[name] - r_)
