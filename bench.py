@@ -1,10 +1,14 @@
 #!/usr/bin/env python3
 """Benchmark of the InfiniGen rehearsal + sparse-attention hot path on one MI355X.
 
-A step is one decode step: for each of the model's L layers, ig_speculate -> ig_gather_kv ->
-ig_sparse_attention over that layer's own slab / KV pool (distinct memory per layer, so the 256 MB
-last-level cache cannot serve the scan).  `value` is microseconds per layer per decode step with
-all inputs resident in HBM.  The roofline object prices the partial-K scan kernel against the HBM
+A step is one decode step: for each of the model's L layers, the rehearsal (ig_speculate), the
+prefetch of the selected rows and the attention over them, on that layer's own slab / KV pool
+(distinct memory per layer, so the 256 MB last-level cache cannot serve the scan).  The step is
+timed as issued eagerly call by call (ig_speculate, ig_gather_kv, ig_sparse_attention) and as HIP
+graph replays of that sequence, of the sequence with prefetch and attention in one pass
+(ig_gather_attention), and of the latter with the next layer's rehearsal on a side stream; `value`
+is the fastest of these in microseconds per layer per decode step, with all inputs resident in HBM
+(host-pool workloads: the KV pool in pinned host memory, the two-stream pipeline).  The roofline object prices the partial-K scan kernel against the HBM
 peak from its algorithmic bytes 2*B*H*N*r and its average duration, taken from HIP events attached
 to each launch.  The cpu_baseline object is the CPU oracle timed on one layer.
 """
@@ -105,7 +109,10 @@ def main():
         pcie = {"h2d_memcpy_GBps": h2d_gbs, "gather_GBps": g_gbs, "frac_of_memcpy": g_gbs / h2d_gbs,
                 "gathered_MB_per_layer": gbytes / 1e6, "gather_alone_us_per_layer": gather_ms * 1e3 / L,
                 "main_alone_us_per_layer": main_ms * 1e3 / L, "overlapped_us_per_layer": eager_ms * 1e3 / L,
-                "overlap_efficiency": (main_ms + gather_ms - eager_ms) / shorter}
+                # 1.0 = the whole step costs what the PCIe-bound prefetch costs alone
+                "pipelined_over_gather_alone": eager_ms / gather_ms,
+                # share of the main stream's work that ran under the prefetch
+                "main_stream_hidden_fraction": (main_ms + gather_ms - eager_ms) / shorter}
         log("pcie", pcie)
         args.no_graph = True
     else:
@@ -116,28 +123,51 @@ def main():
     cnt = R.sel_cnt.cpu().numpy()            # last layer of the step
     log(f"eager {eager_ms:.3f} ms/step = {eager_ms * 1e3 / L:.2f} us/layer")
 
-    # ---- HIP graph of the whole step ----
-    graph_ms = None
+    # ---- HIP graphs of the whole step (HBM pools): the four calls in sequence; prefetch and
+    # attention in one pass; and that with the rehearsal of the next layer on a side stream ----
+    variants = {}
+    launch = "eager, two streams" if R.host_pool else "eager"
+    ms_per_step = eager_ms
     if not args.no_graph:
-        try:
+        def graphed(fn):
             g = torch.cuda.CUDAGraph()
             s = torch.cuda.Stream()
             s.wait_stream(torch.cuda.current_stream())
             with torch.cuda.stream(s):
-                R.step()
+                fn()
             torch.cuda.current_stream().wait_stream(s)
+            torch.cuda.synchronize()
             with torch.cuda.graph(g, stream=s):
-                R.step()
-            for _ in range(W):
-                g.replay()
-            graph_ms = timed(g.replay, K)
-            cnt_g = R.sel_cnt.cpu().numpy()
-            assert np.array_equal(cnt, cnt_g), "graph replay changed the selection"
-            log(f"graph {graph_ms:.3f} ms/step = {graph_ms * 1e3 / L:.2f} us/layer")
-        except Exception as e:   # noqa: BLE001 -- report and fall back to the eager number
-            log("graph capture unavailable:", repr(e))
-            graph_ms = None
-    ms_per_step = graph_ms if graph_ms is not None else eager_ms
+                fn()
+            return g
+        R._use(0)
+        R.step()
+        torch.cuda.synchronize()
+        out_ref = R.out.clone()
+        for name, fn in (("speculate, gather, attention", R.step),
+                         ("speculate, gather+attention in one pass", R.step_one_pass),
+                         ("rehearsal of the next layer on a side stream, gather+attention in one pass",
+                          R.step_two_stream)):
+            try:
+                g = graphed(fn)
+                for _ in range(W):
+                    g.replay()
+                ms = timed(g.replay, K)
+                # replays interleaved with eager work and synchronisation, each checked
+                for _ in range(2):
+                    R._use(0)
+                    R.speculate(0)
+                    torch.cuda.synchronize()
+                    g.replay()
+                    torch.cuda.synchronize()
+                    assert torch.equal(R.out, out_ref), "graph replay changed the attention output"
+                variants[name] = ms * 1e3 / L
+                log(f"graph [{name}] {ms:.3f} ms/step = {ms * 1e3 / L:.2f} us/layer")
+                if ms < ms_per_step:
+                    ms_per_step, launch = ms, "hip graph replay: " + name
+            except Exception as e:   # noqa: BLE001 -- report and keep the eager number
+                log(f"graph [{name}] unavailable:", repr(e))
+    graph_ms = variants.get("speculate, gather, attention")
 
     # ---- fused-attention variant (no K_sel / V_sel copy), eager ----
     fused_ms = None
@@ -180,6 +210,18 @@ def main():
         kernels_overlapped = profiled([R.step_overlapped], max(1, K // 2))
     else:
         kernels = profiled([R.step], K)
+        one = profiled([R.step_one_pass], K)
+        kernels["gather+attention in one pass"] = one["attention"]
+    # streaming-read rate of this GPU on buffers of the slab's size (the slabs themselves, rotated)
+    names[ig.IG_K_READ] = "read"
+    slab_bytes = R.slab[0].numel()
+
+    def read_slabs():
+        for l in range(L):
+            ctx.ig_read_bytes(R.slab[l], slab_bytes - slab_bytes % 16)
+    read_slabs()
+    read_us = profiled([read_slabs], 4)["read"]["avg_us"]
+    read_gbs = slab_bytes / (read_us * 1e-6) / 1e9
     scan_us = kernels["scan"]["avg_us"]
     scan_bytes = R.scan_bytes()
     achieved = scan_bytes / (scan_us * 1e-6) / 1e9
@@ -221,21 +263,36 @@ def main():
         f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)   # noqa: E731
         x, Kt, V, q = f32(h0["x"]), f32(h0["K"]), f32(h0["V"]), f32(h0["q"])
         Wf = f32(R.W_host)
+        def oracle_layer(x, Kt, V, q):
+            if w.rope:
+                q_p = o.project_rope(x, Wf, np.full(w.B, w.N, np.int32), R.A, R.idx_host)
+            else:
+                q_p = o.project(x, Wf, R.idx_host)
+            s = o.scan(q_p, Kt, R.idx_host, R.desc.scale)
+            sel_idx, sel_cnt = o.select(s, w.alpha)
+            m = int(sel_cnt.max())
+            sel_small = np.ascontiguousarray(sel_idx[:, :m])
+            Ks = o.gather(Kt, sel_small, sel_cnt)
+            Vs = o.gather(V, sel_small, sel_cnt)
+            return s, sel_idx, sel_cnt, o.attend(q, Ks, Vs, sel_cnt, R.desc.scale)
+
         t = time.perf_counter()
-        if w.rope:
-            q_p = o.project_rope(x, Wf, np.full(w.B, w.N, np.int32), R.A, R.idx_host)
-        else:
-            q_p = o.project(x, Wf, R.idx_host)
-        s = o.scan(q_p, Kt, R.idx_host, R.desc.scale)
-        sel_idx, sel_cnt = o.select(s, w.alpha)
-        m = int(sel_cnt.max())
-        sel_small = np.ascontiguousarray(sel_idx[:, :m])
-        Ks = o.gather(Kt, sel_small, sel_cnt)
-        Vs = o.gather(V, sel_small, sel_cnt)
-        out = o.attend(q, Ks, Vs, sel_cnt, R.desc.scale)
+        s, sel_idx, sel_cnt, out = oracle_layer(x, Kt, V, q)
         cpu_s = time.perf_counter() - t
-        cpu = {"value": cpu_s * 1e6, "unit": "us/layer/decode step", "cores": 1, "kind": "oracle",
-               "sample": f"1 of {L} layers, whole batch (project+scan+select+gather+attend, single thread)"}
+        # more layers of the same step until about 15 s of oracle time (bounded sample)
+        n_cpu = 1
+        avail = R.n_pool if R.host_pool else L
+        while n_cpu < avail and cpu_s * (n_cpu + 1) / n_cpu < 15.0:
+            l = n_cpu
+            xl, Kl, Vl, ql = (f32(t_.float().cpu().numpy()) for t_ in (R.x[l], R.K[l], R.V[l], R.q[l]))
+            t = time.perf_counter()
+            oracle_layer(xl, Kl, Vl, ql)
+            cpu_s += time.perf_counter() - t
+            n_cpu += 1
+            del xl, Kl, Vl, ql
+        cpu = {"value": cpu_s * 1e6 / n_cpu, "unit": "us/layer/decode step", "cores": 1, "kind": "oracle",
+               "sample": f"{n_cpu} of {L} layers of one decode step, whole batch (project+scan+select+gather+"
+                         f"attend, single thread, {cpu_s:.1f} s in total)"}
         # GPU result for the same layer
         R._use(0)
         R.layer(0)
@@ -275,11 +332,11 @@ def main():
                                f"{'rope' if w.rope else 'folded skew'}, KV pool in "
                                f"{'pinned host memory' if R.host_pool else 'HBM'}",
                    "variant": f"calibrated logit gain {R.gain:g} (scale = gain/sqrt(d))",
-                   "layers_per_step": L, "launch": "hip graph replay" if graph_ms is not None else "eager",
+                   "layers_per_step": L, "launch": launch,
                    "selected_fraction_mean": float(np.mean(fr)), "selected_fraction_min_layer": float(np.min(fr)),
                    "selected_fraction_max_layer": float(np.max(fr))},
         "eager_us_per_layer": eager_ms * 1e3 / L,
-        "graph_us_per_layer": None if graph_ms is None else graph_ms * 1e3 / L,
+        "graph_us_per_layer": variants or None,
         "fused_attention_eager_us_per_layer": None if fused_ms is None else fused_ms * 1e3 / L,
         "scan_GBps": achieved,
         "kernels": kernels,
@@ -288,7 +345,9 @@ def main():
         "roofline": {"kernel": "partial-K scan + max + threshold + compaction", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": SCAN_TRAFFIC_BYTES.get(args.workload),
-                     "algorithmic_bytes_per_launch": scan_bytes, "avg_kernel_us": scan_us},
+                     "algorithmic_bytes_per_launch": scan_bytes, "avg_kernel_us": scan_us,
+                     "plain_read_same_size": {"GBps": read_gbs, "avg_kernel_us": read_us,
+                                              "scan_over_plain_read": read_us / scan_us}},
         "pcie": pcie,
         "cpu_baseline": cpu,
         "parity": parity,

@@ -60,7 +60,8 @@ enum {
   IG_K_ATTENTION = 5,
   IG_K_BUILD = 6,    /* ig_wq_build / ig_slab_build */
   IG_K_COPY = 7,     /* ig_copy_bytes */
-  IG_K_COUNT = 8
+  IG_K_READ = 8,     /* ig_read_bytes */
+  IG_K_COUNT = 9
 };
 
 typedef struct ig_ctx ig_ctx;
@@ -207,6 +208,10 @@ int ig_profile_read(ig_ctx *ctx, int which, double *total_ms, int32_t *launches)
 /* Plain device-to-device copy kernel of `bytes` bytes (multiple of 16); used to scale hardware
  * counters against a transfer of known size and to measure the achievable HBM rate. */
 int ig_copy_bytes(ig_ctx *ctx, const void *src, void *dst, size_t bytes, void *stream);
+
+/* Plain streaming read of `bytes` bytes (multiple of 16) of device memory, nothing written: the
+ * read rate this GPU sustains for a buffer of that size, measured beside the scan. */
+int ig_read_bytes(ig_ctx *ctx, const void *src, size_t bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -16,7 +16,7 @@ __all__ = [
     "IG_OK", "IG_EINVAL", "IG_ESHAPE", "IG_EDTYPE", "IG_ECAPACITY", "IG_EHIP", "IG_ENOCONV",
     "IG_ENOMEM", "IG_F32", "IG_F16", "IG_MEM_DEVICE", "IG_MEM_HOST_PINNED", "IG_K_PROJECT",
     "IG_K_FINALIZE", "IG_K_SCAN", "IG_K_SELECT", "IG_K_GATHER", "IG_K_ATTENTION", "IG_K_BUILD",
-    "IG_K_COPY", "IgDesc", "IgError", "Context", "lib", "lib_path", "ig_skew_offline",
+    "IG_K_COPY", "IG_K_READ", "IgDesc", "IgError", "Context", "lib", "lib_path", "ig_skew_offline",
     "ig_partial_index", "ig_wq_bytes", "ig_slab_bytes", "EXPORTS",
 ]
 
@@ -24,7 +24,7 @@ IG_OK, IG_EINVAL, IG_ESHAPE, IG_EDTYPE, IG_ECAPACITY, IG_EHIP, IG_ENOCONV, IG_EN
 IG_F32, IG_F16 = 0, 1
 IG_MEM_DEVICE, IG_MEM_HOST_PINNED = 0, 1
 (IG_K_PROJECT, IG_K_FINALIZE, IG_K_SCAN, IG_K_SELECT, IG_K_GATHER, IG_K_ATTENTION, IG_K_BUILD,
- IG_K_COPY) = range(8)
+ IG_K_COPY, IG_K_READ) = range(9)
 
 # every symbol include/infinigen.h declares
 EXPORTS = [
@@ -32,7 +32,7 @@ EXPORTS = [
     "ig_partial_index", "ig_wq_bytes", "ig_wq_build", "ig_slab_bytes", "ig_slab_build",
     "ig_speculate", "ig_project", "ig_scan_select", "ig_gather_kv", "ig_sparse_attention",
     "ig_sparse_attention_indexed", "ig_gather_attention", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
-    "ig_copy_bytes",
+    "ig_copy_bytes", "ig_read_bytes",
 ]
 
 
@@ -97,6 +97,7 @@ def lib():
             "ig_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                                ctypes.POINTER(_i32)]),
             "ig_copy_bytes": (ctypes.c_int, [_vp, _vp, _vp, _sz, _vp]),
+            "ig_read_bytes": (ctypes.c_int, [_vp, _vp, _sz, _vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -275,3 +276,6 @@ class Context:
 
     def ig_copy_bytes(self, src, dst, nbytes, stream=None):
         self._ck(lib().ig_copy_bytes(self._h, _ptr(src), _ptr(dst), nbytes, _stream(stream)))
+
+    def ig_read_bytes(self, src, nbytes, stream=None):
+        self._ck(lib().ig_read_bytes(self._h, _ptr(src), nbytes, _stream(stream)))

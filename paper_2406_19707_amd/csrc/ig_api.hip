@@ -412,4 +412,15 @@ int ig_copy_bytes(ig_ctx *ctx, const void *src, void *dst, size_t bytes, void *s
   return ig_launch_copy(ctx, src, dst, bytes, (hipStream_t)stream);
 }
 
+int ig_read_bytes(ig_ctx *ctx, const void *src, size_t bytes, void *stream) {
+  if (!ctx) return IG_EINVAL;
+  if (!src) return ig_fail(ctx, IG_EINVAL, "ig_read_bytes: NULL argument");
+  if (bytes < 16 || bytes % 16 || (uintptr_t)src % 16)
+    return ig_fail(ctx, IG_EINVAL, "ig_read_bytes: size and pointer must be multiples of 16");
+  if (bytes / 16 > 2147483647L * 512L) return ig_fail(ctx, IG_ESHAPE, "ig_read_bytes: too large");
+  int rc = set_device(ctx);
+  if (rc) return rc;
+  return ig_launch_read(ctx, src, bytes, (hipStream_t)stream);
+}
+
 }  // extern "C"

@@ -127,6 +127,7 @@ int ig_launch_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
                         int kv_rows_per_bh, const void *k_new, const void *v_new, void *out,
                         void *K_out, void *V_out, hipStream_t s);
 int ig_launch_copy(ig_ctx *ctx, const void *src, void *dst, size_t bytes, hipStream_t s);
+int ig_launch_read(ig_ctx *ctx, const void *src, size_t bytes, hipStream_t s);
 
 // ---- wave helpers -------------------------------------------------------------------------------
 // Cross-lane moves inside a 16-lane row through DPP (no LDS crossbar traffic).
