@@ -31,7 +31,8 @@ class Rehearsal:
     """State of `layers` decoder layers of one workload and the hot-path call sequence over them."""
 
     def __init__(self, ctx: ig.Context, w: wl.Workload, gain: float | None = None,
-                 layers: int | None = None, host_layers: int = 4, log=lambda *a: None):
+                 layers: int | None = None, host_layers: int = 4, sets: int = 2,
+                 log=lambda *a: None):
         self.ctx, self.w = ctx, w
         self.L = layers or w.layers
         self.gain = w.gain if gain is None else gain
@@ -129,7 +130,7 @@ class Rehearsal:
         self.stride = w.N
         # result buffers; a host pool is pipelined over two sets (rehearsal of layer l+1 runs while the
         # rows of layer l are still crossing PCIe)
-        self.n_sets = 2
+        self.n_sets = sets
         self.sets = []
         for _ in range(self.n_sets):
             self.sets.append(dict(
