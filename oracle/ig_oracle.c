@@ -12,7 +12,9 @@
  *
  * Pins (tests/test_oracle_*.py): skew invariance and SVD structure (Section 4.2, Eq. 2 and Eq. 3),
  * brute-force column ranking, dense-attention equivalence, brute-force threshold enumeration,
- * the exp(-alpha) weight bound of Section 4.3, singular values against LAPACK.
+ * the exp(-alpha) weight bound of Section 4.3, singular values against LAPACK; the head-equalised
+ * selection against rank counting, its reduction to the threshold lists when all heads agree,
+ * and the 20 % cap against the token budget the paper prints (Section 5.3: 409 of 2048).
  * Unpinned: how well the speculated set recalls the true one (the paper gives model-level
  * accuracy only) -- "parity unpinned" for approximation quality; it is reported, never asserted.
  */
@@ -331,6 +333,77 @@ int igo_select(int B, int H, int N, const float *s, float alpha, int32_t *sel_id
       }
     sel_cnt[bh] = n;
   }
+  return IGO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Head-equalised selection (Section 4.3 "Decoding Stage", last sentences; Section 5.1 "Key
+ * Metric"): heads of a layer are computed in parallel, so every head fetches the same number of
+ * tokens, the average over the heads of the number of tokens between the maximum score and the
+ * threshold; a layer sends at most max_frac (20 %) of the cache.
+ * Readings: the average is taken per sequence, over its H heads, and truncated:
+ *   c[b,h] = #{ t : s[b,h,t] >= max_t s[b,h,t] - alpha },  n_b = floor(sum_h c[b,h] / H),
+ *   n_b <- min(n_b, floor(max_frac * N)),  n_b <- max(n_b, 1);
+ * head (b,h) then keeps its n_b highest-scoring tokens (equal scores: the earlier token first),
+ * listed in ascending t.  n_eq [B] receives n_b; sel_cnt [B*H] = n_b for every head of b.
+ * The order "score descending, then t ascending" is produced by a plain sort of (score, t) pairs.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  float s;
+  int32_t t;
+} igo_scored;
+
+static int igo_by_score_then_token(const void *a, const void *b) {
+  const igo_scored *x = (const igo_scored *)a, *y = (const igo_scored *)b;
+  if (x->s > y->s) return -1;
+  if (x->s < y->s) return 1;
+  return (x->t > y->t) - (x->t < y->t);
+}
+
+static int igo_by_token(const void *a, const void *b) {
+  const int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+  return (x > y) - (x < y);
+}
+
+int igo_select_equalized(int B, int H, int N, const float *s, float alpha, double max_frac,
+                         int32_t *sel_idx, int32_t stride, int32_t *sel_cnt, int32_t *n_eq) {
+  if (!(alpha >= 0.0f) || !(max_frac > 0.0) || max_frac > 1.0) return IGO_EINVAL;
+  igo_scored *v = (igo_scored *)malloc(sizeof(igo_scored) * (size_t)N);
+  if (!v) return IGO_ENOMEM;
+  int cap = (int)floor(max_frac * (double)N);
+  if (cap < 1) cap = 1;
+  for (int b = 0; b < B; ++b) {
+    long total = 0;
+    for (int h = 0; h < H; ++h) {
+      const float *sc = s + ((size_t)b * H + h) * N;
+      float m = -INFINITY;
+      for (int t = 0; t < N; ++t)
+        if (sc[t] > m) m = sc[t];
+      const float thr = m - alpha;
+      for (int t = 0; t < N; ++t)
+        if (sc[t] >= thr) ++total;
+    }
+    int n = (int)(total / H);
+    if (n > cap) n = cap;
+    if (n < 1) n = 1;
+    if (n > stride) {
+      free(v);
+      return IGO_EINVAL;
+    }
+    if (n_eq) n_eq[b] = n;
+    for (int h = 0; h < H; ++h) {
+      const size_t bh = (size_t)b * H + h;
+      for (int t = 0; t < N; ++t) {
+        v[t].s = s[bh * N + t];
+        v[t].t = t;
+      }
+      qsort(v, (size_t)N, sizeof(igo_scored), igo_by_score_then_token);
+      for (int j = 0; j < n; ++j) sel_idx[bh * stride + j] = v[j].t;
+      qsort(sel_idx + bh * stride, (size_t)n, sizeof(int32_t), igo_by_token);
+      sel_cnt[bh] = n;
+    }
+  }
+  free(v);
   return IGO_OK;
 }
 

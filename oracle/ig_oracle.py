@@ -162,6 +162,22 @@ def select(s, alpha, stride=None):
     return sel_idx, sel_cnt
 
 
+def select_equalized(s, alpha, max_frac=0.2, stride=None):
+    """Head-equalised selection: every head of a sequence keeps the same number of tokens.
+
+    Returns (sel_idx [B*H, stride] int32 ascending, sel_cnt [B*H], n_eq [B])."""
+    s = _f32(s)
+    B, H, N = s.shape
+    stride = N if stride is None else stride
+    sel_idx = np.full((B * H, stride), -1, np.int32)
+    sel_cnt = np.zeros(B * H, np.int32)
+    n_eq = np.zeros(B, np.int32)
+    _check(_load().igo_select_equalized(B, H, N, _f(s), ctypes.c_float(alpha),
+                                        ctypes.c_double(max_frac), _i(sel_idx), stride,
+                                        _i(sel_cnt), _i(n_eq)), "select_equalized")
+    return sel_idx, sel_cnt, n_eq
+
+
 def gather(pool, sel_idx, sel_cnt):
     """Rows pool[bh, sel_idx[bh, j]] -> out [B*H, stride, d] (zeros beyond the count)."""
     pool, sel_idx, sel_cnt = _f32(pool), _i32(sel_idx), _i32(sel_cnt)
