@@ -159,6 +159,20 @@ int ig_scan_select(ig_ctx *ctx, const ig_desc *desc, const float *q_p, const voi
                    int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, float *scores_opt,
                    void *stream);
 
+/* Head-equalised selection (Section 4.3 "Decoding Stage", closing sentences; Section 5.1 "Key
+ * Metric"): every head of a sequence keeps the same number of tokens,
+ *   n_b = max(1, min(floor(sum_h thr_cnt[b,h] / H), floor(max_frac * N))),
+ * namely its n_b highest-scoring tokens (equal scores: the earlier token first), in ascending t.
+ * scores: device float32 [B, H, N], the speculated scores (ig_speculate's scores_opt).
+ * thr_cnt: device int32 [B*H], the per-head threshold counts (ig_speculate's sel_cnt, unclamped:
+ * taken with sel_stride >= N).  max_frac in (0, 1]; the paper uses 0.2.
+ * Out: sel_idx device int32 [B*H, sel_stride], sel_cnt device int32 [B*H] (= n_b; must not alias
+ * thr_cnt).  Exact for the scores given (integer work only).  Lists longer than sel_stride are
+ * clamped and flagged as in ig_speculate. */
+int ig_equalize_heads(ig_ctx *ctx, const ig_desc *desc, const float *scores, const int32_t *thr_cnt,
+                      double max_frac, int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
+                      void *stream);
+
 /* Prefetch of the selected rows (Section 4.1 overview; Section 4.3): for j < sel_cnt[b,h]
  *   K_sel[b,h,j,:] = Kpool[b,h,sel_idx[b,h,j],:],  V_sel likewise.
  * Kpool, Vpool: [B, H, N_cap, d] of desc->dtype in device memory (IG_MEM_DEVICE) or in pinned,

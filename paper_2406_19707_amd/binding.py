@@ -30,7 +30,7 @@ IG_MEM_DEVICE, IG_MEM_HOST_PINNED = 0, 1
 EXPORTS = [
     "ig_create", "ig_destroy", "ig_last_error", "ig_reserve", "ig_check_status", "ig_skew_offline",
     "ig_partial_index", "ig_wq_bytes", "ig_wq_build", "ig_slab_bytes", "ig_slab_build",
-    "ig_speculate", "ig_project", "ig_scan_select", "ig_gather_kv", "ig_sparse_attention",
+    "ig_speculate", "ig_project", "ig_scan_select", "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention",
     "ig_sparse_attention_indexed", "ig_gather_attention", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
     "ig_copy_bytes", "ig_read_bytes",
 ]
@@ -88,6 +88,7 @@ def lib():
             "ig_speculate": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
             "ig_project": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
             "ig_scan_select": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
+            "ig_equalize_heads": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_double, _vp, _i32, _vp, _vp]),
             "ig_gather_kv": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_int, _vp, _i32, _vp, _vp, _vp, _vp]),
             "ig_sparse_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
             "ig_sparse_attention_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
@@ -255,6 +256,12 @@ class Context:
                                                    _ptr(Kpool), _ptr(Vpool), _ptr(sel_idx),
                                                    sel_stride, _ptr(sel_cnt), _ptr(k_new),
                                                    _ptr(v_new), _ptr(out), _stream(stream)))
+
+    def ig_equalize_heads(self, desc, scores, thr_cnt, max_frac, sel_idx, sel_stride, sel_cnt,
+                          stream=None):
+        self._ck(lib().ig_equalize_heads(self._h, ctypes.byref(desc), _ptr(scores), _ptr(thr_cnt),
+                                         float(max_frac), _ptr(sel_idx), sel_stride, _ptr(sel_cnt),
+                                         _stream(stream)))
 
     def ig_gather_attention(self, desc, q, Kpool, Vpool, sel_idx, sel_stride, sel_cnt, K_sel, V_sel,
                             k_new, v_new, out, stream=None):

@@ -303,6 +303,23 @@ int ig_speculate(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, c
   return ig_launch_scan_select(ctx, d, q, slab, sel_idx, sel_stride, sel_cnt, scores_opt, s);
 }
 
+int ig_equalize_heads(ig_ctx *ctx, const ig_desc *d, const float *scores, const int32_t *thr_cnt,
+                      double max_frac, int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
+                      void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!scores || !thr_cnt) return ig_fail(ctx, IG_EINVAL, "ig_equalize_heads: NULL argument");
+  if (!(max_frac > 0.0) || max_frac > 1.0)
+    return ig_fail(ctx, IG_EINVAL, "max_frac must be in (0, 1] (got %g)", max_frac);
+  if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
+  if (thr_cnt == sel_cnt) return ig_fail(ctx, IG_EINVAL, "ig_equalize_heads: thr_cnt and sel_cnt must not alias");
+  if ((rc = set_device(ctx))) return rc;
+  int cap = (int)floor(max_frac * (double)d->N);
+  if (cap < 1) cap = 1;
+  return ig_launch_equalize(ctx, d, scores, thr_cnt, cap, sel_idx, sel_stride, sel_cnt,
+                            (hipStream_t)stream);
+}
+
 int ig_gather_kv(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const void *Vpool, int pool_space,
                  const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt, void *K_sel,
                  void *V_sel, void *stream) {

@@ -126,6 +126,9 @@ int ig_launch_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
                         const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt,
                         int kv_rows_per_bh, const void *k_new, const void *v_new, void *out,
                         void *K_out, void *V_out, hipStream_t s);
+int ig_launch_equalize(ig_ctx *ctx, const ig_desc *d, const float *scores, const int32_t *thr_cnt,
+                       int cap, int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
+                       hipStream_t s);
 int ig_launch_copy(ig_ctx *ctx, const void *src, void *dst, size_t bytes, hipStream_t s);
 int ig_launch_read(ig_ctx *ctx, const void *src, size_t bytes, hipStream_t s);
 

@@ -1,0 +1,153 @@
+"""GPU parity of the head-equalised selection (ig_equalize_heads) against the CPU oracle.
+
+The selection is integer work on float32 scores, so on identical scores the lists must be
+bit-exact.  End to end (GPU scores against oracle scores, which differ by summation order) a token
+may differ only if its oracle score lies within 1e-3 of the oracle's n-th largest score."""
+import numpy as np
+import pytest
+import torch
+
+import ig_workloads as wl
+from ig_case import make_case, run_oracle
+from oracle import ig_oracle as o
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    import paper_2406_19707_amd as ig
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    c = ig.Context(0)
+    yield c
+    c.close()
+
+
+def equalize_on_gpu(ctx, scores, thr_cnt, alpha, max_frac, stride=None):
+    import paper_2406_19707_amd as ig
+    B, H, N = scores.shape
+    stride = N if stride is None else stride
+    d = ig.IgDesc(B=B, H=H, d=64, r=8, N=N, alpha=alpha)
+    s_dev = torch.from_numpy(np.ascontiguousarray(scores)).cuda()
+    c_dev = torch.from_numpy(np.ascontiguousarray(thr_cnt.astype(np.int32))).cuda()
+    idx = torch.full((B * H, stride), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.full((B * H,), -1, dtype=torch.int32, device="cuda")
+    ctx.ig_equalize_heads(d, s_dev, c_dev, max_frac, idx, stride, cnt)
+    torch.cuda.synchronize()
+    return idx.cpu().numpy(), cnt.cpu().numpy(), ctx.ig_check_status()
+
+
+def assert_same_lists(idx, cnt, ref_idx, ref_cnt):
+    assert np.array_equal(cnt, ref_cnt)
+    for i in range(len(cnt)):
+        assert np.array_equal(idx[i, :cnt[i]], ref_idx[i, :cnt[i]]), i
+
+
+@pytest.mark.parametrize("B,H,N,alpha,max_frac,ties", [
+    (2, 4, 2048, 4.0, 0.2, False),
+    (3, 5, 1999, 2.0, 0.2, True),      # ragged length, many equal scores
+    (1, 3, 257, 1.0, 1.0, True),
+    (2, 2, 5, 0.0, 0.2, True),         # cap floors to 1
+    (1, 2, 20000, 3.0, 0.2, False),    # long sequence: 1024-thread workgroups
+    (1, 2, 9000, 3.0, 0.5, True),
+    (4, 40, 700, 3.0, 0.2, False),     # more heads than a wave
+])
+def test_bit_exact_on_given_scores(ctx, B, H, N, alpha, max_frac, ties):
+    print(f"case B{B} H{H} N{N} alpha {alpha} max_frac {max_frac} ties {ties}", flush=True)
+    rng = np.random.default_rng(B * 1000 + H * 100 + N)
+    s = (rng.standard_normal((B, H, N)) * rng.uniform(0.5, 3.0, (B, H, 1))).astype(np.float32)
+    if ties:
+        s = (np.round(s * 2) / 2).astype(np.float32)
+        s[0, 0, ::3] = -0.0            # signed zeros compare equal
+        s[0, 0, 1::3] = 0.0
+    _, thr_cnt = o.select(s, alpha)
+    ref_idx, ref_cnt, _ = o.select_equalized(s, alpha, max_frac)
+    idx, cnt, status = equalize_on_gpu(ctx, s, thr_cnt, alpha, max_frac)
+    assert status == 0
+    assert_same_lists(idx, cnt, ref_idx, ref_cnt)
+
+
+def test_all_scores_equal_keeps_the_earliest_tokens_up_to_the_cap(ctx):
+    s = np.zeros((1, 2, 2048), np.float32)
+    idx, cnt, status = equalize_on_gpu(ctx, s, np.full(2, 2048), 4.0, 0.2)
+    assert status == 0 and np.all(cnt == 409)
+    assert np.array_equal(idx[:, :409], np.tile(np.arange(409, dtype=np.int32), (2, 1)))
+
+
+def test_short_stride_is_clamped_and_flagged(ctx):
+    import paper_2406_19707_amd as ig
+    s = np.random.default_rng(1).standard_normal((1, 2, 512)).astype(np.float32)
+    ref_idx, _, _ = o.select_equalized(s, 100.0, 1.0)          # everything kept
+    idx, cnt, status = equalize_on_gpu(ctx, s, np.full(2, 512), 100.0, 1.0, stride=100)
+    assert status == ig.IG_ECAPACITY and np.all(cnt == 100)
+    assert np.array_equal(idx, ref_idx[:, :100])
+
+
+def test_error_paths(ctx):
+    import ctypes
+    import paper_2406_19707_amd as ig
+    buf = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    p = buf.data_ptr()
+    d = ig.IgDesc(B=1, H=2, d=128, r=38, N=64)
+    call = lambda frac, cnt_out=p + 4096: ctx.call(  # noqa: E731
+        "ig_equalize_heads", ctypes.byref(d), p, p + 2048, ctypes.c_double(frac), p + 8192, 64, cnt_out, 0)
+    assert call(0.0) == ig.IG_EINVAL
+    assert call(1.5) == ig.IG_EINVAL
+    assert call(float("nan")) == ig.IG_EINVAL
+    assert call(0.2, cnt_out=p + 2048) == ig.IG_EINVAL and "alias" in ctx.last_error()
+
+
+@pytest.mark.parametrize("cfg,shape,gain", [
+    (2, dict(B=3, H=4, N=2048), 6.0),
+    (3, dict(B=2, H=4, N=4096), 24.0),
+    (5, dict(B=1, H=2, N=20000), 6.0),
+])
+def test_end_to_end_with_speculated_scores(ctx, cfg, shape, gain):
+    """ig_speculate (scores + threshold counts) -> ig_equalize_heads -> gather -> attention."""
+    import paper_2406_19707_amd as ig
+    from ig_gpu import Uploaded
+    w = wl.shrink(wl.WORKLOADS[cfg], **shape, pool="hbm")
+    c = make_case(w, gain=gain)
+    print(f"case {w.name} B{w.B} H{w.H} N{c.N}", flush=True)
+    ref = run_oracle(c)
+    up = Uploaded(ctx, c)
+    d = up.desc
+    BH, N = w.B * w.H, c.N
+    tdt = torch.float16
+    scores = torch.zeros((w.B, w.H, N), device="cuda")
+    t_idx = torch.zeros((BH, N), dtype=torch.int32, device="cuda")
+    t_cnt = torch.zeros((BH,), dtype=torch.int32, device="cuda")
+    e_idx = torch.full((BH, N), -1, dtype=torch.int32, device="cuda")
+    e_cnt = torch.zeros((BH,), dtype=torch.int32, device="cuda")
+    K_sel = torch.zeros((BH, N, w.d), dtype=tdt, device="cuda")
+    V_sel = torch.zeros_like(K_sel)
+    out = torch.zeros((w.B, w.H, w.d), dtype=tdt, device="cuda")
+    ctx.ig_speculate(d, up.x, up.wq, up.bias, up.A_p, up.pos, up.slab, t_idx, N, t_cnt, scores)
+    ctx.ig_equalize_heads(d, scores, t_cnt, 0.2, e_idx, N, e_cnt)
+    ctx.ig_gather_kv(d, up.K, up.V, ig.IG_MEM_DEVICE, e_idx, N, e_cnt, K_sel, V_sel)
+    ctx.ig_sparse_attention(d, up.q, K_sel, V_sel, e_cnt, N, None, None, out)
+    torch.cuda.synchronize()
+    assert ctx.ig_check_status() == 0
+    g_scores, g_idx, g_cnt = scores.cpu().numpy(), e_idx.cpu().numpy(), e_cnt.cpu().numpy()
+    # (1) exact on the GPU's own scores and counts
+    x_idx, x_cnt, _ = o.select_equalized(g_scores, w.alpha, 0.2)
+    _, x_thr = o.select(g_scores, w.alpha)
+    assert np.array_equal(x_thr, t_cnt.cpu().numpy())
+    assert_same_lists(g_idx, g_cnt, x_idx, x_cnt)
+    # (2) against the oracle's own scores: only tokens within 1e-3 of the n-th largest score may differ
+    r_idx, r_cnt, r_n = o.select_equalized(ref.s, w.alpha, 0.2)
+    if np.array_equal(r_cnt, g_cnt):
+        s2 = ref.s.reshape(BH, N)
+        for i in range(BH):
+            diff = np.setxor1d(g_idx[i, :g_cnt[i]], r_idx[i, :r_cnt[i]])
+            if diff.size:
+                nth = np.sort(s2[i])[::-1][r_cnt[i] - 1]
+                assert np.all(np.abs(s2[i, diff] - nth) <= 1e-3)
+    print(f"  equalised count per sequence {r_n}, mean threshold count {ref.sel_cnt.mean():.1f}", flush=True)
+    # (3) rows and attention over the equalised lists
+    Ks = o.gather(c.f32("Kt"), g_idx, g_cnt)
+    Vs = o.gather(c.f32("V"), g_idx, g_cnt)
+    assert np.array_equal(K_sel.float().cpu().numpy()[:, :g_cnt.max()], Ks[:, :g_cnt.max()])
+    ref_out = o.attend(c.f32("q"), Ks, Vs, g_cnt, c.scale)
+    err = np.abs(out.float().cpu().numpy().reshape(BH, w.d) - ref_out)
+    assert np.all(err <= 2e-2 + 1e-2 * np.abs(ref_out)), err.max()
