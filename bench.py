@@ -242,6 +242,20 @@ def main():
         fr.append(R.sel_cnt.float().mean().item() / w.N)
     torch.cuda.synchronize()
 
+    # ---- head-equalised variant (every head of a sequence fetches the mean count, 20 % cap) ----
+    equalized = None
+    if not R.host_pool:
+        R._use(0)
+        for _ in range(2):
+            R.step_equalized()
+        eq_ms = timed(R.step_equalized, max(2, K // 2))
+        kq = profiled([R.step_equalized], 2)
+        equalized = {"us_per_layer": eq_ms * 1e3 / L, "launch": "eager",
+                     "equalize_kernel_us": kq["select"]["avg_us"],
+                     "scan_kernel_us_with_scores_kept": kq["scan"]["avg_us"],
+                     "tokens_per_head_last_layer_mean": R.sel_cnt.float().mean().item(),
+                     "max_frac": 0.2}
+
     # ---- literal variant (gain 1: every token selected), eager, a few steps ----
     literal = None
     if R.gain != 1.0 and not args.no_literal and not R.host_pool:
@@ -342,6 +356,7 @@ def main():
         "kernels": kernels,
         "kernels_while_overlapped": kernels_overlapped,
         "literal_variant": literal,
+        "head_equalized_variant": equalized,
         "roofline": {"kernel": "partial-K scan + max + threshold + compaction", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": SCAN_TRAFFIC_BYTES.get(args.workload),

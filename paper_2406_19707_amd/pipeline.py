@@ -240,6 +240,26 @@ class Rehearsal:
             self.speculate(l)
             self.gather_attend(l)
 
+    def step_equalized(self, max_frac=0.2):
+        """The paper's batched variant (Section 4.3, closing sentences): every head of a sequence
+        fetches the same number of tokens.  Rehearsal with the scores kept, equalisation, then
+        prefetch and attention over the equalised lists (HBM pool: in one pass)."""
+        w = self.w
+        if not hasattr(self, "scores"):
+            self.scores = torch.zeros((w.B, w.H, w.N), device="cuda")
+            self.thr_idx = torch.zeros_like(self.sets[0]["sel_idx"])
+            self.thr_cnt = torch.zeros_like(self.sets[0]["sel_cnt"])
+        for l in range(self.L):
+            self.ctx.ig_speculate(self.desc, self.x[l], self.wq, None, self.A_p, self.pos, self.slab[l],
+                                  self.thr_idx, self.stride, self.thr_cnt, self.scores)
+            self.ctx.ig_equalize_heads(self.desc, self.scores, self.thr_cnt, max_frac, self.sel_idx,
+                                       self.stride, self.sel_cnt)
+            if self.host_pool:
+                self.gather(l)
+                self.attend(l)
+            else:
+                self.gather_attend(l)
+
     def step_two_stream(self, one_pass=True):
         """HBM-pool decode step with the rehearsal on a side stream (Fig. 3(d): the next layer is
         speculated while the current one computes): the side stream runs ig_speculate of layer l+1
