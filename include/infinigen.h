@@ -131,6 +131,16 @@ size_t ig_slab_bytes(const ig_desc *desc);
 int ig_slab_build(ig_ctx *ctx, const ig_desc *desc, const void *Kpool, int pool_space,
                   const int32_t *idx_dev, void *slab, void *stream);
 
+/* Append of the token just decoded (Section 2.1: its key and value join the cache; Section 4.4:
+ * the partial key cache on the GPU is updated with it).  `desc` describes the cache before the
+ * append (N valid tokens, N < N_cap, else IG_ECAPACITY; N = 0 is allowed): k_new, v_new (device
+ * [B,H,d], 16-byte aligned; the key already skewed) are written to slot N of Kpool / Vpool (device
+ * or pinned host memory, [B,H,N_cap,d]) and the kept channels idx_dev of k_new to token N of the
+ * slab.  Afterwards the caller uses N + 1. */
+int ig_append_token(ig_ctx *ctx, const ig_desc *desc, const void *k_new, const void *v_new,
+                    const int32_t *idx_dev, void *slab, void *Kpool, void *Vpool, int pool_space,
+                    void *stream);
+
 /* ---- hot path ----------------------------------------------------------------------------- */
 
 /* Attention rehearsal of the next layer (Section 4.3 "Decoding Stage"):

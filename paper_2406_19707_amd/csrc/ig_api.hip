@@ -242,6 +242,35 @@ int ig_slab_build(ig_ctx *ctx, const ig_desc *d, const void *Kpool, int pool_spa
   return ig_launch_slab_build(ctx, d, kp, idx_dev, slab, (hipStream_t)stream);
 }
 
+int ig_append_token(ig_ctx *ctx, const ig_desc *d, const void *k_new, const void *v_new,
+                    const int32_t *idx_dev, void *slab, void *Kpool, void *Vpool, int pool_space,
+                    void *stream) {
+  // the descriptor describes the cache before the append: N valid tokens, the new one goes to slot N
+  if (!ctx) return IG_EINVAL;
+  if (!d) return ig_fail(ctx, IG_EINVAL, "descriptor is NULL");
+  if (d->N == 0 && d->N_cap >= 1) {          // appending to an empty cache is allowed
+    ig_desc one = *d;
+    one.N = 1;
+    int rc0 = check_desc(ctx, &one);
+    if (rc0) return rc0;
+  } else {
+    int rc0 = check_desc(ctx, d);
+    if (rc0) return rc0;
+  }
+  if (d->N >= d->N_cap) return ig_fail(ctx, IG_ECAPACITY, "cache is full: N = %d, N_cap = %d", d->N, d->N_cap);
+  if (!k_new || !v_new || !idx_dev || !slab || !Kpool || !Vpool)
+    return ig_fail(ctx, IG_EINVAL, "ig_append_token: NULL argument");
+  if ((uintptr_t)k_new % 16 || (uintptr_t)v_new % 16)
+    return ig_fail(ctx, IG_EINVAL, "ig_append_token: k_new and v_new must be 16-byte aligned");
+  int rc = set_device(ctx);
+  if (rc) return rc;
+  const void *kp = nullptr, *vp = nullptr;
+  if ((rc = resolve_pool(ctx, Kpool, pool_space, &kp))) return rc;
+  if ((rc = resolve_pool(ctx, Vpool, pool_space, &vp))) return rc;
+  return ig_launch_append(ctx, d, k_new, v_new, idx_dev, slab, const_cast<void *>(kp),
+                          const_cast<void *>(vp), (hipStream_t)stream);
+}
+
 static int project_partials(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq,
                             const float *A_p, const int32_t *pos, ProjGeom *g, hipStream_t s) {
   if (!x || !wq) return ig_fail(ctx, IG_EINVAL, "x or wq is NULL");

@@ -119,6 +119,8 @@ struct QSource {
 int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const void *slab,
                           int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
                           float *scores_opt, hipStream_t s);
+int ig_launch_append(ig_ctx *ctx, const ig_desc *d, const void *k_new, const void *v_new,
+                     const int32_t *idx, void *slab, void *Kpool, void *Vpool, hipStream_t s);
 int ig_launch_gather(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const void *Vpool,
                      const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt,
                      void *K_sel, void *V_sel, int host_pool, hipStream_t s);

@@ -43,6 +43,30 @@ __global__ __launch_bounds__(256) void slab_build(const T *__restrict__ Kpool,
   }
 }
 
+// ---- append of the token just decoded (Section 2.1: the new key and value join the cache; Section
+// 4.4: the matching partial key cache entry is updated with it) -------------------------------------
+// One workgroup per (b,h): the K and V rows go to slot `slot` of the pools (16-byte units, device
+// or mapped pinned host memory), the r kept channels of the key to the slab's channel planes.
+template <typename T>
+__global__ __launch_bounds__(64) void append_token(const T *__restrict__ k_new, const T *__restrict__ v_new,
+                                                   const int32_t *__restrict__ idx, T *__restrict__ slab,
+                                                   u128 *__restrict__ Kpool, u128 *__restrict__ Vpool,
+                                                   int H, int d, int r, int N_cap, int nTiles, int slot) {
+  constexpr int TPL = Elem<T>::TPL;
+  constexpr int TILE = IG_WAVE * TPL;
+  const int bh = blockIdx.x, h = bh % H;
+  const int U = d / TPL;
+  const u128 *kn = reinterpret_cast<const u128 *>(k_new + (long)bh * d);
+  const u128 *vn = reinterpret_cast<const u128 *>(v_new + (long)bh * d);
+  for (int c = threadIdx.x; c < U; c += 64) {
+    Kpool[((long)bh * N_cap + slot) * U + c] = kn[c];
+    Vpool[((long)bh * N_cap + slot) * U + c] = vn[c];
+  }
+  const int tile = slot / TILE, tin = slot % TILE;
+  for (int j = threadIdx.x; j < r; j += 64)
+    slab[((long)bh * nTiles + tile) * r * TILE + (long)j * TILE + tin] = k_new[(long)bh * d + idx[h * r + j]];
+}
+
 // ---- work split shared by gather and attention --------------------------------------------------
 // Selected-token lists are very uneven (a few heads keep a thousand rows, most a few dozen), and
 // one compute unit moves well under 100 GB/s, so a list is cut into up to gridDim.y slices of at
@@ -471,6 +495,25 @@ int ig_launch_slab_build(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const
     auto k = slab_build<float>;
     IG_LAUNCH(ctx, IG_K_BUILD, k, grid, block, s, (const float *)Kpool, idx, (float *)slab,
               (int)d->H, (int)d->d, (int)d->r, (int)d->N, (int)d->N_cap, nTiles);
+  }
+  return IG_OK;
+}
+
+int ig_launch_append(ig_ctx *ctx, const ig_desc *d, const void *k_new, const void *v_new,
+                     const int32_t *idx, void *slab, void *Kpool, void *Vpool, hipStream_t s) {
+  const int tile = ig_tile_tokens(d->dtype);
+  const int nTiles = (d->N_cap + tile - 1) / tile;
+  dim3 grid(d->B * d->H), block(64);
+  if (d->dtype == IG_F16) {
+    auto k = append_token<half_t>;
+    IG_LAUNCH(ctx, IG_K_BUILD, k, grid, block, s, (const half_t *)k_new, (const half_t *)v_new, idx,
+              (half_t *)slab, (u128 *)Kpool, (u128 *)Vpool, (int)d->H, (int)d->d, (int)d->r,
+              (int)d->N_cap, nTiles, (int)d->N);
+  } else {
+    auto k = append_token<float>;
+    IG_LAUNCH(ctx, IG_K_BUILD, k, grid, block, s, (const float *)k_new, (const float *)v_new, idx,
+              (float *)slab, (u128 *)Kpool, (u128 *)Vpool, (int)d->H, (int)d->d, (int)d->r,
+              (int)d->N_cap, nTiles, (int)d->N);
   }
   return IG_OK;
 }
