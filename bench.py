@@ -45,6 +45,7 @@ def main():
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-literal", action="store_true", help="skip the gain-1 (select everything) variant")
+    ap.add_argument("--no-decode-loop", action="store_true", help="skip the growing-cache decode loop")
     ap.add_argument("--copy-reference", action="store_true",
                     help="also launch a plain 256 MiB device copy (reference for scaling hardware counters)")
     args = ap.parse_args()
@@ -256,6 +257,26 @@ def main():
                      "tokens_per_head_last_layer_mean": R.sel_cnt.float().mean().item(),
                      "max_frac": 0.2}
 
+    # ---- decode loop with a growing cache: append of the decoded token after every layer ----
+    decode_loop = None
+    if not args.no_decode_loop:
+        T, L2 = 8, min(L, 8)
+        R2 = Rehearsal(ig.Context(0), w, gain=args.gain or None, layers=L2, host_layers=2,
+                       extra_tokens=T, offline_from=R)
+        R2.decode(2)
+        torch.cuda.synchronize()
+        assert R2.ctx.ig_check_status() == ig.IG_OK
+        t_sparse = timed(lambda: R2.decode(T, dense_first_layer=False), 2) * 1e3 / (T * L2)
+        t_dense0 = timed(lambda: R2.decode(T, dense_first_layer=True), 2) * 1e3 / (T * L2)
+        decode_loop = {"steps": T, "layers": L2, "launch": "eager, one stream",
+                       "calls_per_layer": "ig_speculate, " + ("ig_gather_kv, ig_sparse_attention"
+                                                              if R.host_pool else "ig_gather_attention")
+                                          + " (cached tokens + the token being decoded), ig_append_token",
+                       "us_per_layer_per_step": t_sparse,
+                       "us_per_layer_per_step_first_layer_dense": t_dense0}
+        del R2
+        torch.cuda.empty_cache()
+
     # ---- literal variant (gain 1: every token selected), eager, a few steps ----
     literal = None
     if R.gain != 1.0 and not args.no_literal and not R.host_pool:
@@ -357,6 +378,7 @@ def main():
         "kernels_while_overlapped": kernels_overlapped,
         "literal_variant": literal,
         "head_equalized_variant": equalized,
+        "decode_loop_growing_cache": decode_loop,
         "roofline": {"kernel": "partial-K scan + max + threshold + compaction", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": SCAN_TRAFFIC_BYTES.get(args.workload),

@@ -32,13 +32,26 @@ class Rehearsal:
 
     def __init__(self, ctx: ig.Context, w: wl.Workload, gain: float | None = None,
                  layers: int | None = None, host_layers: int = 4, sets: int = 2,
-                 log=lambda *a: None):
+                 extra_tokens: int = 0, log=lambda *a: None, offline_from: "Rehearsal | None" = None):
         self.ctx, self.w = ctx, w
         self.L = layers or w.layers
         self.gain = w.gain if gain is None else gain
         dev = "cuda"
         tdt = torch.float32 if w.dtype == "f32" else torch.float16
         self.tdt = tdt
+        self.N_cap = w.N + extra_tokens      # room for the tokens a decode loop appends
+        if offline_from is not None:
+            # same model (weights, skewing, partial index, weight blob), other layers / capacity
+            o_ = offline_from
+            assert o_.w is w and o_.gain == self.gain
+            for name in ("A", "idx_host", "r", "idx", "W_host", "wq", "A_p", "pos", "_Wd", "_A_dev"):
+                setattr(self, name, getattr(o_, name))
+            self.desc = ig.IgDesc(B=w.B, H=w.H, d=w.d, r=self.r, N=w.N, N_cap=self.N_cap,
+                                  dtype=o_.desc.dtype, scale=o_.desc.scale, alpha=w.alpha,
+                                  rope=o_.desc.rope)
+            ctx.ig_reserve(self.desc)
+            self._build_layers(host_layers, sets, log)
+            return
 
         # ---- offline: skewing (Section 4.2) on the calibration queries ----
         Wq = wl.projection_weight(w, "Wq")
@@ -55,7 +68,7 @@ class Rehearsal:
         Qs = np.einsum("nhk,hkj->nhj", Qcal.reshape(w.n_cal, w.H, w.d), self.A).reshape(w.n_cal, w.D)
         self.idx_host = ig.ig_partial_index(Qs, None, w.H, w.ratio, ctx=ctx)
         self.r = self.idx_host.shape[1]
-        self.desc = ig.IgDesc(B=w.B, H=w.H, d=w.d, r=self.r, N=w.N, N_cap=w.N,
+        self.desc = ig.IgDesc(B=w.B, H=w.H, d=w.d, r=self.r, N=w.N, N_cap=self.N_cap,
                               dtype=ig.IG_F32 if w.dtype == "f32" else ig.IG_F16,
                               scale=self.gain / math.sqrt(w.d), alpha=w.alpha,
                               rope=1 if w.rope else 0)
@@ -70,12 +83,17 @@ class Rehearsal:
             A_p = np.stack([self.A[h][:, self.idx_host[h]] for h in range(w.H)]).astype(np.float32)
             self.A_p = torch.from_numpy(np.ascontiguousarray(A_p)).to(dev)
             self.pos = torch.full((w.B,), w.N, dtype=torch.int32, device=dev)
-        Wq_model = Wd                      # weight the stand-in model uses for the layer's real query
-        A_dev = torch.from_numpy(self.A).to(dev)
+        self._Wd = Wd                      # weight the stand-in model uses for the layer's real query
+        self._A_dev = torch.from_numpy(self.A).to(dev)
         ctx.ig_reserve(self.desc)
         log("partial weight built")
+        self._build_layers(host_layers, sets, log)
 
-        # ---- per-layer state ----
+    def _build_layers(self, host_layers, sets, log):
+        """Per-layer state: layer inputs, the layer's real query, KV pool, partial key cache."""
+        ctx, w, dev, tdt = self.ctx, self.w, "cuda", self.tdt
+        extra_tokens = self.N_cap - w.N
+        Wq_model, A_dev = self._Wd, self._A_dev
         self.host_pool = w.pool == "host"
         self.n_pool = min(self.L, host_layers) if self.host_pool else self.L
         self.x, self.q, self.slab, self.K, self.V = [], [], [], [], []
@@ -90,14 +108,17 @@ class Rehearsal:
                 del Kn, Vn
                 self.layer0_host = dict(x=x.cpu().numpy(), K=K.numpy(), V=V.numpy())
                 K, V = K.to(dev), V.to(dev)
+                if extra_tokens:
+                    pad = torch.zeros((w.B, w.H, extra_tokens, w.d), dtype=K.dtype, device=dev)
+                    K, V = torch.cat([K, pad], 2).contiguous(), torch.cat([V, pad], 2).contiguous()
             else:
                 g = torch.Generator(device=dev).manual_seed(1000 * w.cfg + 7919 * l)
                 x = torch.randn((w.B, w.D), generator=g, device=dev).to(tdt)
                 xn = x.float() + 0.3 * torch.randn((w.B, w.D), generator=g, device=dev)
-                K = torch.randn((w.B, w.H, w.N, w.d), generator=g, device=dev, dtype=tdt)
-                V = torch.randn((w.B, w.H, w.N, w.d), generator=g, device=dev, dtype=tdt)
+                K = torch.randn((w.B, w.H, self.N_cap, w.d), generator=g, device=dev, dtype=tdt)
+                V = torch.randn((w.B, w.H, self.N_cap, w.d), generator=g, device=dev, dtype=tdt)
                 gain_rows = torch.from_numpy(wl.key_row_gain(w, l)).to(dev).to(tdt)
-                K *= gain_rows[:, None, :, None]
+                K[:, :, :w.N] *= gain_rows[:, None, :, None]
             # the layer's real (skewed) query: the stand-in model's projection of its own input
             qf = (xn.to(tdt) @ Wq_model).float().reshape(w.B, w.H, w.d)
             if w.rope:
@@ -127,7 +148,7 @@ class Rehearsal:
         log("layers built")
         self.space = ig.IG_MEM_HOST_PINNED if self.host_pool else ig.IG_MEM_DEVICE
         BH = w.B * w.H
-        self.stride = w.N
+        self.stride = self.N_cap
         # result buffers; a host pool is pipelined over two sets (rehearsal of layer l+1 runs while the
         # rows of layer l are still crossing PCIe)
         self.n_sets = sets
@@ -287,6 +308,44 @@ class Rehearsal:
             ev_attn[l] = torch.cuda.Event()
             ev_attn[l].record(main)
         main.wait_stream(side)
+
+    def decode(self, steps: int, dense_first_layer: bool = True):
+        """`steps` decode steps over all layers with a growing cache (Section 2.1, Section 4.3):
+        per layer the rehearsal, prefetch and attention over the cached tokens plus the token being
+        decoded, then that token's key / value are appended to the layer's pool and slab.  The first
+        layer attends every token (speculation starts at the second layer, Section 4.3).  Needs
+        extra_tokens >= steps.  Single stream; the synthetic new-token rows are fixed tensors."""
+        w = self.w
+        assert self.w.N + steps <= self.N_cap, "construct with extra_tokens >= steps"
+        if not hasattr(self, "k_new"):
+            g = torch.Generator(device="cuda").manual_seed(4242 + w.cfg)
+            self.k_new = torch.randn((w.B, w.H, w.d), generator=g, device="cuda").to(self.tdt)
+            self.v_new = torch.randn((w.B, w.H, w.d), generator=g, device="cuda").to(self.tdt)
+            self.desc_dense = ig.IgDesc(B=w.B, H=w.H, d=w.d, r=self.r, N=w.N, N_cap=self.N_cap,
+                                        dtype=self.desc.dtype, scale=self.desc.scale,
+                                        alpha=float("inf"), rope=self.desc.rope)
+        self._use(0)
+        n0 = self.desc.N
+        for s_ in range(steps):
+            for l in range(self.L):
+                d = self.desc_dense if (dense_first_layer and l == 0) else self.desc
+                d.N = n0 + s_
+                p = l % self.n_pool
+                self.ctx.ig_speculate(d, self.x[l], self.wq, None, self.A_p, self.pos, self.slab[l],
+                                      self.sel_idx, self.stride, self.sel_cnt, None)
+                if self.host_pool:
+                    self.ctx.ig_gather_kv(d, self.K[p], self.V[p], self.space, self.sel_idx, self.stride,
+                                          self.sel_cnt, self.K_sel, self.V_sel)
+                    self.ctx.ig_sparse_attention(d, self.q[l], self.K_sel, self.V_sel, self.sel_cnt,
+                                                 self.stride, self.k_new, self.v_new, self.out)
+                else:
+                    self.ctx.ig_gather_attention(d, self.q[l], self.K[p], self.V[p], self.sel_idx,
+                                                 self.stride, self.sel_cnt, self.K_sel, self.V_sel,
+                                                 self.k_new, self.v_new, self.out)
+                self.ctx.ig_append_token(d, self.k_new, self.v_new, self.idx, self.slab[l], self.K[p],
+                                         self.V[p], self.space)
+        self.desc.N = n0
+        self.desc_dense.N = n0
 
     def gathered_bytes(self) -> int:
         """Bytes the prefetch of the layer whose lists are current moves (K and V rows)."""
