@@ -14,7 +14,8 @@
  * brute-force column ranking, dense-attention equivalence, brute-force threshold enumeration,
  * the exp(-alpha) weight bound of Section 4.3, singular values against LAPACK; the head-equalised
  * selection against rank counting, its reduction to the threshold lists when all heads agree,
- * and the 20 % cap against the token budget the paper prints (Section 5.3: 409 of 2048).
+ * and the 20 % cap against the token budget the paper prints (Section 5.3: 409 of 2048);
+ * the pool counters against hand-worked cases and an array formulation.
  * Unpinned: how well the speculated set recalls the true one (the paper gives model-level
  * accuracy only) -- "parity unpinned" for approximation quality; it is reported, never asserted.
  */
@@ -404,6 +405,47 @@ int igo_select_equalized(int B, int H, int N, const float *s, float alpha, doubl
     }
   }
   free(v);
+  return IGO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * KV cache pool management, counter-based policy (Section 4.4): the pool manager increments a
+ * counter for each prefetched KV entry; the victim is the entry with the smallest count; if any
+ * counter becomes saturated, all counter values are reduced by half.  The victim is overwritten
+ * by the newly generated key and value (the order of entries in the pool is arbitrary).
+ * Readings: one counter per pool slot of every (sequence, head) pool, counters [B*H, N_cap];
+ * a counter is saturated when it reaches counter_max; the halving (integer division by two) is
+ * applied to the pool of that (sequence, head) after all increments of the step; equal smallest
+ * counts: the lowest slot; an overwritten slot restarts at zero (done by the caller here: the
+ * oracle only names the victim).
+ * ------------------------------------------------------------------------------------------ */
+int igo_pool_touch(int BH, int N, int N_cap, const int32_t *sel_idx, int32_t stride,
+                   const int32_t *sel_cnt, int32_t *counters, int32_t counter_max) {
+  if (counter_max < 1) return IGO_EINVAL;
+  for (int bh = 0; bh < BH; ++bh) {
+    int32_t *c = counters + (size_t)bh * N_cap;
+    int saturated = 0;
+    for (int j = 0; j < sel_cnt[bh]; ++j) {
+      int t = sel_idx[(size_t)bh * stride + j];
+      if (t < 0 || t >= N) return IGO_EINVAL;
+      if (c[t] < counter_max) c[t] += 1;
+      if (c[t] >= counter_max) saturated = 1;
+    }
+    if (saturated)
+      for (int t = 0; t < N; ++t) c[t] /= 2;
+  }
+  return IGO_OK;
+}
+
+int igo_pool_victim(int BH, int N, int N_cap, const int32_t *counters, int32_t *victim) {
+  if (N < 1) return IGO_EINVAL;
+  for (int bh = 0; bh < BH; ++bh) {
+    const int32_t *c = counters + (size_t)bh * N_cap;
+    int best = 0;
+    for (int t = 1; t < N; ++t)
+      if (c[t] < c[best]) best = t;
+    victim[bh] = best;
+  }
   return IGO_OK;
 }
 

@@ -178,6 +178,26 @@ def select_equalized(s, alpha, max_frac=0.2, stride=None):
     return sel_idx, sel_cnt, n_eq
 
 
+def pool_touch(counters, sel_idx, sel_cnt, N, counter_max=255):
+    """Counter policy: +1 for every prefetched slot (saturating), halve a pool whose counter saturates.
+    counters int32 [B*H, N_cap], updated in place."""
+    assert counters.dtype == np.int32 and counters.flags.c_contiguous
+    sel_idx, sel_cnt = _i32(sel_idx), _i32(sel_cnt)
+    BH, N_cap = counters.shape
+    _check(_load().igo_pool_touch(BH, N, N_cap, _i(sel_idx), sel_idx.shape[1], _i(sel_cnt),
+                                  _i(counters), counter_max), "pool_touch")
+    return counters
+
+
+def pool_victim(counters, N):
+    """Slot with the smallest count among the first N of every pool (ties: the lowest slot)."""
+    counters = _i32(counters)
+    BH, N_cap = counters.shape
+    victim = np.zeros(BH, np.int32)
+    _check(_load().igo_pool_victim(BH, N, N_cap, _i(counters), _i(victim)), "pool_victim")
+    return victim
+
+
 def gather(pool, sel_idx, sel_cnt):
     """Rows pool[bh, sel_idx[bh, j]] -> out [B*H, stride, d] (zeros beyond the count)."""
     pool, sel_idx, sel_cnt = _f32(pool), _i32(sel_idx), _i32(sel_cnt)
