@@ -141,6 +141,25 @@ int ig_append_token(ig_ctx *ctx, const ig_desc *desc, const void *k_new, const v
                     const int32_t *idx_dev, void *slab, void *Kpool, void *Vpool, int pool_space,
                     void *stream);
 
+/* KV cache pool management, counter-based policy (Section 4.4).  counters: device int32
+ * [B*H, N_cap], one per pool slot, zero-initialised by the caller.
+ *   ig_pool_touch    +1 (saturating at counter_max) for every slot a list names, i.e. for every
+ *                    prefetched entry; a pool in which a counter reached counter_max has all its
+ *                    counters halved after the increments.  counter_max >= 1 (255: 8-bit counters).
+ *   ig_pool_victim   victim[b*H+h] = the slot with the smallest count among the N valid slots of
+ *                    that pool, the lowest slot on ties.  victim: device int32 [B*H].
+ *   ig_pool_replace  overwrites slot victim[b*H+h] of every pool with the new token: K and V rows
+ *                    in Kpool / Vpool (device or pinned host), the kept key channels in the slab;
+ *                    the slot's counter restarts at zero (counters may be NULL).  Slots outside
+ *                    [0, N_cap) are skipped.  k_new, v_new as in ig_append_token. */
+int ig_pool_touch(ig_ctx *ctx, const ig_desc *desc, const int32_t *sel_idx, int32_t sel_stride,
+                  const int32_t *sel_cnt, int32_t *counters, int32_t counter_max, void *stream);
+int ig_pool_victim(ig_ctx *ctx, const ig_desc *desc, const int32_t *counters, int32_t *victim,
+                   void *stream);
+int ig_pool_replace(ig_ctx *ctx, const ig_desc *desc, const int32_t *victim, const void *k_new,
+                    const void *v_new, const int32_t *idx_dev, void *slab, void *Kpool, void *Vpool,
+                    int pool_space, int32_t *counters, void *stream);
+
 /* ---- hot path ----------------------------------------------------------------------------- */
 
 /* Attention rehearsal of the next layer (Section 4.3 "Decoding Stage"):

@@ -30,6 +30,7 @@ IG_MEM_DEVICE, IG_MEM_HOST_PINNED = 0, 1
 EXPORTS = [
     "ig_create", "ig_destroy", "ig_last_error", "ig_reserve", "ig_check_status", "ig_skew_offline",
     "ig_partial_index", "ig_wq_bytes", "ig_wq_build", "ig_slab_bytes", "ig_slab_build", "ig_append_token",
+    "ig_pool_touch", "ig_pool_victim", "ig_pool_replace",
     "ig_speculate", "ig_project", "ig_scan_select", "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention",
     "ig_sparse_attention_indexed", "ig_gather_attention", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
     "ig_copy_bytes", "ig_read_bytes",
@@ -86,6 +87,9 @@ def lib():
             "ig_slab_bytes": (_sz, [_dp]),
             "ig_slab_build": (ctypes.c_int, [_vp, _dp, _vp, ctypes.c_int, _vp, _vp, _vp]),
             "ig_append_token": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int, _vp]),
+            "ig_pool_touch": (ctypes.c_int, [_vp, _dp, _vp, _i32, _vp, _vp, _i32, _vp]),
+            "ig_pool_victim": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp]),
+            "ig_pool_replace": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int, _vp, _vp]),
             "ig_speculate": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
             "ig_project": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
             "ig_scan_select": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
@@ -227,6 +231,20 @@ class Context:
         self._ck(lib().ig_append_token(self._h, ctypes.byref(desc), _ptr(k_new), _ptr(v_new),
                                        _ptr(idx_dev), _ptr(slab), _ptr(Kpool), _ptr(Vpool),
                                        pool_space, _stream(stream)))
+
+    def ig_pool_touch(self, desc, sel_idx, sel_stride, sel_cnt, counters, counter_max=255, stream=None):
+        self._ck(lib().ig_pool_touch(self._h, ctypes.byref(desc), _ptr(sel_idx), sel_stride,
+                                     _ptr(sel_cnt), _ptr(counters), counter_max, _stream(stream)))
+
+    def ig_pool_victim(self, desc, counters, victim, stream=None):
+        self._ck(lib().ig_pool_victim(self._h, ctypes.byref(desc), _ptr(counters), _ptr(victim),
+                                      _stream(stream)))
+
+    def ig_pool_replace(self, desc, victim, k_new, v_new, idx_dev, slab, Kpool, Vpool, pool_space,
+                        counters=None, stream=None):
+        self._ck(lib().ig_pool_replace(self._h, ctypes.byref(desc), _ptr(victim), _ptr(k_new),
+                                       _ptr(v_new), _ptr(idx_dev), _ptr(slab), _ptr(Kpool),
+                                       _ptr(Vpool), pool_space, _ptr(counters), _stream(stream)))
 
     def ig_speculate(self, desc, x, wq, bias, A_p, pos, slab, sel_idx, sel_stride, sel_cnt,
                      scores_opt=None, stream=None):

@@ -82,6 +82,12 @@ int check_desc(ig_ctx *ctx, const ig_desc *d) {
   return IG_OK;
 }
 
+int check_sel(ig_ctx *ctx, const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt) {
+  if (!sel_idx || !sel_cnt) return ig_fail(ctx, IG_EINVAL, "sel_idx or sel_cnt is NULL");
+  if (sel_stride < 1) return ig_fail(ctx, IG_ESHAPE, "sel_stride = %d", sel_stride);
+  return IG_OK;
+}
+
 int set_device(ig_ctx *ctx) {
   IG_HIP(ctx, hipSetDevice(ctx->device));
   return IG_OK;
@@ -268,7 +274,45 @@ int ig_append_token(ig_ctx *ctx, const ig_desc *d, const void *k_new, const void
   if ((rc = resolve_pool(ctx, Kpool, pool_space, &kp))) return rc;
   if ((rc = resolve_pool(ctx, Vpool, pool_space, &vp))) return rc;
   return ig_launch_append(ctx, d, k_new, v_new, idx_dev, slab, const_cast<void *>(kp),
-                          const_cast<void *>(vp), (hipStream_t)stream);
+                          const_cast<void *>(vp), nullptr, nullptr, (hipStream_t)stream);
+}
+
+int ig_pool_touch(ig_ctx *ctx, const ig_desc *d, const int32_t *sel_idx, int32_t sel_stride,
+                  const int32_t *sel_cnt, int32_t *counters, int32_t counter_max, void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!counters) return ig_fail(ctx, IG_EINVAL, "ig_pool_touch: counters is NULL");
+  if (counter_max < 1) return ig_fail(ctx, IG_EINVAL, "counter_max = %d", counter_max);
+  if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
+  if ((rc = set_device(ctx))) return rc;
+  return ig_launch_pool_touch(ctx, d, sel_idx, sel_stride, sel_cnt, counters, counter_max,
+                              (hipStream_t)stream);
+}
+
+int ig_pool_victim(ig_ctx *ctx, const ig_desc *d, const int32_t *counters, int32_t *victim,
+                   void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!counters || !victim) return ig_fail(ctx, IG_EINVAL, "ig_pool_victim: NULL argument");
+  if ((rc = set_device(ctx))) return rc;
+  return ig_launch_pool_victim(ctx, d, counters, victim, (hipStream_t)stream);
+}
+
+int ig_pool_replace(ig_ctx *ctx, const ig_desc *d, const int32_t *victim, const void *k_new,
+                    const void *v_new, const int32_t *idx_dev, void *slab, void *Kpool, void *Vpool,
+                    int pool_space, int32_t *counters, void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!victim || !k_new || !v_new || !idx_dev || !slab || !Kpool || !Vpool)
+    return ig_fail(ctx, IG_EINVAL, "ig_pool_replace: NULL argument");
+  if ((uintptr_t)k_new % 16 || (uintptr_t)v_new % 16)
+    return ig_fail(ctx, IG_EINVAL, "ig_pool_replace: k_new and v_new must be 16-byte aligned");
+  if ((rc = set_device(ctx))) return rc;
+  const void *kp = nullptr, *vp = nullptr;
+  if ((rc = resolve_pool(ctx, Kpool, pool_space, &kp))) return rc;
+  if ((rc = resolve_pool(ctx, Vpool, pool_space, &vp))) return rc;
+  return ig_launch_append(ctx, d, k_new, v_new, idx_dev, slab, const_cast<void *>(kp),
+                          const_cast<void *>(vp), victim, counters, (hipStream_t)stream);
 }
 
 static int project_partials(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq,
@@ -290,12 +334,6 @@ int ig_project(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, con
   ProjGeom g;
   if ((rc = project_partials(ctx, d, x, wq, A_p, pos, &g, (hipStream_t)stream))) return rc;
   return ig_launch_finalize(ctx, d, g, ctx->part, bias, A_p, pos, q_p, (hipStream_t)stream);
-}
-
-static int check_sel(ig_ctx *ctx, const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt) {
-  if (!sel_idx || !sel_cnt) return ig_fail(ctx, IG_EINVAL, "sel_idx or sel_cnt is NULL");
-  if (sel_stride < 1) return ig_fail(ctx, IG_ESHAPE, "sel_stride = %d", sel_stride);
-  return IG_OK;
 }
 
 int ig_scan_select(ig_ctx *ctx, const ig_desc *d, const float *q_p, const void *slab,

@@ -120,7 +120,12 @@ int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const
                           int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
                           float *scores_opt, hipStream_t s);
 int ig_launch_append(ig_ctx *ctx, const ig_desc *d, const void *k_new, const void *v_new,
-                     const int32_t *idx, void *slab, void *Kpool, void *Vpool, hipStream_t s);
+                     const int32_t *idx, void *slab, void *Kpool, void *Vpool,
+                     const int32_t *slots, int32_t *counters, hipStream_t s);
+int ig_launch_pool_touch(ig_ctx *ctx, const ig_desc *d, const int32_t *sel_idx, int32_t sel_stride,
+                         const int32_t *sel_cnt, int32_t *counters, int counter_max, hipStream_t s);
+int ig_launch_pool_victim(ig_ctx *ctx, const ig_desc *d, const int32_t *counters, int32_t *victim,
+                          hipStream_t s);
 int ig_launch_gather(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const void *Vpool,
                      const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt,
                      void *K_sel, void *V_sel, int host_pool, hipStream_t s);

@@ -51,10 +51,17 @@ template <typename T>
 __global__ __launch_bounds__(64) void append_token(const T *__restrict__ k_new, const T *__restrict__ v_new,
                                                    const int32_t *__restrict__ idx, T *__restrict__ slab,
                                                    u128 *__restrict__ Kpool, u128 *__restrict__ Vpool,
-                                                   int H, int d, int r, int N_cap, int nTiles, int slot) {
+                                                   int H, int d, int r, int N_cap, int nTiles, int slot_all,
+                                                   const int32_t *__restrict__ slots,
+                                                   int32_t *__restrict__ counters) {
   constexpr int TPL = Elem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
   const int bh = blockIdx.x, h = bh % H;
+  // one slot for every pool (append) or the pool's own victim slot (replacement); a slot outside
+  // the pool is ignored
+  const int slot = slots ? slots[bh] : slot_all;
+  if (slot < 0 || slot >= N_cap) return;
+  if (counters && threadIdx.x == 0) counters[(long)bh * N_cap + slot] = 0;
   const int U = d / TPL;
   const u128 *kn = reinterpret_cast<const u128 *>(k_new + (long)bh * d);
   const u128 *vn = reinterpret_cast<const u128 *>(v_new + (long)bh * d);
@@ -65,6 +72,54 @@ __global__ __launch_bounds__(64) void append_token(const T *__restrict__ k_new, 
   const int tile = slot / TILE, tin = slot % TILE;
   for (int j = threadIdx.x; j < r; j += 64)
     slab[((long)bh * nTiles + tile) * r * TILE + (long)j * TILE + tin] = k_new[(long)bh * d + idx[h * r + j]];
+}
+
+// ---- pool counters (Section 4.4, counter-based victim selection) ------------------------------------
+// One workgroup per (b,h) pool.  touch: +1 (saturating) on the counter of every prefetched slot; a
+// list holds a slot once, so plain stores suffice; if a counter reached the saturation value, all
+// counters of the pool are halved after the increments.  victim: the slot with the smallest count
+// among the N valid ones, the lowest slot on ties (minimum over count * 2^32 + slot).
+__global__ __launch_bounds__(256) void pool_touch(const int32_t *__restrict__ sel_idx,
+                                                  const int32_t *__restrict__ sel_cnt,
+                                                  int32_t *__restrict__ counters, int stride, int N,
+                                                  int N_cap, int counter_max) {
+  const int bh = blockIdx.x;
+  int32_t *c = counters + (long)bh * N_cap;
+  const int n = min(sel_cnt[bh], stride);
+  int sat = 0;
+  for (int j = threadIdx.x; j < n; j += 256) {
+    const int t = sel_idx[(long)bh * stride + j];
+    if (t >= 0 && t < N) {
+      const int v = min(c[t] + 1, counter_max);
+      c[t] = v;
+      sat |= v >= counter_max;
+    }
+  }
+  if (__syncthreads_or(sat))
+    for (int t = threadIdx.x; t < N; t += 256) c[t] >>= 1;
+}
+
+__global__ __launch_bounds__(256) void pool_victim(const int32_t *__restrict__ counters,
+                                                   int32_t *__restrict__ victim, int N, int N_cap) {
+  __shared__ unsigned long long best[4];
+  const int bh = blockIdx.x, lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int32_t *c = counters + (long)bh * N_cap;
+  unsigned long long m = ~0ull;
+  for (int t = threadIdx.x; t < N; t += 256) {
+    const unsigned long long key = ((unsigned long long)(unsigned)c[t] << 32) | (unsigned)t;
+    m = key < m ? key : m;
+  }
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) {
+    const unsigned long long u = __shfl_xor(m, o, 64);
+    m = u < m ? u : m;
+  }
+  if (lane == 0) best[w] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int k = 1; k < 4; ++k) m = best[k] < m ? best[k] : m;
+    victim[bh] = (int32_t)(m & 0xFFFFFFFFull);
+  }
 }
 
 // ---- work split shared by gather and attention --------------------------------------------------
@@ -500,7 +555,8 @@ int ig_launch_slab_build(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const
 }
 
 int ig_launch_append(ig_ctx *ctx, const ig_desc *d, const void *k_new, const void *v_new,
-                     const int32_t *idx, void *slab, void *Kpool, void *Vpool, hipStream_t s) {
+                     const int32_t *idx, void *slab, void *Kpool, void *Vpool,
+                     const int32_t *slots, int32_t *counters, hipStream_t s) {
   const int tile = ig_tile_tokens(d->dtype);
   const int nTiles = (d->N_cap + tile - 1) / tile;
   dim3 grid(d->B * d->H), block(64);
@@ -508,13 +564,29 @@ int ig_launch_append(ig_ctx *ctx, const ig_desc *d, const void *k_new, const voi
     auto k = append_token<half_t>;
     IG_LAUNCH(ctx, IG_K_BUILD, k, grid, block, s, (const half_t *)k_new, (const half_t *)v_new, idx,
               (half_t *)slab, (u128 *)Kpool, (u128 *)Vpool, (int)d->H, (int)d->d, (int)d->r,
-              (int)d->N_cap, nTiles, (int)d->N);
+              (int)d->N_cap, nTiles, (int)d->N, slots, counters);
   } else {
     auto k = append_token<float>;
     IG_LAUNCH(ctx, IG_K_BUILD, k, grid, block, s, (const float *)k_new, (const float *)v_new, idx,
               (float *)slab, (u128 *)Kpool, (u128 *)Vpool, (int)d->H, (int)d->d, (int)d->r,
-              (int)d->N_cap, nTiles, (int)d->N);
+              (int)d->N_cap, nTiles, (int)d->N, slots, counters);
   }
+  return IG_OK;
+}
+
+int ig_launch_pool_touch(ig_ctx *ctx, const ig_desc *d, const int32_t *sel_idx, int32_t sel_stride,
+                         const int32_t *sel_cnt, int32_t *counters, int counter_max, hipStream_t s) {
+  auto k = pool_touch;
+  IG_LAUNCH(ctx, IG_K_BUILD, k, dim3(d->B * d->H), dim3(256), s, sel_idx, sel_cnt, counters,
+            (int)sel_stride, (int)d->N, (int)d->N_cap, counter_max);
+  return IG_OK;
+}
+
+int ig_launch_pool_victim(ig_ctx *ctx, const ig_desc *d, const int32_t *counters, int32_t *victim,
+                          hipStream_t s) {
+  auto k = pool_victim;
+  IG_LAUNCH(ctx, IG_K_BUILD, k, dim3(d->B * d->H), dim3(256), s, counters, victim, (int)d->N,
+            (int)d->N_cap);
   return IG_OK;
 }
 
