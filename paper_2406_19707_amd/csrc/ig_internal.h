@@ -23,6 +23,20 @@ template <> struct Elem<float> {
   typedef floatx4 vec;
 };
 
+// Tokens of one channel that a lane of the scan loads at once (the slab's tile is 64 lanes of them).
+#ifndef IG_SLAB_TPL_HALF
+#define IG_SLAB_TPL_HALF 8
+#endif
+template <typename T> struct SlabElem;
+template <> struct SlabElem<half_t> {
+  static constexpr int TPL = IG_SLAB_TPL_HALF;
+  typedef _Float16 vec __attribute__((ext_vector_type(IG_SLAB_TPL_HALF)));
+};
+template <> struct SlabElem<float> {
+  static constexpr int TPL = 4;
+  typedef floatx4 vec;
+};
+
 constexpr int IG_WAVE = 64;
 constexpr int IG_KS_MAX = 16;     // split-K partial sums a consumer adds up at most
 constexpr int IG_STATUS_CAPACITY = 1;
@@ -30,8 +44,8 @@ constexpr int IG_SLICE_MAX = 16;   // slices a selected-token list is cut into a
 
 // Slab geometry: tokens are grouped in tiles of 64 lanes x TPL tokens; inside a tile the r kept
 // channels are planes of TILE contiguous tokens:  slab[(bh*nTiles + tile)*r*TILE + j*TILE + t%TILE].
-template <typename T> __host__ __device__ constexpr int tile_tokens() { return IG_WAVE * Elem<T>::TPL; }
-static inline int ig_tile_tokens(int dtype) { return dtype == IG_F16 ? 512 : 256; }
+template <typename T> __host__ __device__ constexpr int tile_tokens() { return IG_WAVE * SlabElem<T>::TPL; }
+static inline int ig_tile_tokens(int dtype) { return dtype == IG_F16 ? IG_WAVE * IG_SLAB_TPL_HALF : 256; }
 static inline int ig_elem_bytes(int dtype) { return dtype == IG_F16 ? 2 : 4; }
 
 // Geometry of the partial query projection.

@@ -15,8 +15,8 @@ __global__ __launch_bounds__(256) void slab_build(const T *__restrict__ Kpool,
                                                   const int32_t *__restrict__ idx,
                                                   T *__restrict__ slab, int H, int d, int r, int N,
                                                   int N_cap, int nTiles) {
-  constexpr int TPL = Elem<T>::TPL;
-  constexpr int TILE = IG_WAVE * TPL;
+  constexpr int TPL = Elem<T>::TPL;              // elements of a pool row per 16-byte unit
+  constexpr int TILE = IG_WAVE * SlabElem<T>::TPL;
   constexpr int CHUNK = 32;
   __shared__ T rows[CHUNK * (256 + 8)];
   const int ldr = d + 8;
@@ -55,7 +55,7 @@ __global__ __launch_bounds__(64) void append_token(const T *__restrict__ k_new, 
                                                    const int32_t *__restrict__ slots,
                                                    int32_t *__restrict__ counters) {
   constexpr int TPL = Elem<T>::TPL;
-  constexpr int TILE = IG_WAVE * TPL;
+  constexpr int TILE = IG_WAVE * SlabElem<T>::TPL;
   const int bh = blockIdx.x, h = bh % H;
   // one slot for every pool (append) or the pool's own victim slot (replacement); a slot outside
   // the pool is ignored

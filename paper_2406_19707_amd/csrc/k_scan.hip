@@ -70,8 +70,8 @@ __device__ __forceinline__ float query_block(const float (&qv)[4], int j0, int l
 
 template <typename T, int CH>
 __device__ __forceinline__ void load_block(const T *tile, int r, int j0, int lane,
-                                           typename Elem<T>::vec (&v)[CH]) {
-  constexpr int TPL = Elem<T>::TPL;
+                                           typename SlabElem<T>::vec (&v)[CH]) {
+  constexpr int TPL = SlabElem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
   const char *base = reinterpret_cast<const char *>(tile);
   const unsigned lane_off = (unsigned)lane * (unsigned)(TPL * sizeof(T));
@@ -79,15 +79,15 @@ __device__ __forceinline__ void load_block(const T *tile, int r, int j0, int lan
   for (int j = 0; j < CH; ++j) {
     const int jj = min(j0 + j, r - 1);   // channels past r re-read the last plane; their query entry is 0
     const char *plane = base + (size_t)jj * (TILE * sizeof(T));
-    v[j] = *reinterpret_cast<const typename Elem<T>::vec *>(plane + lane_off);
+    v[j] = *reinterpret_cast<const typename SlabElem<T>::vec *>(plane + lane_off);
   }
 }
 
 // qblk: lane l holds the query entry of channel j0 + l (0 past r)
 template <typename T, int CH>
-__device__ __forceinline__ void fma_block(const typename Elem<T>::vec (&v)[CH], float qblk,
-                                          float (&acc)[Elem<T>::TPL]) {
-  constexpr int TPL = Elem<T>::TPL;
+__device__ __forceinline__ void fma_block(const typename SlabElem<T>::vec (&v)[CH], float qblk,
+                                          float (&acc)[SlabElem<T>::TPL]) {
+  constexpr int TPL = SlabElem<T>::TPL;
   const int qbits = __float_as_int(qblk);
 #if defined(IG_EXPERIMENT) && defined(IGX_NOFMA)
 #pragma unroll
@@ -108,9 +108,9 @@ __device__ __forceinline__ void fma_block(const typename Elem<T>::vec (&v)[CH], 
 // All channels of one tile for one wave: query loads, slab loads, then FMAs as the data arrives.
 template <typename T, int CH>
 __device__ __forceinline__ void scan_tile(const ScanArgs &a, const T *tile, int b, int h, int lane,
-                                          float (&acc)[Elem<T>::TPL]) {
-  constexpr int TPL = Elem<T>::TPL;
-  typename Elem<T>::vec v[CH];
+                                          float (&acc)[SlabElem<T>::TPL]) {
+  constexpr int TPL = SlabElem<T>::TPL;
+  typename SlabElem<T>::vec v[CH];
 #pragma unroll
   for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
   QueryLoads ql;
@@ -186,7 +186,7 @@ __device__ __forceinline__ int compact_block(const float (&sc)[TPL], int t0, int
 // One workgroup per (b,h); wave w scans tile w (nTiles <= NW) and keeps its scores in registers.
 template <typename T, int CH, int NW>
 __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
-  constexpr int TPL = Elem<T>::TPL;
+  constexpr int TPL = SlabElem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
   __shared__ float lds_max[NW];
   __shared__ int lds_cnt[NW];
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
 // go to a buffer, and select_count / select_write do the threshold pass.
 template <typename T, int CH>
 __global__ __launch_bounds__(256) void scan_tiles(ScanArgs a) {
-  constexpr int TPL = Elem<T>::TPL;
+  constexpr int TPL = SlabElem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
   const int bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
