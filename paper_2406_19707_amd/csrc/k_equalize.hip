@@ -7,7 +7,8 @@
 //   n      = clamp(floor(sum_h count[b,h] / H), 1, cap)
 //   T      = the n-th largest score of the head, found exactly by a most-significant-digit radix
 //            select on an order-preserving integer image of the float (4 passes of 8 bits, one
-//            256-bin LDS histogram each; the scores are re-read from L2, so N is unbounded)
+//            256-bin LDS histogram each).  The keys of a head stay in registers (KPT per thread)
+//            when they fit; longer sequences re-read the scores from L2 in every pass.
 //   list   = tokens with score > T, plus the earliest tokens with score == T until n are kept,
 //            written in ascending token order with ballot / bit-count prefix ranks.
 // Integer work after the scores: the result is exact for the scores given.
@@ -21,7 +22,7 @@ __device__ __forceinline__ unsigned score_key(float s) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-template <int THREADS>
+template <int THREADS, int KPT>
 __global__ __launch_bounds__(THREADS) void equalize_select(const float *__restrict__ scores,
                                                            const int32_t *__restrict__ thr_cnt,
                                                            int32_t *__restrict__ sel_idx,
@@ -50,6 +51,16 @@ __global__ __launch_bounds__(THREADS) void equalize_select(const float *__restri
   __syncthreads();
   const int n = max(1, min(min(s_total / H, cap), N));
 
+  // keys of tokens tid, tid + THREADS, ... (KPT of them) in registers; KPT == 0: re-read each pass
+  unsigned keys[KPT > 0 ? KPT : 1];
+  if (KPT > 0) {
+#pragma unroll
+    for (int i = 0; i < KPT; ++i) {
+      const int t = i * THREADS + tid;
+      keys[i] = t < N ? score_key(s[t]) : 0u;
+    }
+  }
+
   // ---- radix select of the n-th largest key ----
   unsigned prefix = 0;
   int need = n;
@@ -58,9 +69,17 @@ __global__ __launch_bounds__(THREADS) void equalize_select(const float *__restri
     const unsigned hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
     if (tid < 256) hist[tid] = 0;
     __syncthreads();
-    for (int t = tid; t < N; t += THREADS) {
-      const unsigned k = score_key(s[t]);
-      if ((k & hi_mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+    if (KPT > 0) {
+#pragma unroll
+      for (int i = 0; i < KPT; ++i) {
+        const unsigned k = keys[i];
+        if (i * THREADS + tid < N && (k & hi_mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+      }
+    } else {
+      for (int t = tid; t < N; t += THREADS) {
+        const unsigned k = score_key(s[t]);
+        if ((k & hi_mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+      }
     }
     __syncthreads();
     // bin d holds the target when (#keys in bins above d) < need <= (#keys in bins >= d)
@@ -94,9 +113,8 @@ __global__ __launch_bounds__(THREADS) void equalize_select(const float *__restri
   // ---- ordered compaction ----
   int base_out = 0, base_eq = 0;
   int32_t *list = sel_idx + (long)bh * stride;
-  for (int t0 = 0; t0 < N; t0 += THREADS) {
+  auto step = [&](int t0, unsigned k) {      // tokens t0 .. t0 + THREADS - 1, one per thread
     const int t = t0 + tid;
-    const unsigned k = t < N ? score_key(s[t]) : 0u;
     const bool gt = t < N && k > T, eq = t < N && k == T;
     const unsigned long long be = __ballot(eq);
     if (lane == 0) w_eq[w] = __popcll(be);
@@ -122,6 +140,13 @@ __global__ __launch_bounds__(THREADS) void equalize_select(const float *__restri
     if (keep && pos < stride) list[pos] = t;
     base_out += keep_all;
     base_eq += eq_all;
+  };
+  if constexpr (KPT > 0) {
+#pragma unroll
+    for (int it = 0; it < KPT; ++it)
+      if (it * THREADS < N) step(it * THREADS, keys[it]);     // wave-uniform condition
+  } else {
+    for (int t0 = 0; t0 < N; t0 += THREADS) step(t0, t0 + tid < N ? score_key(s[t0 + tid]) : 0u);
   }
   if (tid == 0) {
     sel_cnt[bh] = min(base_out, stride);
@@ -135,14 +160,17 @@ int ig_launch_equalize(ig_ctx *ctx, const ig_desc *d, const float *scores, const
                        int cap, int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
                        hipStream_t s) {
   const int BH = d->B * d->H;
-  if (d->N > 8192) {
-    auto k = equalize_select<1024>;
-    IG_LAUNCH(ctx, IG_K_SELECT, k, dim3(BH), dim3(1024), s, scores, thr_cnt, sel_idx, sel_cnt,
-              ctx->status, (int)d->H, (int)d->N, cap, (int)sel_stride);
-  } else {
-    auto k = equalize_select<256>;
-    IG_LAUNCH(ctx, IG_K_SELECT, k, dim3(BH), dim3(256), s, scores, thr_cnt, sel_idx, sel_cnt,
-              ctx->status, (int)d->H, (int)d->N, cap, (int)sel_stride);
+#define EQ_CASE(THREADS, KPT)                                                                      \
+  {                                                                                                \
+    auto k = equalize_select<THREADS, KPT>;                                                        \
+    IG_LAUNCH(ctx, IG_K_SELECT, k, dim3(BH), dim3(THREADS), s, scores, thr_cnt, sel_idx, sel_cnt,  \
+              ctx->status, (int)d->H, (int)d->N, cap, (int)sel_stride);                            \
+    return IG_OK;                                                                                  \
   }
-  return IG_OK;
+  if (d->N <= 256 * 8) EQ_CASE(256, 8)
+  if (d->N <= 256 * 16) EQ_CASE(256, 16)
+  if (d->N <= 1024 * 16) EQ_CASE(1024, 16)
+  if (d->N <= 1024 * 32) EQ_CASE(1024, 32)
+  EQ_CASE(1024, 0)
+#undef EQ_CASE
 }

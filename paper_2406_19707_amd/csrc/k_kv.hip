@@ -605,11 +605,6 @@ int ig_launch_gather(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const voi
   const size_t lds = (size_t)(BH + 1) * sizeof(int);
   if (lds > 60 * 1024) return ig_fail(ctx, IG_ESHAPE, "host gather: B*H = %d exceeds %d", BH, 60 * 256 - 1);
   int wgs = 128, threads = 256, batch = 8;
-#ifdef IG_EXPERIMENT
-  if (getenv("IG_HG_WGS")) wgs = atoi(getenv("IG_HG_WGS"));
-  if (getenv("IG_HG_THREADS")) threads = atoi(getenv("IG_HG_THREADS"));
-  if (getenv("IG_HG_BATCH")) batch = atoi(getenv("IG_HG_BATCH"));
-#endif
   dim3 grid(wgs), block(threads);
 #define HG_CASE(TH, BA)                                                                              \
   if (threads == TH && batch == BA) {                                                               \
@@ -630,10 +625,6 @@ int ig_launch_gather(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const voi
     return IG_OK;                                                                                   \
   }
   HG_CASE(256, 8)
-#ifdef IG_EXPERIMENT
-  HG_CASE(256, 4) HG_CASE(256, 2) HG_CASE(256, 1)
-  HG_CASE(64, 8) HG_CASE(64, 4) HG_CASE(64, 2) HG_CASE(64, 1)
-#endif
 #undef HG_CASE
   return ig_fail(ctx, IG_ESHAPE, "host gather: unsupported launch shape");
 }

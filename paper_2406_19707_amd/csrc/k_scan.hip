@@ -89,14 +89,6 @@ __device__ __forceinline__ void fma_block(const typename SlabElem<T>::vec (&v)[C
                                           float (&acc)[SlabElem<T>::TPL]) {
   constexpr int TPL = SlabElem<T>::TPL;
   const int qbits = __float_as_int(qblk);
-#if defined(IG_EXPERIMENT) && defined(IGX_NOFMA)
-#pragma unroll
-  for (int j = 0; j < CH; ++j) {
-    const float qj = __int_as_float(__builtin_amdgcn_readlane(qbits, j));
-    acc[j % TPL] = fmaf((float)v[j][0], qj, acc[j % TPL]);
-  }
-  return;
-#endif
 #pragma unroll
   for (int j = 0; j < CH; ++j) {
     const float qj = __int_as_float(__builtin_amdgcn_readlane(qbits, j));
@@ -114,16 +106,10 @@ __device__ __forceinline__ void scan_tile(const ScanArgs &a, const T *tile, int 
 #pragma unroll
   for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
   QueryLoads ql;
-#if defined(IG_EXPERIMENT) && defined(IGX_NOQ)
-  load_block<T, CH>(tile, a.r, 0, lane, v);
-  float qv[4];
-  qv[0] = (lane < a.r ? 0.01f * (float)(lane - 19) : 0.f) * a.scale;
-#else
   query_issue(a, b, h, lane, 0, ql);
   load_block<T, CH>(tile, a.r, 0, lane, v);
   float qv[4];
   qv[0] = query_finish(a, ql);
-#endif
   qv[1] = qv[2] = qv[3] = 0.f;
   if (a.r <= CH) {           // the usual case: one block, lane l already holds channel l
     fma_block<T, CH>(v, qv[0], acc);
@@ -139,6 +125,24 @@ __device__ __forceinline__ void scan_tile(const ScanArgs &a, const T *tile, int 
   for (int j0 = CH; j0 < a.r; j0 += CH) {
     load_block<T, CH>(tile, a.r, j0, lane, v);
     fma_block<T, CH>(v, query_block(qv, j0, lane), acc);
+  }
+}
+
+// A lane's TPL consecutive scores go out as 16-byte stores when the run is whole and aligned.
+template <int TPL>
+__device__ __forceinline__ void store_scores(float *dst /* score of token 0 of the head */, long head_off,
+                                             int t, int N, const float (&acc)[TPL]) {
+  float *p = dst + head_off + t;
+  if (t + TPL <= N && ((head_off + t) & 3) == 0) {
+#pragma unroll
+    for (int e = 0; e < TPL; e += 4) {
+      floatx4 v = {acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+      *reinterpret_cast<floatx4 *>(p + e) = v;
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < TPL; ++e)
+      if (t + e < N) p[e] = acc[e];
   }
 }
 
@@ -199,16 +203,6 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
 #pragma unroll
   for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
   if (active) scan_tile<T, CH>(a, tile, b, h, lane, acc);
-#if defined(IG_EXPERIMENT) && defined(IGX_STOP1)
-  {
-    float m1 = acc[0];
-#pragma unroll
-    for (int e = 1; e < TPL; ++e) m1 = fmaxf(m1, acc[e]);
-    m1 = wave_max(m1);
-    if (lane == 0) a.sel_idx[(long)bh * a.sel_stride + w] = __float_as_int(m1);
-    return;
-  }
-#endif
   const int t0 = w * TILE;
   float m = -INFINITY;
 #pragma unroll
@@ -217,13 +211,7 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
     if (!active || t >= a.N) acc[e] = -INFINITY;
     m = fmaxf(m, acc[e]);
   }
-  if (a.scores_out && active) {
-#pragma unroll
-    for (int e = 0; e < TPL; ++e) {
-      int t = t0 + lane * TPL + e;
-      if (t < a.N) a.scores_out[(long)bh * a.N + t] = acc[e];
-    }
-  }
+  if (a.scores_out && active) store_scores<TPL>(a.scores_out, (long)bh * a.N, t0 + lane * TPL, a.N, acc);
   m = wave_max(m);
   if (lane == 0) lds_max[w] = m;
   __syncthreads();
@@ -253,15 +241,11 @@ __global__ __launch_bounds__(256) void scan_tiles(ScanArgs a) {
   float acc[TPL];
   scan_tile<T, CH>(a, tile, b, h, lane, acc);
   const int t0 = tileno * TILE;
+  store_scores<TPL>(a.scores_out, (long)bh * a.N, t0 + lane * TPL, a.N, acc);
   float m = -INFINITY;
 #pragma unroll
-  for (int e = 0; e < TPL; ++e) {
-    int t = t0 + lane * TPL + e;
-    if (t < a.N) {
-      a.scores_out[(long)bh * a.N + t] = acc[e];
-      m = fmaxf(m, acc[e]);
-    }
-  }
+  for (int e = 0; e < TPL; ++e)
+    if (t0 + lane * TPL + e < a.N) m = fmaxf(m, acc[e]);
   m = wave_max(m);
   if (lane == 0) a.tmax[(long)bh * a.nTiles + tileno] = m;
 }
@@ -417,15 +401,6 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
   // Fused when a (b,h) fits one workgroup and there are enough (b,h) pairs to fill the chip;
   // otherwise one wave per tile so that long sequences spread over all compute units.
   bool fused = nTiles <= 16 && (BH >= 128 || nTiles <= 4);
-#ifdef IG_EXPERIMENT
-  const int cap_o = getenv("IG_CAP") ? atoi(getenv("IG_CAP")) : 0;
-  if (getenv("IG_FORCE_TILED")) fused = false;
-  if (fused && cap_o) {
-    if (nTiles <= 4) return launch_fused<T, 4>(ctx, a, BH, pick_ch(d->r, cap_o), s);
-    if (nTiles <= 8) return launch_fused<T, 8>(ctx, a, BH, pick_ch(d->r, cap_o), s);
-    return launch_fused<T, 16>(ctx, a, BH, pick_ch(d->r, cap_o), s);
-  }
-#endif
   if (fused) {
     // When all workgroups fit on the chip at once (one round) a wave should have all its channels
     // in flight; with several rounds, smaller blocks leave room for more resident workgroups whose
@@ -444,9 +419,6 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
   int rc = ig_ensure(ctx, (void **)&ctx->tmax, &ctx->tmax_bytes, need_m);
   if (rc) return rc;
   a.tmax = ctx->tmax;
-#ifdef IG_EXPERIMENT
-  if (cap_o) return launch_tiles<T>(ctx, a, BH, pick_ch(d->r, cap_o), s);
-#endif
   return launch_tiles<T>(ctx, a, BH, pick_ch(d->r, 40), s);
 }
 
