@@ -50,8 +50,9 @@ def main():
                     help="also launch a plain 256 MiB device copy (reference for scaling hardware counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (--gpus 1); the path shards over (sequence, "
-              "head) pairs without communication, see DESIGN.md", file=sys.stderr)
+        print("bench.py: this build runs on one GPU only (--gpus 1); the path would shard over "
+              "(sequence, head) pairs without communication, but no multi-GPU run is part of it",
+              file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
