@@ -112,6 +112,14 @@ int ig_skew_offline(ig_ctx *ctx, int D, int H, int n_cal, const float *Wq, const
 int ig_partial_index(ig_ctx *ctx, int H, int d, int n, const float *Qs, const float *Ks,
                      double ratio, int32_t *idx, int32_t *r_out);
 
+/* The same index generation on the GPU, for a prompt whose skewed queries / keys are device
+ * arrays Qs, Ks [n, H*d] of `dtype` (Ks may be NULL): idx_dev receives int32 [H, r],
+ * r = floor(ratio*d), d <= 256.  Sums are float32 in a fixed order (repeatable bit for bit); two
+ * columns whose sums agree to float32 rounding may rank differently than in ig_partial_index.
+ * May allocate workspace on the first call. */
+int ig_partial_index_device(ig_ctx *ctx, int dtype, int H, int d, int n, const void *Qs,
+                            const void *Ks, double ratio, int32_t *idx_dev, void *stream);
+
 /* ---- setup on the device ------------------------------------------------------------------ */
 
 /* Partial query weight (Section 4.3 "Prefill Stage"): the kept columns of the skewed query

@@ -229,6 +229,23 @@ int ig_wq_build(ig_ctx *ctx, const ig_desc *d, const void *Wq, const int32_t *id
   return ig_launch_wq_build(ctx, d, ig_proj_geom(d), Wq, idx_dev, wq, (hipStream_t)stream);
 }
 
+int ig_partial_index_device(ig_ctx *ctx, int dtype, int H, int d, int n, const void *Qs,
+                            const void *Ks, double ratio, int32_t *idx_dev, void *stream) {
+  if (!ctx) return IG_EINVAL;
+  if (dtype != IG_F32 && dtype != IG_F16) return ig_fail(ctx, IG_EDTYPE, "unknown dtype %d", dtype);
+  if (H < 1 || d < 1 || n < 1) return ig_fail(ctx, IG_ESHAPE, "ig_partial_index_device: bad shape");
+  if (d > 256) return ig_fail(ctx, IG_ESHAPE, "ig_partial_index_device: d = %d exceeds 256", d);
+  if (!Qs || !idx_dev) return ig_fail(ctx, IG_EINVAL, "ig_partial_index_device: NULL argument");
+  if (!(ratio > 0.0) || ratio > 1.0) return ig_fail(ctx, IG_EINVAL, "ratio must be in (0, 1]");
+  const int r = (int)floor(ratio * (double)d);
+  if (r < 1) return ig_fail(ctx, IG_ESHAPE, "ratio * d < 1");
+  int rc = set_device(ctx);
+  if (rc) return rc;
+  // the partial column sums share the projection's workspace (both are transient)
+  if ((rc = ig_ensure(ctx, (void **)&ctx->part, &ctx->part_bytes, ig_partial_index_workspace(H, d)))) return rc;
+  return ig_launch_partial_index(ctx, dtype, H, d, n, Qs, Ks, r, ctx->part, idx_dev, (hipStream_t)stream);
+}
+
 size_t ig_slab_bytes(const ig_desc *d) {
   if (!d || d->B < 1 || d->H < 1 || d->r < 1 || d->N_cap < 1) return 0;
   const int tile = ig_tile_tokens(d->dtype);

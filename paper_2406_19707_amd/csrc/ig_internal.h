@@ -150,6 +150,9 @@ int ig_launch_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
 int ig_launch_equalize(ig_ctx *ctx, const ig_desc *d, const float *scores, const int32_t *thr_cnt,
                        int cap, int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
                        hipStream_t s);
+int ig_launch_partial_index(ig_ctx *ctx, int dtype, int H, int d, int n, const void *Qs, const void *Ks,
+                            int r, float *part, int32_t *idx, hipStream_t s);
+size_t ig_partial_index_workspace(int H, int d);
 int ig_launch_copy(ig_ctx *ctx, const void *src, void *dst, size_t bytes, hipStream_t s);
 int ig_launch_read(ig_ctx *ctx, const void *src, size_t bytes, hipStream_t s);
 
