@@ -116,6 +116,28 @@ def test_many_heads_fused_eight_and_sixteen_waves(ctx, N):
     check_case(ctx, make_case(w, gain=6.0))
 
 
+@pytest.mark.parametrize("ratio,all_columns", [(0.6, False), (1.0, True)])
+def test_wide_partial_queries_more_than_64_columns(ctx, ratio, all_columns):
+    # r = 76 and r = 128: the partial query spans two per-lane registers and several channel blocks
+    w = wl.shrink(wl.WORKLOADS[2], B=2, H=4, N=1100, ratio=ratio)
+    check_case(ctx, make_case(w, gain=3.0, all_columns=all_columns))
+
+
+def test_wide_partial_queries_long_sequence_tiled_path(ctx):
+    w = wl.shrink(wl.WORKLOADS[5], B=1, H=2, N=9000, ratio=0.7)     # r = 89, one wave per tile
+    check_case(ctx, make_case(w, gain=3.0))
+
+
+def test_head_dimension_256_and_odd_head_count(ctx):
+    w = wl.shrink(wl.WORKLOADS[2], B=2, H=3, d=256, N=700, n_cal=384, heavy_count=8)   # r = 76, 512-byte rows
+    check_case(ctx, make_case(w, gain=4.0))
+
+
+def test_many_pairs_small_heads(ctx):
+    w = wl.shrink(wl.WORKLOADS[2], B=24, H=64, d=16, N=520, n_cal=64, heavy_count=6)   # 1536 pairs, r = 4
+    check_case(ctx, make_case(w, gain=2.0))
+
+
 def test_cfg3_shape_rope_f16(ctx):
     w = wl.shrink(wl.WORKLOADS[3], B=2, H=4, N=4096)
     check_case(ctx, make_case(w, gain=24.0))
