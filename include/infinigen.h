@@ -116,7 +116,8 @@ int ig_partial_index(ig_ctx *ctx, int H, int d, int n, const float *Qs, const fl
  * arrays Qs, Ks [n, H*d] of `dtype` (Ks may be NULL): idx_dev receives int32 [H, r],
  * r = floor(ratio*d), d <= 256.  Sums are float32 in a fixed order (repeatable bit for bit); two
  * columns whose sums agree to float32 rounding may rank differently than in ig_partial_index.
- * May allocate workspace on the first call. */
+ * Uses (and may grow, which allocates and synchronises) the context's projection workspace: a
+ * prefill-time call, not to be issued between ig_reserve and a captured decode step. */
 int ig_partial_index_device(ig_ctx *ctx, int dtype, int H, int d, int n, const void *Qs,
                             const void *Ks, double ratio, int32_t *idx_dev, void *stream);
 
