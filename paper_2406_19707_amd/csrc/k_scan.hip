@@ -27,6 +27,12 @@ struct ScanArgs {
   int H, r, N, nTiles;
   int sel_stride;
   float scale, alpha;
+  // rotary models, fused path: the workgroup derives its partial query itself from the full
+  // projection's split-K partial sums (qsrc: [ks][b][D] columns), see rope_query()
+  const float *A_p;    // [H, d, r] kept columns of the skewing matrices, or NULL (not this mode)
+  const int32_t *pos;  // [B]
+  int d;
+  float theta;
 };
 
 // Partial query of (b,h), kept in registers: lane l of every scanning wave holds q[l + 64*k], k < 4
@@ -128,6 +134,76 @@ __device__ __forceinline__ void scan_tile(const ScanArgs &a, const T *tile, int 
   }
 }
 
+// The same with the query already in registers (qv[k]: scaled entry of channel lane + 64*k) and
+// the first channel block already loaded into v.
+template <typename T, int CH>
+__device__ __forceinline__ void scan_tile_given_q(const ScanArgs &a, const T *tile, int lane,
+                                                  typename SlabElem<T>::vec (&v)[CH], const float (&qv)[4],
+                                                  float (&acc)[SlabElem<T>::TPL]) {
+  if (a.r <= CH) {
+    fma_block<T, CH>(v, qv[0], acc);
+    return;
+  }
+  fma_block<T, CH>(v, query_block(qv, 0, lane), acc);
+  for (int j0 = CH; j0 < a.r; j0 += CH) {
+    load_block<T, CH>(tile, a.r, j0, lane, v);
+    fma_block<T, CH>(v, query_block(qv, j0, lane), acc);
+  }
+}
+
+// Partial query of a rotary model, computed by the whole workgroup (THREADS threads) into LDS
+// (Section 4.3 "Decoding Stage" for models whose skew cannot be folded into W_Q):
+//   q[c]   = bias[h*d+c] + sum_s part[s][b][h*d+c]            (split-K sums in a fixed order)
+//   rotate pairs (c, c+d/2) by pos[b]*theta^(-2c/d)            (angle in double)
+//   q_p[k] = sum_c q_rot[c] * A_p[h][c][k]                     (rows split over thread groups, added in order)
+// Same arithmetic as the stand-alone finalisation kernel; only the number of row groups differs.
+// q_lds, qr_lds: d floats each; psum: THREADS floats; result: qp_lds[k], k < r (unscaled).
+template <int THREADS>
+__device__ __forceinline__ void rope_query(const ScanArgs &a, int b, int h, float *q_lds, float *qr_lds,
+                                           float *psum, float *qp_lds) {
+  const int t = threadIdx.x, d = a.d, r = a.r;
+  for (int c = t; c < d; c += THREADS) {
+    const float *p = a.qsrc + (long)b * a.b_stride + (long)h * d + c;
+    float v[IG_KS_MAX];
+#pragma unroll
+    for (int s = 0; s < IG_KS_MAX; ++s) v[s] = (s < a.ks) ? p[(long)s * a.ks_stride] : 0.f;
+    float acc = a.bias ? a.bias[h * d + c] : 0.f;
+#pragma unroll
+    for (int s = 0; s < IG_KS_MAX; ++s) acc += v[s];
+    q_lds[c] = acc;
+  }
+  __syncthreads();
+  const int half = d / 2;
+  for (int c = t; c < half; c += THREADS) {
+    const double ang = (double)a.pos[b] * exp2(-2.0 * (double)c / (double)d * log2((double)a.theta));
+    double sn, cs;
+    sincos(ang, &sn, &cs);
+    const float x0 = q_lds[c], x1 = q_lds[c + half];
+    qr_lds[c] = (float)((double)x0 * cs - (double)x1 * sn);
+    qr_lds[c + half] = (float)((double)x1 * cs + (double)x0 * sn);
+  }
+  __syncthreads();
+  const int RK = r <= 64 ? 64 : (r <= 128 ? 128 : 256);
+  const int G = THREADS / RK;
+  const int k = t % RK, g = t / RK;
+  const int per = (d + G - 1) / G;
+  float acc = 0.f;
+  if (k < r) {
+    const float *ap = a.A_p + (long)h * d * r + k;
+    const int c1 = min(d, (g + 1) * per);
+#pragma unroll 8
+    for (int c = min(d, g * per); c < c1; ++c) acc = fmaf(qr_lds[c], ap[(long)c * r], acc);
+  }
+  psum[t] = acc;
+  __syncthreads();
+  if (t < r) {
+    float tot = 0.f;
+    for (int gg = 0; gg < G; ++gg) tot += psum[gg * RK + t];
+    qp_lds[t] = tot;
+  }
+  __syncthreads();
+}
+
 // A lane's TPL consecutive scores go out as 16-byte stores when the run is whole and aligned.
 template <int TPL>
 __device__ __forceinline__ void store_scores(float *dst /* score of token 0 of the head */, long head_off,
@@ -188,7 +264,7 @@ __device__ __forceinline__ int compact_block(const float (&sc)[TPL], int t0, int
 }
 
 // One workgroup per (b,h); wave w scans tile w (nTiles <= NW) and keeps its scores in registers.
-template <typename T, int CH, int NW>
+template <typename T, int CH, int NW, bool ROPE>
 __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
   constexpr int TPL = SlabElem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
@@ -202,7 +278,22 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
   float acc[TPL];
 #pragma unroll
   for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
-  if (active) scan_tile<T, CH>(a, tile, b, h, lane, acc);
+  if constexpr (ROPE) {
+    // rotary model: the first channel block is put in flight, then all waves work out the
+    // partial query together while it travels
+    __shared__ float q_lds[512], qr_lds[512], psum[NW * 64], qp_lds[256];
+    typename SlabElem<T>::vec v[CH];
+    if (active) load_block<T, CH>(tile, a.r, 0, lane, v);
+    rope_query<NW * 64>(a, b, h, q_lds, qr_lds, psum, qp_lds);
+    if (active) {
+      float qv[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) qv[k] = (lane + 64 * k < a.r) ? qp_lds[lane + 64 * k] * a.scale : 0.f;
+      scan_tile_given_q<T, CH>(a, tile, lane, v, qv, acc);
+    }
+  } else if (active) {
+    scan_tile<T, CH>(a, tile, b, h, lane, acc);
+  }
   const int t0 = w * TILE;
   float m = -INFINITY;
 #pragma unroll
@@ -344,8 +435,13 @@ int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
   dim3 grid(BH), block(NW * 64);
 #define CASE(CHV)                                                              \
   case CHV: {                                                                  \
-    auto k = scan_select_fused<T, CHV, NW>;                                    \
-    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                           \
+    if (a.A_p) {                                                               \
+      auto k = scan_select_fused<T, CHV, NW, true>;                            \
+      IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                         \
+    } else {                                                                   \
+      auto k = scan_select_fused<T, CHV, NW, false>;                           \
+      IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                         \
+    }                                                                          \
     return IG_OK;                                                              \
   }
   // registers per wave shrink as the workgroup grows: 4 waves allow 40 loads in flight, 8 waves 24,
@@ -400,7 +496,7 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
   const int nTiles = a.nTiles;
   // Fused when a (b,h) fits one workgroup and there are enough (b,h) pairs to fill the chip;
   // otherwise one wave per tile so that long sequences spread over all compute units.
-  bool fused = nTiles <= 16 && (BH >= 128 || nTiles <= 4);
+  const bool fused = ig_scan_is_fused(d);
   if (fused) {
     // When all workgroups fit on the chip at once (one round) a wave should have all its channels
     // in flight; with several rounds, smaller blocks leave room for more resident workgroups whose
@@ -423,6 +519,15 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
 }
 
 }  // namespace
+
+// Fused (one workgroup per (b,h), scores never leave registers) when a (b,h) fits 16 waves and
+// there are enough pairs to fill the chip; otherwise one wave per tile.
+bool ig_scan_is_fused(const ig_desc *d) {
+  const int tile = ig_tile_tokens(d->dtype);
+  const int nTiles = (d->N_cap + tile - 1) / tile;
+  const int BH = d->B * d->H;
+  return nTiles <= 16 && (BH >= 128 || nTiles <= 4);
+}
 
 int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const void *slab,
                           int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
@@ -447,6 +552,12 @@ int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const
   a.sel_stride = sel_stride;
   a.scale = d->scale;
   a.alpha = d->alpha;
+  a.A_p = q.A_p;
+  a.pos = q.pos;
+  a.d = d->d;
+  a.theta = d->rope_theta;
+  if (q.A_p && !ig_scan_is_fused(d)) return ig_fail(ctx, IG_EINVAL, "scan: rotary query source needs the fused path");
+  if (q.A_p && d->d > 512) return ig_fail(ctx, IG_ESHAPE, "rope: d = %d exceeds 512", d->d);
   if (d->r > 256) return ig_fail(ctx, IG_ESHAPE, "r = %d exceeds 256", d->r);
   if (q.ks < 1 || q.ks > IG_KS_MAX) return ig_fail(ctx, IG_ESHAPE, "split-K %d out of range", q.ks);
   return d->dtype == IG_F16 ? launch_scan<half_t>(ctx, d, a, s) : launch_scan<float>(ctx, d, a, s);
