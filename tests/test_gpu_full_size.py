@@ -53,7 +53,16 @@ def test_cfg2_full_size_sampled_pairs_and_properties():
     ctx.ig_gather_kv(d, Kd, Vd, ig.IG_MEM_DEVICE, sel_idx, w.N, sel_cnt, K_sel, V_sel)
     ctx.ig_sparse_attention(d, qd, K_sel, V_sel, sel_cnt, w.N, None, None, out)
     ctx.ig_sparse_attention_indexed(d, qd, Kd, Vd, sel_idx, w.N, sel_cnt, None, None, out_idx)
+    # the form bench.py's `value` uses: rehearsal without the score dump, then prefetch and
+    # attention in one pass
+    sel_idx2, sel_cnt2 = torch.full_like(sel_idx, -1), torch.zeros_like(sel_cnt)
+    K_one, V_one, out_one = torch.zeros_like(K_sel), torch.zeros_like(V_sel), torch.zeros_like(out)
+    ctx.ig_speculate(d, x, wq, None, None, None, slab, sel_idx2, w.N, sel_cnt2, None)
+    ctx.ig_gather_attention(d, qd, Kd, Vd, sel_idx2, w.N, sel_cnt2, K_one, V_one, None, None, out_one)
     torch.cuda.synchronize()
+    assert torch.equal(sel_cnt, sel_cnt2) and torch.equal(sel_idx, sel_idx2)
+    assert torch.equal(K_one, K_sel) and torch.equal(V_one, V_sel)
+    assert torch.equal(out_one, out_idx)
     assert ctx.ig_check_status() == ig.IG_OK
     g_idx, g_cnt = sel_idx.cpu().numpy(), sel_cnt.cpu().numpy()
     g_s = scores.cpu().numpy().reshape(BH, w.N)
