@@ -133,8 +133,8 @@ __global__ __launch_bounds__(256) void pool_victim(const int32_t *__restrict__ c
 
 // ---- work split shared by gather and attention --------------------------------------------------
 // Selected-token lists are very uneven (a few heads keep a thousand rows, most a few dozen), and
-// one compute unit moves well under 100 GB/s, so a list is cut into up to gridDim.y slices of at
-// most SLICE_ROWS rows where possible: slices = min(gridDim.y, ceil(rows / SLICE_ROWS)), slice s
+// one compute unit moves well under 100 GB/s, so a list is cut into up to SLICE_MAX slices of at
+// most SLICE_ROWS rows where possible: slices = min(SLICE_MAX, ceil(rows / SLICE_ROWS)), slice s
 // covering rows [rows*s/slices, rows*(s+1)/slices).  Every workgroup derives this from the
 // device-side count, so the host never reads the counts; surplus workgroups leave at once.
 //
@@ -169,8 +169,7 @@ __device__ __forceinline__ bool slice_range(int rows, int s, int max_slices, int
 // ---- gather, device-resident pool ---------------------------------------------------------------
 // Row copies in 16-byte units, U units per row; grid B*H*SLICE_MAX (see work_item).  A thread's copies are
 // issued in batches of GATHER_BATCH, so that index loads, then K and V row loads, are in flight
-// together (this is also what keeps enough PCIe reads outstanding when the pool is pinned host
-// memory).
+// together.
 constexpr int GATHER_BATCH = 8;
 __global__ __launch_bounds__(256) void gather_rows_sliced(
     const u128 *__restrict__ Kpool, const u128 *__restrict__ Vpool, const int32_t *__restrict__ sel_idx,

@@ -8,6 +8,10 @@
 // issues one fully coalesced 1 KiB load (lane l gets tokens l*TPL .. l*TPL+TPL-1 of that channel)
 // and multiplies by the wave-uniform partial query entry, so a token's score is accumulated in
 // one lane without any cross-lane reduction.  The kernel is HBM-bound (1 FMA per 2 bytes).
+//
+// The partial query comes from the projection's split-K partial sums, added here in a fixed order
+// (no separate reduction kernel); for rotary models on the fused path the workgroup also applies
+// the rotation and the partial skew itself (rope_query) while its first slab loads are in flight.
 #include "ig_internal.h"
 
 namespace {
