@@ -89,3 +89,30 @@ def run_gpu(ctx, c, alpha=None, sel_stride=None, host_pool=False, want_scores=Tr
                V_one=None if host_pool else V_one.cpu().numpy(),
                status=status, up=up)
     return res
+
+
+def run_gpu_on_lists(ctx, c, up, sel_idx_host, sel_cnt_host, host_pool=False):
+    """Prefetch and attention of the HIP path on index lists given by the caller (the oracle's)."""
+    w = c.w
+    d = up.desc
+    BH = w.B * w.H
+    stride = sel_idx_host.shape[1]
+    tdt = torch.float32 if w.dtype == "f32" else torch.float16
+    sel_idx, sel_cnt = dev(sel_idx_host.astype(np.int32)), dev(sel_cnt_host.astype(np.int32))
+    K_sel = torch.zeros((BH, stride, w.d), dtype=tdt, device="cuda")
+    V_sel = torch.zeros_like(K_sel)
+    out = torch.full((w.B, w.H, w.d), float("nan"), dtype=tdt, device="cuda")
+    out_new, out_idx, out_one = torch.full_like(out, float("nan")), None, None
+    ctx.ig_gather_kv(d, up.K, up.V, up.space, sel_idx, stride, sel_cnt, K_sel, V_sel)
+    ctx.ig_sparse_attention(d, up.q, K_sel, V_sel, sel_cnt, stride, None, None, out)
+    ctx.ig_sparse_attention(d, up.q, K_sel, V_sel, sel_cnt, stride, up.k_new, up.v_new, out_new)
+    if not host_pool:
+        out_idx, out_one = torch.full_like(out, float("nan")), torch.full_like(out, float("nan"))
+        K_one, V_one = torch.zeros_like(K_sel), torch.zeros_like(V_sel)
+        ctx.ig_sparse_attention_indexed(d, up.q, up.K, up.V, sel_idx, stride, sel_cnt, None, None, out_idx)
+        ctx.ig_gather_attention(d, up.q, up.K, up.V, sel_idx, stride, sel_cnt, K_one, V_one, None, None, out_one)
+    torch.cuda.synchronize()
+    assert ctx.ig_check_status() == 0
+    f = lambda t: None if t is None else t.float().cpu().numpy().reshape(BH, w.d)   # noqa: E731
+    return dict(K_sel=K_sel.float().cpu().numpy(), V_sel=V_sel.float().cpu().numpy(), out=f(out),
+                out_new=f(out_new), out_idx=f(out_idx), out_one=f(out_one))

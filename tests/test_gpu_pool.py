@@ -99,7 +99,10 @@ def test_full_cache_keeps_decoding_with_eviction(ctx, cfg, shape, gain, N, T, ho
         ref = OracleResult(q_p, s, r_idx, r_cnt, None, None, None, None)
         g_idx, g_cnt = sel_idx.cpu().numpy(), sel_cnt.cpu().numpy()
         slack = compare_selection(g_idx, g_cnt, ref, w.alpha)
-        o.pool_touch(ref_counters, g_idx, g_cnt, N, counter_max=3)     # counters follow the lists that were prefetched
+        # the counters follow the lists that were prefetched; the oracle's own lists are used, which
+        # are the GPU's whenever no score sits within 1e-3 of a threshold (true for these seeds)
+        assert slack == 0, "a score inside the threshold band: pick another seed for this exact comparison"
+        o.pool_touch(ref_counters, r_idx, r_cnt, N, counter_max=3)
         vic = o.pool_victim(ref_counters, N)
         assert np.array_equal(victim.cpu().numpy(), vic), step
         for i in range(BH):
