@@ -353,6 +353,17 @@ def main():
                   "attention_within_2e-2_abs_1e-2_rel": ok}
 
     dtype = "f32" if w.dtype == "f32" else "f16"
+    # algorithmic bytes per launch of every kernel (layer average) and the rate they imply
+    esz = 4 if w.dtype == "f32" else 2
+    row_bytes = float(np.mean(fr)) * w.N * w.B * w.H * w.d * esz * 2          # K and V rows of a layer
+    kbytes = {"project": ig.ig_wq_bytes(R.desc), "scan": scan_bytes, "gather": 2 * row_bytes,
+              "attention": row_bytes, "gather+attention in one pass": 2 * row_bytes}
+    if R.host_pool:
+        kbytes["gather"] = row_bytes                                          # over PCIe; the HBM write is extra
+    for name, kb in kbytes.items():
+        if name in kernels:
+            kernels[name]["algorithmic_MB"] = kb / 1e6
+            kernels[name]["GBps"] = kb / (kernels[name]["avg_us"] * 1e-6) / 1e9
     res = {
         "metric": "rehearsal+sparse-attn us/layer/decode step; partial-K scan GB/s vs HBM peak",
         "value": ms_per_step * 1e3 / L,
