@@ -89,7 +89,8 @@ const char *ig_last_error(const ig_ctx *ctx);
 /* Size the context's workspaces for `desc` now (allocates; synchronous). */
 int ig_reserve(ig_ctx *ctx, const ig_desc *desc);
 /* Synchronise the device and report sticky device-side conditions: IG_ECAPACITY if any list was
- * clamped to sel_stride since the last check, else IG_OK.  Clears the condition. */
+ * clamped to sel_stride since the last check, IG_ENOCONV if ig_skew_device did not converge, else
+ * IG_OK.  Clears the conditions. */
 int ig_check_status(ig_ctx *ctx);
 
 /* ---- offline / prefill helpers (host pointers, float32, synchronous, CPU) ----------------- */
@@ -111,6 +112,14 @@ int ig_skew_offline(ig_ctx *ctx, int D, int H, int n_cal, const float *Wq, const
  * Ties go to the lower column. */
 int ig_partial_index(ig_ctx *ctx, int H, int d, int n, const float *Qs, const float *Ks,
                      double ratio, int32_t *idx, int32_t *r_out);
+
+/* Offline skewing on the GPU: the same A [H,d,d] and sigma [H,d] (may be NULL) as ig_skew_offline,
+ * from device arrays (Qcal float32 [n_cal, D]); d even, at most 256.  All arithmetic in double;
+ * a fixed number of parallel Jacobi sweeps; if they leave off-diagonal mass above tolerance the
+ * next ig_check_status returns IG_ENOCONV.  Allocates a double-precision workspace on first use.
+ * The weights are skewed by the caller (W~ = W * blockdiag(A)), a plain batched product. */
+int ig_skew_device(ig_ctx *ctx, int D, int H, int n_cal, const float *Qcal, float *A, float *sigma,
+                   void *stream);
 
 /* The same index generation on the GPU, for a prompt whose skewed queries / keys are device
  * arrays Qs, Ks [n, H*d] of `dtype` (Ks may be NULL): idx_dev receives int32 [H, r],

@@ -29,7 +29,7 @@ IG_MEM_DEVICE, IG_MEM_HOST_PINNED = 0, 1
 # every symbol include/infinigen.h declares
 EXPORTS = [
     "ig_create", "ig_destroy", "ig_last_error", "ig_reserve", "ig_check_status", "ig_skew_offline",
-    "ig_partial_index", "ig_partial_index_device", "ig_wq_bytes", "ig_wq_build", "ig_slab_bytes",
+    "ig_partial_index", "ig_skew_device", "ig_partial_index_device", "ig_wq_bytes", "ig_wq_build", "ig_slab_bytes",
     "ig_slab_build", "ig_append_token",
     "ig_pool_touch", "ig_pool_victim", "ig_pool_replace",
     "ig_speculate", "ig_project", "ig_scan_select", "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention",
@@ -83,6 +83,7 @@ def lib():
             "ig_skew_offline": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int] + [_vp] * 11),
             "ig_partial_index": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp,
                                                 ctypes.c_double, _vp, ctypes.POINTER(_i32)]),
+            "ig_skew_device": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp, _vp, _vp]),
             "ig_partial_index_device": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                                        ctypes.c_int, _vp, _vp, ctypes.c_double, _vp, _vp]),
             "ig_wq_bytes": (_sz, [_dp]),
@@ -229,6 +230,10 @@ class Context:
     def ig_slab_build(self, desc, Kpool, pool_space, idx_dev, slab, stream=None):
         self._ck(lib().ig_slab_build(self._h, ctypes.byref(desc), _ptr(Kpool), pool_space,
                                      _ptr(idx_dev), _ptr(slab), _stream(stream)))
+
+    def ig_skew_device(self, D, H, n_cal, Qcal, A, sigma=None, stream=None):
+        self._ck(lib().ig_skew_device(self._h, D, H, n_cal, _ptr(Qcal), _ptr(A), _ptr(sigma),
+                                      _stream(stream)))
 
     def ig_partial_index_device(self, dtype, H, d, n, Qs, Ks, ratio, idx_dev, stream=None):
         self._ck(lib().ig_partial_index_device(self._h, dtype, H, d, n, _ptr(Qs), _ptr(Ks),

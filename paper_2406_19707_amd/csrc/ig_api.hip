@@ -154,6 +154,8 @@ int ig_create(int device, ig_ctx **out) {
   ctx->attn_cnt = nullptr;
   ctx->pcount = nullptr;
   ctx->pcount_bytes = 0;
+  ctx->skew_ws = nullptr;
+  ctx->skew_ws_bytes = 0;
   ctx->attn_part_bytes = ctx->attn_cnt_bytes = 0;
   ctx->part_bytes = ctx->qp_bytes = ctx->scores_bytes = ctx->tmax_bytes = 0;
   ctx->status = nullptr;
@@ -183,6 +185,7 @@ int ig_destroy(ig_ctx *ctx) {
   if (ctx->scores) (void)hipFree(ctx->scores);
   if (ctx->tmax) (void)hipFree(ctx->tmax);
   if (ctx->pcount) (void)hipFree(ctx->pcount);
+  if (ctx->skew_ws) (void)hipFree(ctx->skew_ws);
   if (ctx->attn_part) (void)hipFree(ctx->attn_part);
   if (ctx->attn_cnt) (void)hipFree(ctx->attn_cnt);
   if (ctx->status) (void)hipFree(ctx->status);
@@ -209,6 +212,8 @@ int ig_check_status(ig_ctx *ctx) {
   if (st) IG_HIP(ctx, hipMemset(ctx->status, 0, sizeof(st)));
   if (st & IG_STATUS_CAPACITY)
     return ig_fail(ctx, IG_ECAPACITY, "a selected-token list was longer than sel_stride and was clamped");
+  if (st & IG_STATUS_NOCONV)
+    return ig_fail(ctx, IG_ENOCONV, "ig_skew_device: the Jacobi sweeps left off-diagonal mass above tolerance");
   return IG_OK;
 }
 
@@ -227,6 +232,19 @@ int ig_wq_build(ig_ctx *ctx, const ig_desc *d, const void *Wq, const int32_t *id
   if ((uintptr_t)wq % 16) return ig_fail(ctx, IG_EINVAL, "ig_wq_build: wq must be 16-byte aligned");
   if ((rc = set_device(ctx))) return rc;
   return ig_launch_wq_build(ctx, d, ig_proj_geom(d), Wq, idx_dev, wq, (hipStream_t)stream);
+}
+
+int ig_skew_device(ig_ctx *ctx, int D, int H, int n_cal, const float *Qcal, float *A, float *sigma,
+                   void *stream) {
+  if (!ctx) return IG_EINVAL;
+  if (D < 1 || H < 1 || D % H || n_cal < 1) return ig_fail(ctx, IG_ESHAPE, "ig_skew_device: bad shape");
+  const int d = D / H;
+  if (d % 2 || d > 256) return ig_fail(ctx, IG_ESHAPE, "ig_skew_device: d = %d must be even and at most 256", d);
+  if (!Qcal || !A) return ig_fail(ctx, IG_EINVAL, "ig_skew_device: Qcal or A is NULL");
+  int rc = set_device(ctx);
+  if (rc) return rc;
+  if ((rc = ig_ensure(ctx, (void **)&ctx->skew_ws, &ctx->skew_ws_bytes, ig_skew_workspace(H, d)))) return rc;
+  return ig_launch_skew(ctx, D, H, n_cal, Qcal, ctx->skew_ws, A, sigma, (hipStream_t)stream);
 }
 
 int ig_partial_index_device(ig_ctx *ctx, int dtype, int H, int d, int n, const void *Qs,

@@ -40,6 +40,7 @@ template <> struct SlabElem<float> {
 constexpr int IG_WAVE = 64;
 constexpr int IG_KS_MAX = 16;     // split-K partial sums a consumer adds up at most
 constexpr int IG_STATUS_CAPACITY = 1;
+constexpr int IG_STATUS_NOCONV = 2;    // Jacobi sweeps of ig_skew_device left too much off the diagonal
 constexpr int IG_SLICE_MAX = 16;   // slices a selected-token list is cut into at most (gather, attention)
 
 // Slab geometry: tokens are grouped in tiles of 64 lanes x TPL tokens; inside a tile the r kept
@@ -77,6 +78,7 @@ struct ig_ctx {
   int32_t *pcount;  size_t pcount_bytes;  // long-sequence path: kept tokens per 4096-token part
   float *attn_part; size_t attn_part_bytes;  // attention: per-slice softmax states [B*H][16][d+2]
   int32_t *attn_cnt; size_t attn_cnt_bytes;  // attention: per-(b,h) arrival counters, zero between calls
+  double *skew_ws;  size_t skew_ws_bytes;   // ig_skew_device: Gram matrices and eigenvectors [2][H][d][d]
   int32_t *status;                        // device status word (sticky flags)
   bool profiling;
   std::vector<ProfRec> recs;
@@ -158,6 +160,9 @@ int ig_launch_equalize(ig_ctx *ctx, const ig_desc *d, const float *scores, const
 int ig_launch_partial_index(ig_ctx *ctx, int dtype, int H, int d, int n, const void *Qs, const void *Ks,
                             int r, float *part, int32_t *idx, hipStream_t s);
 size_t ig_partial_index_workspace(int H, int d);
+size_t ig_skew_workspace(int H, int d);
+int ig_launch_skew(ig_ctx *ctx, int D, int H, int n_cal, const float *Qcal, double *ws, float *A,
+                   float *sigma, hipStream_t s);
 int ig_launch_copy(ig_ctx *ctx, const void *src, void *dst, size_t bytes, hipStream_t s);
 int ig_launch_read(ig_ctx *ctx, const void *src, size_t bytes, hipStream_t s);
 
