@@ -172,6 +172,35 @@ def test_f16_model_dimension_not_multiple_of_32_uses_fma_projection(ctx):
     check_case(ctx, make_case(w, gain=2.0))
 
 
+def _random_shapes():
+    rng = np.random.default_rng(20240627)
+    cases = []
+    for i in range(14):
+        f16 = bool(rng.integers(0, 2))
+        rope = bool(rng.integers(0, 2))
+        d = int(rng.choice([8, 16, 32, 64, 128] if f16 else [4, 8, 16, 32, 64]))
+        if rope and d % 2:
+            d *= 2
+        H = int(rng.integers(1, 7))
+        B = int(rng.integers(1, 6))
+        N = int(rng.integers(1, 2600))
+        N_cap = N + int(rng.integers(0, 3)) * int(rng.integers(1, 300))
+        ratio = float(rng.choice([0.2, 0.3, 0.5, 0.75, 1.0]))
+        if int(ratio * d) < 1:
+            ratio = 1.0
+        cases.append(pytest.param(dict(B=B, H=H, d=d, N=N, dtype="f16" if f16 else "f32", rope=rope,
+                                       ratio=ratio, n_cal=64, heavy_count=min(5, N)),
+                                  N_cap, float(rng.choice([1.0, 3.0, 8.0])), bool(rng.integers(0, 2)),
+                                  id=f"r{i}-B{B}H{H}d{d}N{N}"))
+    return cases
+
+
+@pytest.mark.parametrize("shape,N_cap,gain,bias", _random_shapes())
+def test_seeded_random_shapes(ctx, shape, N_cap, gain, bias):
+    w = wl.shrink(wl.WORKLOADS[2], **shape)
+    check_case(ctx, make_case(w, gain=gain, N_cap=N_cap, bias=bias))
+
+
 def test_host_pinned_pool_gather(ctx):
     w = wl.shrink(wl.WORKLOADS[4], B=2, H=4, N=2048)
     check_case(ctx, make_case(w, gain=6.0), host_pool=True)
