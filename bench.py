@@ -27,7 +27,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per scan launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the counter
 # reads for a plain 256 MiB copy (profiles/cfg2_hbm_traffic_counters.txt); None = not collected.
-SCAN_TRAFFIC_BYTES = {2: 41.24e6}
+SCAN_TRAFFIC_BYTES = {2: 41.24e6, 3: 162.66e6, 4: 179.69e6, 5: 283.43e6}
 
 
 def log(*a):
@@ -258,6 +258,32 @@ def main():
                      "tokens_per_head_last_layer_mean": R.sel_cnt.float().mean().item(),
                      "max_frac": 0.2}
 
+    # ---- index-only partial weight (columns read out of the full weight at run time) ----
+    index_only = None
+    if not w.rope:
+        R._use(0)
+        R.speculate(L - 1)
+        torch.cuda.synchronize()
+        blob_idx, blob_cnt = R.sel_idx.clone(), R.sel_cnt.clone()
+        for _ in range(2):
+            R.step_index_only()
+        torch.cuda.synchronize()
+        differing = int((R.sel_cnt != blob_cnt).sum().item())
+        io_ms = timed(R.step_index_only, max(2, K // 2))
+        ki = profiled([R.step_index_only], 2)
+        D_ = w.D
+        eb = 2 if w.dtype == "f16" else 4
+        index_only = {"us_per_layer": io_ms * 1e3 / L,
+                      "launch": "eager, one stream" + (", rehearsal only" if R.host_pool else ""),
+                      "project_kernel_us": ki["project"]["avg_us"],
+                      "project_kernel_us_stored_blob": kernels["project"]["avg_us"],
+                      "weight_bytes_read_MB": D_ * D_ * eb / 1e6,
+                      "weight_bytes_read_MB_stored_blob": D_ * w.H * R.r * eb / 1e6,
+                      "project_GBps": D_ * D_ * eb / (ki["project"]["avg_us"] * 1e-6) / 1e9,
+                      "blob_bytes_saved_MB": R.wq.numel() / 1e6,
+                      "lists_with_other_count_than_stored_blob_last_layer": differing}
+        del blob_idx
+
     # ---- decode loop with a growing cache: append of the decoded token after every layer ----
     decode_loop = None
     if not args.no_decode_loop:
@@ -390,6 +416,7 @@ def main():
         "kernels_while_overlapped": kernels_overlapped,
         "literal_variant": literal,
         "head_equalized_variant": equalized,
+        "index_only_weight_variant": index_only,
         "decode_loop_growing_cache": decode_loop,
         "roofline": {"kernel": "partial-K scan + max + threshold + compaction", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -206,6 +206,23 @@ int ig_scan_select(ig_ctx *ctx, const ig_desc *desc, const float *q_p, const voi
                    int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, float *scores_opt,
                    void *stream);
 
+/* Index-only partial weight (Section 6.2 "Memory Consumption": only the column indices of the
+ * partial query weight are stored and the columns are taken from the full query weight, which the
+ * model keeps on the GPU anyway).  Same definitions as ig_project / ig_speculate with
+ * q_p[b,h,j] = bias[h*r+j] + sum_k x[b,k] Wq[k, h*d + idx_dev[h,j]], desc->rope == 0 only (a rotary
+ * model's rehearsal uses the full W_Q in ig_speculate already).  Wq: device [D, D] of
+ * desc->dtype, the skewed query weight, 16-byte aligned; idx_dev: device int32 [H, r], entries in
+ * [0, d) (others are clamped into that range).  No ig_wq_build blob is needed; the weight bytes
+ * read per call grow from D*H*r to D*D elements.  Needs d*sizeof(dtype) to be a multiple of 16 and
+ * at most 1024 bytes, else IG_ESHAPE.  Float32 sums in a fixed order (repeatable bit for bit),
+ * but another order than ig_project's. */
+int ig_project_indexed(ig_ctx *ctx, const ig_desc *desc, const void *x, const void *Wq,
+                       const int32_t *idx_dev, const float *bias, float *q_p, void *stream);
+int ig_speculate_indexed(ig_ctx *ctx, const ig_desc *desc, const void *x, const void *Wq,
+                         const int32_t *idx_dev, const float *bias, const void *slab,
+                         int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, float *scores_opt,
+                         void *stream);
+
 /* Head-equalised selection (Section 4.3 "Decoding Stage", closing sentences; Section 5.1 "Key
  * Metric"): every head of a sequence keeps the same number of tokens,
  *   n_b = max(1, min(floor(sum_h thr_cnt[b,h] / H), floor(max_frac * N))),

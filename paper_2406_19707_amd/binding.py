@@ -32,7 +32,8 @@ EXPORTS = [
     "ig_partial_index", "ig_skew_device", "ig_partial_index_device", "ig_wq_bytes", "ig_wq_build", "ig_slab_bytes",
     "ig_slab_build", "ig_append_token",
     "ig_pool_touch", "ig_pool_victim", "ig_pool_replace",
-    "ig_speculate", "ig_project", "ig_scan_select", "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention",
+    "ig_speculate", "ig_project", "ig_scan_select", "ig_project_indexed", "ig_speculate_indexed",
+    "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention",
     "ig_sparse_attention_indexed", "ig_gather_attention", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
     "ig_copy_bytes", "ig_read_bytes",
 ]
@@ -97,6 +98,8 @@ def lib():
             "ig_speculate": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
             "ig_project": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
             "ig_scan_select": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
+            "ig_project_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp]),
+            "ig_speculate_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
             "ig_equalize_heads": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_double, _vp, _i32, _vp, _vp]),
             "ig_gather_kv": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_int, _vp, _i32, _vp, _vp, _vp, _vp]),
             "ig_sparse_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
@@ -273,6 +276,17 @@ class Context:
         self._ck(lib().ig_scan_select(self._h, ctypes.byref(desc), _ptr(q_p), _ptr(slab),
                                       _ptr(sel_idx), sel_stride, _ptr(sel_cnt), _ptr(scores_opt),
                                       _stream(stream)))
+
+    def ig_project_indexed(self, desc, x, Wq, idx_dev, bias, q_p, stream=None):
+        self._ck(lib().ig_project_indexed(self._h, ctypes.byref(desc), _ptr(x), _ptr(Wq), _ptr(idx_dev),
+                                          _ptr(bias), _ptr(q_p), _stream(stream)))
+
+    def ig_speculate_indexed(self, desc, x, Wq, idx_dev, bias, slab, sel_idx, sel_stride, sel_cnt,
+                             scores_opt=None, stream=None):
+        self._ck(lib().ig_speculate_indexed(self._h, ctypes.byref(desc), _ptr(x), _ptr(Wq),
+                                            _ptr(idx_dev), _ptr(bias), _ptr(slab), _ptr(sel_idx),
+                                            sel_stride, _ptr(sel_cnt), _ptr(scores_opt),
+                                            _stream(stream)))
 
     def ig_gather_kv(self, desc, Kpool, Vpool, pool_space, sel_idx, sel_stride, sel_cnt, K_sel,
                      V_sel, stream=None):

@@ -112,8 +112,10 @@ int resolve_pool(ig_ctx *ctx, const void *p, int space, const void **out) {
 
 int reserve_for(ig_ctx *ctx, const ig_desc *d, bool scores) {
   ProjGeom g = ig_proj_geom(d);
+  int k_per = 0;
+  const int ks_cols = d->rope ? 0 : ig_proj_columns_ks(d, &k_per);   // the index-only variant's split
   int rc = ig_ensure(ctx, (void **)&ctx->part, &ctx->part_bytes,
-                     (size_t)g.KS * g.Bpad * g.Cpad * sizeof(float));
+                     (size_t)(g.KS > ks_cols ? g.KS : ks_cols) * g.Bpad * g.Cpad * sizeof(float));
   if (rc) return rc;
   rc = ig_ensure(ctx, (void **)&ctx->qp, &ctx->qp_bytes, (size_t)d->B * d->H * d->r * sizeof(float));
   if (rc) return rc;
@@ -369,6 +371,54 @@ int ig_project(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, con
   ProjGeom g;
   if ((rc = project_partials(ctx, d, x, wq, A_p, pos, &g, (hipStream_t)stream))) return rc;
   return ig_launch_finalize(ctx, d, g, ctx->part, bias, A_p, pos, q_p, (hipStream_t)stream);
+}
+
+// Index-only partial weight: split-K partial sums of x W[:, kept columns] into ctx->part, in the
+// geometry `g` of the stored-blob projection but with the split `*ks` of the column kernel.
+static int project_columns_partials(ig_ctx *ctx, const ig_desc *d, const void *x, const void *Wq,
+                                    const int32_t *idx_dev, ProjGeom *g, int *ks, hipStream_t s) {
+  if (!x || !Wq || !idx_dev) return ig_fail(ctx, IG_EINVAL, "x, Wq or idx_dev is NULL");
+  if (d->rope) return ig_fail(ctx, IG_EINVAL, "the index-only weight is for rope == 0 (rope == 1 uses the full W_Q already)");
+  if ((uintptr_t)Wq % 16 || (uintptr_t)x % 16) return ig_fail(ctx, IG_EINVAL, "x and Wq must be 16-byte aligned");
+  int rc = set_device(ctx);
+  if (rc) return rc;
+  *g = ig_proj_geom(d);
+  int k_per = 0;
+  *ks = ig_proj_columns_ks(d, &k_per);
+  if ((rc = ig_ensure(ctx, (void **)&ctx->part, &ctx->part_bytes,
+                      (size_t)(*ks > g->KS ? *ks : g->KS) * g->Bpad * g->Cpad * sizeof(float))))
+    return rc;
+  if ((rc = ig_ensure(ctx, (void **)&ctx->qp, &ctx->qp_bytes, (size_t)d->B * d->H * d->r * sizeof(float))))
+    return rc;
+  return ig_launch_project_columns(ctx, d, *g, x, Wq, idx_dev, ctx->part, s);
+}
+
+int ig_project_indexed(ig_ctx *ctx, const ig_desc *d, const void *x, const void *Wq,
+                       const int32_t *idx_dev, const float *bias, float *q_p, void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!q_p) return ig_fail(ctx, IG_EINVAL, "q_p is NULL");
+  ProjGeom g;
+  int ks = 0;
+  if ((rc = project_columns_partials(ctx, d, x, Wq, idx_dev, &g, &ks, (hipStream_t)stream))) return rc;
+  g.KS = ks;
+  return ig_launch_finalize(ctx, d, g, ctx->part, bias, nullptr, nullptr, q_p, (hipStream_t)stream);
+}
+
+int ig_speculate_indexed(ig_ctx *ctx, const ig_desc *d, const void *x, const void *Wq,
+                         const int32_t *idx_dev, const float *bias, const void *slab,
+                         int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, float *scores_opt,
+                         void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!slab) return ig_fail(ctx, IG_EINVAL, "slab is NULL");
+  if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
+  ProjGeom g;
+  int ks = 0;
+  hipStream_t s = (hipStream_t)stream;
+  if ((rc = project_columns_partials(ctx, d, x, Wq, idx_dev, &g, &ks, s))) return rc;
+  QSource q{ctx->part, ks, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias};
+  return ig_launch_scan_select(ctx, d, q, slab, sel_idx, sel_stride, sel_cnt, scores_opt, s);
 }
 
 int ig_scan_select(ig_ctx *ctx, const ig_desc *d, const float *q_p, const void *slab,

@@ -121,6 +121,10 @@ int ig_launch_slab_build(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const
                          void *slab, hipStream_t s);
 int ig_launch_project(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const void *x,
                       const void *wq, float *part, hipStream_t s);
+// index-only partial weight: columns idx of the full weight W, same partial-sum layout
+int ig_proj_columns_ks(const ig_desc *d, int *k_per);
+int ig_launch_project_columns(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const void *x,
+                              const void *W, const int32_t *idx, float *part, hipStream_t s);
 int ig_launch_finalize(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const float *part,
                        const float *bias, const float *A_p, const int32_t *pos, float *q_p,
                        hipStream_t s);

@@ -162,6 +162,190 @@ __global__ __launch_bounds__(64) void project_fma(const T *__restrict__ blob, co
   for (int i = 0; i < 16; ++i) part[((long)ks * Bpad + n0 + i) * Cpad + c] = acc[i];
 }
 
+// ---- index-only partial weight ------------------------------------------------------------------
+// Section 6.2 "Memory Consumption": instead of a second copy of the kept columns, only their
+// indices are stored and the columns are taken from the full (skewed) query weight, which the
+// model keeps on the GPU anyway.  Picking 2-byte columns out of a row-major matrix touches nearly
+// every 64-byte line of it, so the kernel reads the rows of a head whole, with 16-byte loads, and
+// multiplies all d columns (fp32 FMAs: B*D*D of them, below the time of the D*D read for B <= 16);
+// the kept columns are picked from the result.
+// Workgroup (h, ks, batch block): 4 waves; a wave-wide load covers 64/LPRp rows of the head's
+// d-column span (LPR = 16-byte pieces per row, LPRp = LPR rounded up to a power of two).  The
+// NBR batch rows of x for the K chunk are staged in LDS as float.  The sums over a wave's rows are
+// folded with a butterfly, the four waves are added in wave order, and the split-K partial sums go
+// to part[ks][row][h*r + j], the layout the scan and the finalisation read.
+template <typename T, int NBR>
+__global__ __launch_bounds__(256) void project_columns(const T *__restrict__ W, const T *__restrict__ x,
+                                                       const int32_t *__restrict__ idx,
+                                                       float *__restrict__ part, int B, int D, int d,
+                                                       int r, int LPR, int LPRp, int k_per, int Bpad,
+                                                       int Cpad) {
+  constexpr int TPL = Elem<T>::TPL;
+  constexpr int KC = 512;                  // K rows staged per chunk
+  constexpr int U = NBR <= 8 ? 8 : 4;      // loads in flight per lane
+  typedef typename Elem<T>::vec vec;
+  __shared__ float xs[NBR * KC];
+  __shared__ float red[NBR * 512];
+  const int h = blockIdx.x, ks = blockIdx.y, n0 = blockIdx.z * NBR;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int RPW = 64 / LPRp;
+  const int sub = lane / LPRp, li = lane % LPRp;
+  const bool active = li < LPR;
+  const int k0 = ks * k_per, k1 = min(D, k0 + k_per);
+  float acc[NBR][TPL];
+#pragma unroll
+  for (int b = 0; b < NBR; ++b)
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) acc[b][e] = 0.f;
+  const T *wcol = W + (long)h * d + (active ? li : 0) * TPL;
+  for (int kc = k0; kc < k1; kc += KC) {
+    const int kn = min(KC, k1 - kc);
+    __syncthreads();
+    for (int b = 0; b < NBR; ++b) {
+      const int row = n0 + b;
+      for (int kk = tid; kk < kn; kk += 256)
+        xs[b * KC + kk] = row < B ? (float)x[(long)row * D + kc + kk] : 0.f;
+    }
+    __syncthreads();
+    const int steps = (kn + 4 * RPW - 1) / (4 * RPW);
+    for (int s0 = 0; s0 < steps; s0 += U) {
+      vec v[U];
+      int kk[U];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const int k = ((s0 + u) * 4 + w) * RPW + sub;
+        const bool ok = active && k < kn;
+        kk[u] = min(k, kn - 1);
+        vec z = {};
+        v[u] = ok ? *reinterpret_cast<const vec *>(wcol + (long)(kc + kk[u]) * D) : z;
+      }
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        float wf[TPL];
+#pragma unroll
+        for (int e = 0; e < TPL; ++e) wf[e] = (float)v[u][e];
+#pragma unroll
+        for (int b = 0; b < NBR; ++b) {
+          const float xv = xs[b * KC + kk[u]];
+#pragma unroll
+          for (int e = 0; e < TPL; ++e) acc[b][e] = fmaf(xv, wf[e], acc[b][e]);
+        }
+      }
+    }
+  }
+  // rows of one wave
+  for (int o = LPRp; o < 64; o <<= 1) {
+#pragma unroll
+    for (int b = 0; b < NBR; ++b)
+#pragma unroll
+      for (int e = 0; e < TPL; ++e) acc[b][e] += __shfl_xor(acc[b][e], o, 64);
+  }
+  // the four waves, in wave order
+  for (int ww = 0; ww < 4; ++ww) {
+    if (w == ww && sub == 0 && active) {
+#pragma unroll
+      for (int b = 0; b < NBR; ++b)
+#pragma unroll
+        for (int e = 0; e < TPL; ++e) {
+          const int at = b * 512 + li * TPL + e;
+          red[at] = (ww == 0 ? 0.f : red[at]) + acc[b][e];
+        }
+    }
+    __syncthreads();
+  }
+  for (int i = tid; i < NBR * r; i += 256) {
+    const int b = i / r, j = i % r;
+    const int row = n0 + b;
+    const int col = min(max(idx[h * r + j], 0), d - 1);
+    if (row < Bpad) part[((long)ks * Bpad + row) * Cpad + h * r + j] = red[b * 512 + col];
+  }
+}
+
+// The same for half precision on the matrix cores (D a multiple of 128): workgroup (128-column
+// block, ks, batch blocks).  Lane (n = lane%16, kg = lane/16) of a wave loads, for 8 consecutive
+// rows k, the 16 bytes holding columns 8n .. 8n+7 of the block (16 lanes cover one 256-byte row
+// piece, a wave-wide step covers 32 rows), turns its 8x8 block of halves around in registers so
+// that each of its 8 columns has 8 consecutive k, and issues 8 MFMAs 16x16x32 per batch block:
+// MFMA j multiplies columns {8m + j} (A operand, m = lane%16) with the x fragment (B operand, 16
+// batch rows).  Result register v of lane l in MFMA j: column 8*(4*(l/16) + v) + j, batch row l%16.
+// The four waves take every fourth step; their sums are added in wave order through LDS.
+template <int NB>
+__global__ __launch_bounds__(256) void project_columns_mfma(const half_t *__restrict__ W,
+                                                            const half_t *__restrict__ x,
+                                                            const int32_t *__restrict__ idx,
+                                                            float *__restrict__ part, int B, int D,
+                                                            int H, int d, int r, int k_per, int Bpad,
+                                                            int Cpad) {
+  constexpr int RS = 129;                   // row stride of the LDS result tile (floats)
+  __shared__ float red[NB * 16 * RS];
+  const int cb = blockIdx.x, ks = blockIdx.y, nb0 = blockIdx.z * NB;
+  const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63;
+  const int n = lane & 15, kg = lane >> 4;
+  const int k0 = ks * k_per, k1 = min(D, k0 + k_per);      // both multiples of 32
+  floatx4 acc[NB][8];
+#pragma unroll
+  for (int i = 0; i < NB; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  const half8 zero = {0, 0, 0, 0, 0, 0, 0, 0};
+  const half_t *wp = W + (long)cb * 128 + n * 8;
+  // two steps per pass: 16 row loads of a lane are in flight before the first MFMA
+  for (int kb = k0 + w * 32; kb < k1; kb += 256) {
+    half8 rows[2][8], xf[2][NB];
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int kt = kb + t * 128 + kg * 8;
+      const bool ok = kt < k1;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) rows[t][e] = ok ? *reinterpret_cast<const half8 *>(wp + (long)(kt + e) * D) : zero;
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const int row = (nb0 + i) * 16 + n;
+        xf[t][i] = (ok && row < B) ? *reinterpret_cast<const half8 *>(x + (long)row * D + kt) : zero;
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      if (kb + t * 128 < k1) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          half8 a;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) a[e] = rows[t][e][j];
+#pragma unroll
+          for (int i = 0; i < NB; ++i)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, xf[t][i], acc[i][j], 0, 0, 0);
+        }
+      }
+    }
+  }
+  for (int ww = 0; ww < 4; ++ww) {
+    if (w == ww) {
+#pragma unroll
+      for (int i = 0; i < NB; ++i)
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) {
+            const int at = (i * 16 + n) * RS + 8 * (4 * kg + v) + j;
+            red[at] = (ww == 0 ? 0.f : red[at]) + acc[i][j][v];
+          }
+    }
+    __syncthreads();
+  }
+  // kept columns that fall into this block, for the heads that overlap it
+  const int c_lo = cb * 128;
+  const int h_lo = c_lo / d, h_hi = min(H - 1, (c_lo + 127) / d);
+  for (int i = h_lo * r + tid; i < (h_hi + 1) * r; i += 256) {
+    const int col = (i / r) * d + min(max(idx[i], 0), d - 1) - c_lo;
+    if (col < 0 || col >= 128) continue;
+    for (int b = 0; b < NB * 16; ++b) {
+      const int row = nb0 * 16 + b;
+      if (row < Bpad) part[((long)ks * Bpad + row) * Cpad + i] = red[b * RS + col];
+    }
+  }
+}
+
 // ---- finalisation -------------------------------------------------------------------------------
 // folded: q_p[b,h,j] = bias[h*r+j] + sum_s part[s][b][h*r+j]
 // rope:   q[c] = bias[h*d+c] + sum_s part[s][b][h*d+c]; rotate pairs (c, c+d/2) by
@@ -285,6 +469,78 @@ int ig_launch_project(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const vo
     }
   }
   return IG_OK;
+}
+
+// Split of the index-only projection: enough workgroups for two per compute unit.  Half precision
+// with D a multiple of 128 runs on the matrix cores (column blocks of 128, K slices that are
+// multiples of 32, up to 4 batch blocks of 16 per workgroup); everything else on the FMA kernel
+// (one head per workgroup, 8 or 16 batch rows).
+static bool proj_columns_mfma(const ig_desc *d) { return d->dtype == IG_F16 && (d->H * d->d) % 128 == 0; }
+
+int ig_proj_columns_ks(const ig_desc *d, int *k_per) {
+  const int D = d->H * d->d;
+  int wgs, unit;
+  if (proj_columns_mfma(d)) {
+    const int nbtot = (d->B + 15) / 16;
+    wgs = (D / 128) * ((nbtot + 3) / 4);
+    unit = 32;
+  } else {
+    const int nbr = d->B <= 8 ? 8 : 16;
+    wgs = d->H * ((d->B + nbr - 1) / nbr);
+    unit = 1;
+  }
+  const int units = D / unit;
+  int ks = (512 + wgs - 1) / wgs;
+  if (ks > IG_KS_MAX) ks = IG_KS_MAX;
+  if (ks > units) ks = units;
+  if (ks < 1) ks = 1;
+  *k_per = (units + ks - 1) / ks * unit;
+  return (D + *k_per - 1) / *k_per;
+}
+
+int ig_launch_project_columns(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const void *x,
+                              const void *W, const int32_t *idx, float *part, hipStream_t s) {
+  const int D = d->H * d->d;
+  int k_per = 0;
+  const int KS = ig_proj_columns_ks(d, &k_per);
+  if (proj_columns_mfma(d)) {
+    const int nbtot = (d->B + 15) / 16;
+    const int nb = nbtot == 1 ? 1 : (nbtot == 2 ? 2 : 4);
+    dim3 grid(D / 128, KS, (nbtot + nb - 1) / nb), block(256);
+#define PM_CASE(NB)                                                                                \
+  {                                                                                                \
+    auto k = project_columns_mfma<NB>;                                                             \
+    IG_LAUNCH(ctx, IG_K_PROJECT, k, grid, block, s, (const half_t *)W, (const half_t *)x, idx,     \
+              part, (int)d->B, D, (int)d->H, (int)d->d, (int)d->r, k_per, g.Bpad, g.Cpad);         \
+    return IG_OK;                                                                                  \
+  }
+    if (nb == 1) PM_CASE(1)
+    if (nb == 2) PM_CASE(2)
+    PM_CASE(4)
+#undef PM_CASE
+  }
+  const int row_bytes = d->d * ig_elem_bytes(d->dtype);
+  if (row_bytes % 16 || row_bytes / 16 > 64 || d->d > 512)
+    return ig_fail(ctx, IG_ESHAPE, "index-only projection: d = %d needs 16-byte rows of at most 1 KiB", d->d);
+  const int LPR = row_bytes / 16;
+  int LPRp = 1;
+  while (LPRp < LPR) LPRp <<= 1;
+  const int nbr = d->B <= 8 ? 8 : 16;
+  dim3 grid(d->H, KS, (d->B + nbr - 1) / nbr), block(256);
+#define PC_CASE(T, NBR)                                                                            \
+  {                                                                                                \
+    auto k = project_columns<T, NBR>;                                                              \
+    IG_LAUNCH(ctx, IG_K_PROJECT, k, grid, block, s, (const T *)W, (const T *)x, idx, part,         \
+              (int)d->B, D, (int)d->d, (int)d->r, LPR, LPRp, k_per, g.Bpad, g.Cpad);               \
+    return IG_OK;                                                                                  \
+  }
+  if (d->dtype == IG_F16) {
+    if (nbr == 8) PC_CASE(half_t, 8)
+    PC_CASE(half_t, 16)
+  }
+  if (nbr == 8) PC_CASE(float, 8)
+  PC_CASE(float, 16)
+#undef PC_CASE
 }
 
 int ig_launch_finalize(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const float *part,

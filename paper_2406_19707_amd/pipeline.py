@@ -174,6 +174,12 @@ class Rehearsal:
         self.ctx.ig_speculate(self.desc, self.x[l], self.wq, None, self.A_p, self.pos, self.slab[l],
                               self.sel_idx, self.stride, self.sel_cnt, scores)
 
+    def speculate_index_only(self, l, scores=None):
+        """Rehearsal with the index-only partial weight (Section 6.2 "Memory Consumption"): the kept
+        columns are read out of the model's full skewed query weight; no weight blob is used."""
+        self.ctx.ig_speculate_indexed(self.desc, self.x[l], self._Wd, self.idx, None, self.slab[l],
+                                      self.sel_idx, self.stride, self.sel_cnt, scores)
+
     def gather(self, l, stream=None):
         p = l % self.n_pool
         self.ctx.ig_gather_kv(self.desc, self.K[p], self.V[p], self.space, self.sel_idx, self.stride,
@@ -260,6 +266,14 @@ class Rehearsal:
         for l in range(self.L):
             self.speculate(l)
             self.gather_attend(l)
+
+    def step_index_only(self):
+        """step_one_pass() with the index-only partial weight (host pool: the rehearsals only, the
+        prefetch over PCIe does not depend on where the weight columns come from)."""
+        for l in range(self.L):
+            self.speculate_index_only(l)
+            if not self.host_pool:
+                self.gather_attend(l)
 
     def step_equalized(self, max_frac=0.2):
         """The paper's batched variant (Section 4.3, closing sentences): every head of a sequence
