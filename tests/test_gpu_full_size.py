@@ -1,6 +1,8 @@
 """GPU parity at the benchmark's full size (configs[1]: B8 H32 d128 N2048 r38, f16 KV, HBM pool), in
 the launch configuration bench.py times: the oracle checks sampled (sequence, head) pairs one by
-one, and properties that hold at any size are checked on every pair."""
+one, and properties that hold at any size are checked on every pair.  The two other shapes whose
+kernels take different paths at full size (configs[2]: rotary, 512 pairs of 8 tiles; configs[3]:
+1120 pairs, pinned host pool) are compared with the oracle on every pair."""
 import numpy as np
 import pytest
 import torch
@@ -107,3 +109,22 @@ def test_cfg2_full_size_sampled_pairs_and_properties():
         assert np.all(np.abs(g_out[i] - ref) <= 2e-2 + 1e-2 * np.abs(ref)), (i, np.abs(g_out[i] - ref).max())
     print(f"  oracle agrees on pairs {sample}", flush=True)
     ctx.close()
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("cfg,host_pool,B", [(3, False, None), (4, True, None), (5, True, 1)])
+def test_full_size_every_pair_against_the_oracle(cfg, host_pool, B):
+    import paper_2406_19707_amd as ig
+    from ig_case import make_case
+    from test_gpu_parity import check_case
+    w = wl.WORKLOADS[cfg]
+    if B is not None:            # configs[4] at its full length (32768 tokens, 64 tiles per pair), one sequence
+        w = wl.shrink(w, B=B)
+    print(f"full-size case {w.name}: building inputs", flush=True)
+    c = make_case(w, gain=w.gain)
+    print("  inputs built", flush=True)
+    ctx = ig.Context(0)
+    try:
+        check_case(ctx, c, host_pool=host_pool, expect_fraction=(0.0001, 0.3))
+    finally:
+        ctx.close()
