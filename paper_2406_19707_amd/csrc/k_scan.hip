@@ -322,6 +322,91 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
   }
 }
 
+// Sequences of up to LDS_SCORES tokens that do not fit 16 waves at once: still one workgroup of
+// 16 waves per (b,h); wave w scans tiles w, w + 16, ... and parks the scores in LDS (4 B/token,
+// 128 KiB), so that the threshold pass needs neither a score buffer in memory nor further
+// kernels.  The waves run through their tiles without meeting; they meet once for the maximum.
+constexpr int LDS_SCORES = 32768;
+
+template <typename T, int CH, bool ROPE>
+__global__ __launch_bounds__(1024) void scan_select_lds(ScanArgs a) {
+  constexpr int TPL = SlabElem<T>::TPL;
+  constexpr int TILE = IG_WAVE * TPL;
+  constexpr int NW = 16;
+  __shared__ float lds_s[LDS_SCORES];
+  __shared__ float lds_max[NW];
+  __shared__ int lds_cnt[NW];
+  const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const T *head = static_cast<const T *>(a.slab) + (long)bh * a.nTiles * a.r * TILE;
+  typename SlabElem<T>::vec v[CH];
+  // first channel block of the wave's first tile in flight while the partial query is worked out
+  if (w < a.nTiles) load_block<T, CH>(head + (long)w * a.r * TILE, a.r, 0, lane, v);
+  float qv[4];
+  if constexpr (ROPE) {
+    __shared__ float q_lds[512], qr_lds[512], psum[NW * 64], qp_lds[256];
+    rope_query<NW * 64>(a, b, h, q_lds, qr_lds, psum, qp_lds);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) qv[k] = (lane + 64 * k < a.r) ? qp_lds[lane + 64 * k] * a.scale : 0.f;
+  } else {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      qv[k] = 0.f;
+      if (64 * k < a.r) {
+        QueryLoads ql;
+        query_issue(a, b, h, lane, k, ql);
+        qv[k] = query_finish(a, ql);
+      }
+    }
+  }
+  float m = -INFINITY;
+  for (int ti = w; ti < a.nTiles; ti += NW) {
+    const T *tile = head + (long)ti * a.r * TILE;
+    if (ti != w) load_block<T, CH>(tile, a.r, 0, lane, v);
+    float acc[TPL];
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
+    scan_tile_given_q<T, CH>(a, tile, lane, v, qv, acc);
+    const int t0 = ti * TILE;
+    if (a.scores_out) store_scores<TPL>(a.scores_out, (long)bh * a.N, t0 + lane * TPL, a.N, acc);
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) {
+      if (t0 + lane * TPL + e >= a.N) acc[e] = -INFINITY;
+      m = fmaxf(m, acc[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < TPL; e += 4) {
+      const floatx4 o = {acc[e], acc[e + 1], acc[e + 2], acc[e + 3]};
+      *reinterpret_cast<floatx4 *>(lds_s + t0 + lane * TPL + e) = o;
+    }
+  }
+  m = wave_max(m);
+  if (lane == 0) lds_max[w] = m;
+  __syncthreads();
+  float mm = lds_max[0];
+#pragma unroll
+  for (int k = 1; k < NW; ++k) mm = fmaxf(mm, lds_max[k]);
+  const float thr = mm - a.alpha;
+  int base = 0;
+  for (int t0w = 0; t0w < a.nTiles; t0w += NW) {       // 16 tiles per pass, in token order
+    const int ti = t0w + w;
+    float acc[TPL];
+#pragma unroll
+    for (int e = 0; e < TPL; e += 4) {
+      floatx4 o = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+      if (ti < a.nTiles) o = *reinterpret_cast<const floatx4 *>(lds_s + ti * TILE + lane * TPL + e);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) acc[e + k] = o[k];
+    }
+    base += compact_block<TPL, NW>(acc, ti * TILE, a.N, thr, base, a.sel_idx + (long)bh * a.sel_stride,
+                                   a.sel_stride, lds_cnt, w, lane);
+  }
+  if (threadIdx.x == 0) {
+    a.sel_cnt[bh] = min(base, a.sel_stride);
+    if (base > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
+  }
+}
+
 // Long sequences / few heads: one wave per tile, 4 tiles per workgroup; scores and per-tile maxima
 // go to a buffer, and select_count / select_write do the threshold pass.
 template <typename T, int CH>
@@ -471,6 +556,28 @@ int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
 }
 
 template <typename T>
+int launch_lds(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) {
+  dim3 grid(BH), block(1024);
+#define CASE(CHV)                                                              \
+  case CHV: {                                                                  \
+    if (a.A_p) {                                                               \
+      auto k = scan_select_lds<T, CHV, true>;                                  \
+      IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                         \
+    } else {                                                                   \
+      auto k = scan_select_lds<T, CHV, false>;                                 \
+      IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                         \
+    }                                                                          \
+    return IG_OK;                                                              \
+  }
+  switch (ch) {
+    CASE(4) CASE(8)
+    default: break;
+  }
+#undef CASE
+  return ig_fail(ctx, IG_ESHAPE, "scan: unsupported channel block %d", ch);
+}
+
+template <typename T>
 int launch_tiles(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) {
   dim3 grid((a.nTiles + 3) / 4, BH), block(256);
 #define CASE(CHV)                                                              \
@@ -498,7 +605,7 @@ template <typename T>
 int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
   const int BH = d->B * d->H;
   const int nTiles = a.nTiles;
-  // Fused when a (b,h) fits one workgroup and there are enough (b,h) pairs to fill the chip;
+  // One workgroup per (b,h) when it fits and there are enough (b,h) pairs to fill the chip;
   // otherwise one wave per tile so that long sequences spread over all compute units.
   const bool fused = ig_scan_is_fused(d);
   if (fused) {
@@ -507,7 +614,10 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
     // load and select phases then overlap (measured: 60 % -> 71 % of HBM peak at 1120 workgroups).
     if (nTiles <= 4) return launch_fused<T, 4>(ctx, a, BH, pick_ch(d->r, BH > 512 ? 20 : 40), s);
     if (nTiles <= 8) return launch_fused<T, 8>(ctx, a, BH, pick_ch(d->r, 16), s);
-    return launch_fused<T, 16>(ctx, a, BH, pick_ch(d->r, 12), s);
+    if (nTiles <= 16) return launch_fused<T, 16>(ctx, a, BH, pick_ch(d->r, 12), s);
+    // 16 waves already keep a compute unit's memory queue full: 8 loads per wave in flight are
+    // enough (4, 8 and 12 measured the same), and 12 would spill registers
+    return launch_lds<T>(ctx, a, BH, pick_ch(d->r, 8), s);
   }
   size_t need_s = (size_t)BH * d->N * sizeof(float), need_m = (size_t)BH * nTiles * sizeof(float);
   float *user_scores = a.scores_out;
@@ -519,18 +629,22 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
   int rc = ig_ensure(ctx, (void **)&ctx->tmax, &ctx->tmax_bytes, need_m);
   if (rc) return rc;
   a.tmax = ctx->tmax;
-  return launch_tiles<T>(ctx, a, BH, pick_ch(d->r, 40), s);
+  // at most 28 channel loads in flight: 32 and more leave one wave per SIMD (measured with r = 38:
+  // 30.8 us against 35.5 us at 80 pairs of 32768 tokens)
+  return launch_tiles<T>(ctx, a, BH, pick_ch(d->r, 28), s);
 }
 
 }  // namespace
 
-// Fused (one workgroup per (b,h), scores never leave registers) when a (b,h) fits 16 waves and
-// there are enough pairs to fill the chip; otherwise one wave per tile.
+// One workgroup per (b,h) and a single kernel when a pair fits 16 waves (scores stay in registers)
+// or 32768 tokens (scores parked in LDS) and there are enough pairs to fill the chip; otherwise
+// one wave per tile and the threshold pass in two further kernels.
 bool ig_scan_is_fused(const ig_desc *d) {
   const int tile = ig_tile_tokens(d->dtype);
   const int nTiles = (d->N_cap + tile - 1) / tile;
   const int BH = d->B * d->H;
-  return nTiles <= 16 && (BH >= 128 || nTiles <= 4);
+  if (nTiles > 16) return nTiles * tile <= 32768 && BH >= 64;     // scores parked in LDS, one workgroup per pair
+  return BH >= 128 || nTiles <= 4;
 }
 
 int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const void *slab,

@@ -112,13 +112,13 @@ def test_cfg2_full_size_sampled_pairs_and_properties():
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("cfg,host_pool,B", [(3, False, None), (4, True, None), (5, True, 1)])
+@pytest.mark.parametrize("cfg,host_pool,B", [(3, False, None), (4, True, None), (5, True, 2)])
 def test_full_size_every_pair_against_the_oracle(cfg, host_pool, B):
     import paper_2406_19707_amd as ig
     from ig_case import make_case
     from test_gpu_parity import check_case
     w = wl.WORKLOADS[cfg]
-    if B is not None:            # configs[4] at its full length (32768 tokens, 64 tiles per pair), one sequence
+    if B is not None:            # configs[4] at its full length (32768 tokens, 64 tiles per pair), two sequences (80 pairs)
         w = wl.shrink(w, B=B)
     print(f"full-size case {w.name}: building inputs", flush=True)
     c = make_case(w, gain=w.gain)

@@ -151,6 +151,17 @@ def test_cfg3_shape_rope_with_bias_ragged(ctx):
     check_case(ctx, make_case(w, gain=16.0, bias=True, N_cap=1500))
 
 
+@pytest.mark.parametrize("cfg,B,H,d,N,N_cap,gain,bias", [
+    (2, 8, 8, 32, 9000, 9000, 6.0, False),       # 18 tiles of 512: two passes of the 16 waves, ragged tail
+    (3, 4, 16, 32, 12345, 13000, 20.0, True),    # rotary, spare capacity, bias
+    (5, 2, 32, 16, 32768, 32768, 40.0, False),   # the longest sequence this path takes (64 tiles), rotary
+    (1, 8, 8, 32, 5000, 5100, 8.0, False),       # float32: tiles of 256 tokens, 20 of them
+])
+def test_long_sequences_many_pairs_scores_parked_in_lds(ctx, cfg, B, H, d, N, N_cap, gain, bias):
+    w = wl.shrink(wl.WORKLOADS[cfg], B=B, H=H, d=d, N=N, n_cal=max(64, 2 * d), heavy_count=24)
+    check_case(ctx, make_case(w, gain=gain, bias=bias, N_cap=N_cap), host_pool=False)
+
+
 def test_cfg5_shape_long_context_tiled_path(ctx):
     w = wl.shrink(wl.WORKLOADS[5], B=1, H=2, N=20000)
     check_case(ctx, make_case(w, gain=6.0, N_cap=20480))
