@@ -123,12 +123,12 @@ int reserve_for(ig_ctx *ctx, const ig_desc *d, bool scores) {
     const int tile = ig_tile_tokens(d->dtype);
     const int nTiles = (d->N_cap + tile - 1) / tile;
     rc = ig_ensure(ctx, (void **)&ctx->scores, &ctx->scores_bytes,
-                   (size_t)d->B * d->H * d->N * sizeof(float));
+                   (size_t)d->B * d->H * d->N_cap * sizeof(float));   // by capacity: N may grow
     if (rc) return rc;
     rc = ig_ensure(ctx, (void **)&ctx->tmax, &ctx->tmax_bytes, (size_t)d->B * d->H * nTiles * sizeof(float));
     if (rc) return rc;
     rc = ig_ensure(ctx, (void **)&ctx->pcount, &ctx->pcount_bytes,
-                   (size_t)d->B * d->H * ((d->N + 4095) / 4096) * sizeof(int32_t));
+                   (size_t)d->B * d->H * ((d->N_cap + 4095) / 4096) * sizeof(int32_t));
     if (rc) return rc;
     rc = ig_ensure(ctx, (void **)&ctx->attn_part, &ctx->attn_part_bytes,
                    (size_t)d->B * d->H * IG_SLICE_MAX * (d->d + 2) * sizeof(float));

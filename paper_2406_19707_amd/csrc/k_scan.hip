@@ -28,7 +28,9 @@ struct ScanArgs {
   long ks_stride;
   long b_stride;
   int ks;
-  int H, r, N, nTiles;
+  int H, r, N;
+  int nTiles;   // tiles allocated per (b,h): the slab's stride (from N_cap)
+  int nValid;   // tiles that hold valid tokens (from N): the only ones read
   int sel_stride;
   float scale, alpha;
   // rotary models, fused path: the workgroup derives its partial query itself from the full
@@ -267,7 +269,7 @@ __device__ __forceinline__ int compact_block(const float (&sc)[TPL], int t0, int
   return all;
 }
 
-// One workgroup per (b,h); wave w scans tile w (nTiles <= NW) and keeps its scores in registers.
+// One workgroup per (b,h); wave w scans tile w (nValid <= NW) and keeps its scores in registers.
 template <typename T, int CH, int NW, bool ROPE>
 __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
   constexpr int TPL = SlabElem<T>::TPL;
@@ -277,7 +279,7 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
   const int bh = blockIdx.x, b = bh / a.H, h = bh % a.H;
   // the wave index is made a scalar so that tile addresses stay in scalar registers
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const bool active = w < a.nTiles;
+  const bool active = w < a.nValid;
   const T *tile = static_cast<const T *>(a.slab) + ((long)bh * a.nTiles + (active ? w : 0)) * a.r * TILE;
   float acc[TPL];
 #pragma unroll
@@ -341,7 +343,7 @@ __global__ __launch_bounds__(1024) void scan_select_lds(ScanArgs a) {
   const T *head = static_cast<const T *>(a.slab) + (long)bh * a.nTiles * a.r * TILE;
   typename SlabElem<T>::vec v[CH];
   // first channel block of the wave's first tile in flight while the partial query is worked out
-  if (w < a.nTiles) load_block<T, CH>(head + (long)w * a.r * TILE, a.r, 0, lane, v);
+  if (w < a.nValid) load_block<T, CH>(head + (long)w * a.r * TILE, a.r, 0, lane, v);
   float qv[4];
   if constexpr (ROPE) {
     __shared__ float q_lds[512], qr_lds[512], psum[NW * 64], qp_lds[256];
@@ -360,7 +362,7 @@ __global__ __launch_bounds__(1024) void scan_select_lds(ScanArgs a) {
     }
   }
   float m = -INFINITY;
-  for (int ti = w; ti < a.nTiles; ti += NW) {
+  for (int ti = w; ti < a.nValid; ti += NW) {
     const T *tile = head + (long)ti * a.r * TILE;
     if (ti != w) load_block<T, CH>(tile, a.r, 0, lane, v);
     float acc[TPL];
@@ -388,13 +390,13 @@ __global__ __launch_bounds__(1024) void scan_select_lds(ScanArgs a) {
   for (int k = 1; k < NW; ++k) mm = fmaxf(mm, lds_max[k]);
   const float thr = mm - a.alpha;
   int base = 0;
-  for (int t0w = 0; t0w < a.nTiles; t0w += NW) {       // 16 tiles per pass, in token order
+  for (int t0w = 0; t0w < a.nValid; t0w += NW) {       // 16 tiles per pass, in token order
     const int ti = t0w + w;
     float acc[TPL];
 #pragma unroll
     for (int e = 0; e < TPL; e += 4) {
       floatx4 o = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-      if (ti < a.nTiles) o = *reinterpret_cast<const floatx4 *>(lds_s + ti * TILE + lane * TPL + e);
+      if (ti < a.nValid) o = *reinterpret_cast<const floatx4 *>(lds_s + ti * TILE + lane * TPL + e);
 #pragma unroll
       for (int k = 0; k < 4; ++k) acc[e + k] = o[k];
     }
@@ -416,7 +418,7 @@ __global__ __launch_bounds__(256) void scan_tiles(ScanArgs a) {
   const int bh = blockIdx.y, b = bh / a.H, h = bh % a.H;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int tileno = blockIdx.x * 4 + w;
-  if (tileno >= a.nTiles) return;
+  if (tileno >= a.nValid) return;
   const T *tile = static_cast<const T *>(a.slab) + ((long)bh * a.nTiles + tileno) * a.r * TILE;
   float acc[TPL];
   scan_tile<T, CH>(a, tile, b, h, lane, acc);
@@ -439,7 +441,7 @@ constexpr int SELECT_PART = 4096;   // 1024 threads x 4 tokens
 
 __device__ __forceinline__ float select_threshold(const ScanArgs &a, int bh, float *lds_max, int w, int lane) {
   float m = -INFINITY;
-  for (int k = threadIdx.x; k < a.nTiles; k += 1024) m = fmaxf(m, a.tmax[(long)bh * a.nTiles + k]);
+  for (int k = threadIdx.x; k < a.nValid; k += 1024) m = fmaxf(m, a.tmax[(long)bh * a.nTiles + k]);
   m = wave_max(m);
   if (lane == 0) lds_max[w] = m;
   __syncthreads();
@@ -579,7 +581,7 @@ int launch_lds(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) {
 
 template <typename T>
 int launch_tiles(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) {
-  dim3 grid((a.nTiles + 3) / 4, BH), block(256);
+  dim3 grid((a.nValid + 3) / 4, BH), block(256);
 #define CASE(CHV)                                                              \
   case CHV: {                                                                  \
     auto k = scan_tiles<T, CHV>;                                               \
@@ -604,7 +606,7 @@ int launch_tiles(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
 template <typename T>
 int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
   const int BH = d->B * d->H;
-  const int nTiles = a.nTiles;
+  const int nTiles = a.nValid;     // the work, not the capacity, picks the kernel
   // One workgroup per (b,h) when it fits and there are enough (b,h) pairs to fill the chip;
   // otherwise one wave per tile so that long sequences spread over all compute units.
   const bool fused = ig_scan_is_fused(d);
@@ -619,7 +621,7 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
     // enough (4, 8 and 12 measured the same), and 12 would spill registers
     return launch_lds<T>(ctx, a, BH, pick_ch(d->r, 8), s);
   }
-  size_t need_s = (size_t)BH * d->N * sizeof(float), need_m = (size_t)BH * nTiles * sizeof(float);
+  size_t need_s = (size_t)BH * d->N * sizeof(float), need_m = (size_t)BH * a.nTiles * sizeof(float);
   float *user_scores = a.scores_out;
   if (!user_scores) {
     int rc = ig_ensure(ctx, (void **)&ctx->scores, &ctx->scores_bytes, need_s);
@@ -641,7 +643,7 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
 // one wave per tile and the threshold pass in two further kernels.
 bool ig_scan_is_fused(const ig_desc *d) {
   const int tile = ig_tile_tokens(d->dtype);
-  const int nTiles = (d->N_cap + tile - 1) / tile;
+  const int nTiles = (d->N + tile - 1) / tile;        // tiles with valid tokens
   const int BH = d->B * d->H;
   if (nTiles > 16) return nTiles * tile <= 32768 && BH >= 64;     // scores parked in LDS, one workgroup per pair
   return BH >= 128 || nTiles <= 4;
@@ -667,6 +669,7 @@ int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const
   a.N = d->N;
   const int tile = ig_tile_tokens(d->dtype);
   a.nTiles = (d->N_cap + tile - 1) / tile;
+  a.nValid = (d->N + tile - 1) / tile;
   a.sel_stride = sel_stride;
   a.scale = d->scale;
   a.alpha = d->alpha;

@@ -101,7 +101,7 @@ def test_all_columns_and_infinite_alpha_is_dense_attention(ctx):
     assert np.abs(got["out"] - dense).max() <= 1e-4
 
 
-@pytest.mark.parametrize("N,N_cap", [(2048, 2048), (1999, 2048), (700, 1024), (1, 8)])
+@pytest.mark.parametrize("N,N_cap", [(2048, 2048), (1999, 2048), (700, 1024), (1, 8), (700, 6000)])
 def test_cfg2_shape_f16_fused_four_waves(ctx, N, N_cap):
     w = wl.shrink(wl.WORKLOADS[2], B=3, H=4, N=N, heavy_count=min(20, N))
     check_case(ctx, make_case(w, gain=6.0, N_cap=N_cap))
@@ -156,6 +156,7 @@ def test_cfg3_shape_rope_with_bias_ragged(ctx):
     (3, 4, 16, 32, 12345, 13000, 20.0, True),    # rotary, spare capacity, bias
     (5, 2, 32, 16, 32768, 32768, 40.0, False),   # the longest sequence this path takes (64 tiles), rotary
     (1, 8, 8, 32, 5000, 5100, 8.0, False),       # float32: tiles of 256 tokens, 20 of them
+    (2, 8, 8, 32, 9000, 40000, 6.0, False),      # capacity far beyond the valid tokens: only 18 of 79 tiles are read
 ])
 def test_long_sequences_many_pairs_scores_parked_in_lds(ctx, cfg, B, H, d, N, N_cap, gain, bias):
     w = wl.shrink(wl.WORKLOADS[cfg], B=B, H=H, d=d, N=N, n_cal=max(64, 2 * d), heavy_count=24)
@@ -165,6 +166,11 @@ def test_long_sequences_many_pairs_scores_parked_in_lds(ctx, cfg, B, H, d, N, N_
 def test_cfg5_shape_long_context_tiled_path(ctx):
     w = wl.shrink(wl.WORKLOADS[5], B=1, H=2, N=20000)
     check_case(ctx, make_case(w, gain=6.0, N_cap=20480))
+
+
+def test_long_sequence_tiled_path_with_spare_capacity(ctx):
+    w = wl.shrink(wl.WORKLOADS[5], B=1, H=2, N=9000)              # 18 valid tiles of 98 allocated
+    check_case(ctx, make_case(w, gain=6.0, N_cap=50000))
 
 
 def test_f32_long_sequence_tiled_path(ctx):
