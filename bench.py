@@ -96,15 +96,12 @@ def main():
         assert ctx.ig_check_status() == ig.IG_OK
         eager_ms = timed(R.step_overlapped, K)
         main_ms = timed(R.step_without_gather, K)
+        R.collect_lists()
         with torch.cuda.stream(R.side):
             R.step_gather_only()
             torch.cuda.synchronize()
             gather_ms = timed(R.step_gather_only, K)
-        rows = 0
-        for l in range(L):
-            R._use(l)
-            R.speculate(l)
-            rows += int(R.sel_cnt.sum().item())
+        rows = sum(int(c.sum().item()) for _, c in R.layer_lists)
         gbytes = rows * 2 * w.d * 2 / L                      # K and V rows per layer
         g_gbs = gbytes / (gather_ms * 1e-3 / L) / 1e9
         shorter = min(main_ms, gather_ms)
@@ -115,6 +112,14 @@ def main():
                 "pipelined_over_gather_alone": eager_ms / gather_ms,
                 # share of the main stream's work that ran under the prefetch
                 "main_stream_hidden_fraction": (main_ms + gather_ms - eager_ms) / shorter}
+        # the same step on one stream (rehearsal, prefetch, attention of a layer in sequence): the
+        # PCIe link idles while the main-stream kernels run, but nothing runs against the prefetch
+        R._use(0)
+        for _ in range(W):
+            R.step()
+        torch.cuda.synchronize()
+        one_stream_ms = timed(R.step, K)
+        pcie["one_stream_us_per_layer"] = one_stream_ms * 1e3 / L
         log("pcie", pcie)
         args.no_graph = True
     else:
@@ -130,6 +135,9 @@ def main():
     variants = {}
     launch = "eager, two streams" if R.host_pool else "eager"
     ms_per_step = eager_ms
+    if R.host_pool and one_stream_ms < ms_per_step:
+        ms_per_step, launch = one_stream_ms, "eager, one stream"
+
     if not args.no_graph:
         def graphed(fn):
             g = torch.cuda.CUDAGraph()

@@ -218,13 +218,25 @@ class Rehearsal:
             self.speculate(l)
             self.attend(l)
 
+    def collect_lists(self):
+        """Every layer's own index lists, kept for step_gather_only (the pipelined step reuses two
+        list buffers, which would leave only the last two layers' lists behind)."""
+        self.layer_lists = []
+        for l in range(self.L):
+            self._use(l)
+            self.speculate(l)
+            self.layer_lists.append((self.sel_idx.clone(), self.sel_cnt.clone()))
+        torch.cuda.synchronize()
+
     def step_gather_only(self):
-        """Side-stream work of a host-pool step alone (lists as left by the last rehearsals)."""
+        """Side-stream work of a host-pool step alone: the prefetch of every layer with that
+        layer's own lists (collect_lists() first)."""
         for l in range(self.L):
             self._use(l)
             p = l % self.n_pool
-            self.side_ctx.ig_gather_kv(self.desc, self.K[p], self.V[p], self.space, self.sel_idx,
-                                       self.stride, self.sel_cnt, self.K_sel, self.V_sel, self.side)
+            sel_idx, sel_cnt = self.layer_lists[l]
+            self.side_ctx.ig_gather_kv(self.desc, self.K[p], self.V[p], self.space, sel_idx,
+                                       self.stride, sel_cnt, self.K_sel, self.V_sel, self.side)
 
     def step_fused_attention(self):
         """Variant for an HBM-resident pool: the index lists are applied inside the attention."""
