@@ -168,6 +168,17 @@ def test_cfg5_shape_long_context_tiled_path(ctx):
     check_case(ctx, make_case(w, gain=6.0, N_cap=20480))
 
 
+@pytest.mark.parametrize("B,H,N", [
+    (8, 8, 8192),     # 16 tiles: the last shape of the 16-wave register form
+    (8, 8, 8193),     # 17 tiles, 64 pairs: scores parked in LDS
+    (7, 9, 8193),     # 63 pairs: too few for one workgroup per pair, one wave per tile
+    (4, 16, 32769),   # 65 tiles: beyond the LDS form
+])
+def test_scan_form_boundaries(ctx, B, H, N):
+    w = wl.shrink(wl.WORKLOADS[2], B=B, H=H, d=16, N=N, ratio=0.5, n_cal=64, heavy_count=12)
+    check_case(ctx, make_case(w, gain=8.0))
+
+
 def test_long_sequence_tiled_path_with_spare_capacity(ctx):
     w = wl.shrink(wl.WORKLOADS[5], B=1, H=2, N=9000)              # 18 valid tiles of 98 allocated
     check_case(ctx, make_case(w, gain=6.0, N_cap=50000))
