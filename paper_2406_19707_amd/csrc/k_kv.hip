@@ -357,11 +357,30 @@ __global__ __launch_bounds__(256) void sparse_attention(
   const long base = (long)bh * kv_rows * LPR;
   const int32_t *list = sel_idx + (long)bh * stride;
   const int rows_per_batch = 4 * RPW * ATT_BATCH;
+  // Fused prefetch (K_out): the rows read from the pool are also the rows ig_gather_kv would copy.
+  // With several slices the row stores of a slice's last batch are held back until the slice has
+  // published its softmax state, so that the wait for that publication does not also wait for
+  // 64 KiB of row stores to be acknowledged; they then travel while the counter round trip and
+  // the final merge are under way.
+  const bool fuse_store = INDEXED && K_out != nullptr;
+  const bool defer = fuse_store && slices > 1;
+  u128 kr[ATT_BATCH], vr[ATT_BATCH];
+  int r_keep = -1;                       // first row of the batch whose stores are held back
+  auto store_rows = [&](int r0) {
+#pragma unroll
+    for (int i = 0; i < ATT_BATCH; ++i) {
+      const int j = r0 + (i * 4 + w) * RPW + sub;
+      if (j < row1 && j < n) {
+        const long o = ((long)bh * stride + j) * LPR + li;
+        store_stream(K_out + o, kr[i]);
+        store_stream(V_out + o, vr[i]);
+      }
+    }
+  };
   for (int r0 = row0; r0 < row1; r0 += rows_per_batch) {
     // Branch-free loads, so that the whole batch is in flight at once: a step past the slice's end
     // re-reads the slice's last row and its logit is masked below; the new-token row is a pointer
     // select, not a branch.
-    u128 kr[ATT_BATCH], vr[ATT_BATCH];
     bool valid[ATT_BATCH];
     long rowoff[ATT_BATCH];
 #pragma unroll
@@ -382,17 +401,9 @@ __global__ __launch_bounds__(256) void sparse_attention(
       kr[i] = *kp;
       vr[i] = *vp;
     }
-    if (INDEXED && K_out) {
-      // fused prefetch: the rows just read from the pool are also the rows ig_gather_kv would copy
-#pragma unroll
-      for (int i = 0; i < ATT_BATCH; ++i) {
-        const int j = r0 + (i * 4 + w) * RPW + sub;
-        if (j < row1 && j < n) {
-          const long o = ((long)bh * stride + j) * LPR + li;
-          store_stream(K_out + o, kr[i]);
-          store_stream(V_out + o, vr[i]);
-        }
-      }
+    if (fuse_store) {
+      if (defer && r0 + rows_per_batch >= row1) r_keep = r0;
+      else store_rows(r0);
     }
     float l[ATT_BATCH];
     float bm = m;
@@ -473,41 +484,57 @@ __global__ __launch_bounds__(256) void sparse_attention(
   // wait until this wave's coherent stores have been acknowledged, then meet the other waves
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   __syncthreads();
+  // held-back row stores: waves 1..3 issue theirs now; wave 0, which waits for the counter and does
+  // the final merge, issues its own only when it has nothing left to wait for
+  if (w != 0 && r_keep >= 0) store_rows(r_keep);
   if (threadIdx.x == 0) {
     const int prev = __hip_atomic_fetch_add(&counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     s_last = (prev == slices - 1);
     if (s_last) __hip_atomic_store(&counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
   __syncthreads();
-  if (!s_last) return;
-  // every thread issues all of its loads (independent, predicated on the slice count) before using any
-  const float *all = part + (long)bh * max_slices * (d + 2);
-  for (int c = threadIdx.x; c < d; c += 256) {
-    float mk[SLICE_MAX], zk[SLICE_MAX], ak[SLICE_MAX];
+  if (w != 0) return;
+  if (s_last) {
+    // wave 0 of the last arrival: lane c owns output channels c, c + 64, ...; all loads of a pass
+    // (independent, predicated on the slice count) are issued before any is used
+    const float *all = part + (long)bh * max_slices * (d + 2);
+    float mk[SLICE_MAX], zk[SLICE_MAX];
 #pragma unroll
     for (int k = 0; k < SLICE_MAX; ++k) {
       mk[k] = -INFINITY;
       zk[k] = 0.f;
-      ak[k] = 0.f;
       if (k < slices) {
-        const float *pk = all + (long)k * (d + 2);
-        mk[k] = coherent_load(pk);
-        zk[k] = coherent_load(pk + 1);
-        ak[k] = coherent_load(pk + 2 + c);
+        mk[k] = coherent_load(all + (long)k * (d + 2));
+        zk[k] = coherent_load(all + (long)k * (d + 2) + 1);
       }
     }
-    float MM = -INFINITY;
+    constexpr int CPP = 2;               // channels per lane and pass
+    for (int c0 = lane; c0 < d; c0 += 64 * CPP) {
+      float ak[CPP][SLICE_MAX];
 #pragma unroll
-    for (int k = 0; k < SLICE_MAX; ++k) MM = fmaxf(MM, mk[k]);
-    float zz = 0.f, a = 0.f;
+      for (int q = 0; q < CPP; ++q)
 #pragma unroll
-    for (int k = 0; k < SLICE_MAX; ++k) {
-      const float f = exp_or_zero(mk[k], MM);
-      zz += zk[k] * f;
-      a += ak[k] * f;
+        for (int k = 0; k < SLICE_MAX; ++k) {
+          const int c = c0 + 64 * q;
+          ak[q][k] = (k < slices && c < d) ? coherent_load(all + (long)k * (d + 2) + 2 + c) : 0.f;
+        }
+      float MM = -INFINITY;
+#pragma unroll
+      for (int k = 0; k < SLICE_MAX; ++k) MM = fmaxf(MM, mk[k]);
+      float zz = 0.f;
+#pragma unroll
+      for (int k = 0; k < SLICE_MAX; ++k) zz += zk[k] * exp_or_zero(mk[k], MM);
+#pragma unroll
+      for (int q = 0; q < CPP; ++q) {
+        const int c = c0 + 64 * q;
+        float a = 0.f;
+#pragma unroll
+        for (int k = 0; k < SLICE_MAX; ++k) a += ak[q][k] * exp_or_zero(mk[k], MM);
+        if (c < d) out[(long)bh * d + c] = (T)(zz > 0.f ? a / zz : 0.f);
+      }
     }
-    out[(long)bh * d + c] = (T)(zz > 0.f ? a / zz : 0.f);
   }
+  if (r_keep >= 0) store_rows(r_keep);
 }
 
 __global__ __launch_bounds__(256) void copy_bytes(const u128 *__restrict__ src, u128 *__restrict__ dst,
