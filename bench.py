@@ -157,7 +157,9 @@ def main():
         for name, fn in (("speculate, gather, attention", R.step),
                          ("speculate, gather+attention in one pass", R.step_one_pass),
                          ("rehearsal of the next layer on a side stream, gather+attention in one pass",
-                          R.step_two_stream)):
+                          R.step_two_stream),
+                         ("projection, then the next layer's scan and this layer's gather+attention in one launch",
+                          R.step_joint)):
             try:
                 g = graphed(fn)
                 for _ in range(W):
@@ -222,6 +224,11 @@ def main():
         kernels = profiled([R.step], K)
         one = profiled([R.step_one_pass], K)
         kernels["gather+attention in one pass"] = one["attention"]
+        names[ig.IG_K_LAYER] = "joint"
+        joint = profiled([R.step_joint], K)
+        if "joint" in joint:
+            kernels["next layer's scan + this layer's gather+attention in one launch"] = joint["joint"]
+        del names[ig.IG_K_LAYER]
     # streaming-read rate of this GPU on buffers of the slab's size (the slabs themselves, rotated)
     names[ig.IG_K_READ] = "read"
     slab_bytes = R.slab[0].numel()
@@ -391,7 +398,8 @@ def main():
     esz = 4 if w.dtype == "f32" else 2
     row_bytes = float(np.mean(fr)) * w.N * w.B * w.H * w.d * esz * 2          # K and V rows of a layer
     kbytes = {"project": ig.ig_wq_bytes(R.desc), "scan": scan_bytes, "gather": 2 * row_bytes,
-              "attention": row_bytes, "gather+attention in one pass": 2 * row_bytes}
+              "attention": row_bytes, "gather+attention in one pass": 2 * row_bytes,
+              "next layer's scan + this layer's gather+attention in one launch": scan_bytes + 2 * row_bytes}
     if R.host_pool:
         kbytes["gather"] = row_bytes                                          # over PCIe; the HBM write is extra
     for name, kb in kbytes.items():

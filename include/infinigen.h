@@ -61,7 +61,8 @@ enum {
   IG_K_BUILD = 6,    /* ig_wq_build / ig_slab_build */
   IG_K_COPY = 7,     /* ig_copy_bytes */
   IG_K_READ = 8,     /* ig_read_bytes */
-  IG_K_COUNT = 9
+  IG_K_LAYER = 9,    /* ig_layer_step: next layer's scan + this layer's prefetch and attention, one launch */
+  IG_K_COUNT = 10
 };
 
 typedef struct ig_ctx ig_ctx;
@@ -274,6 +275,22 @@ int ig_gather_attention(ig_ctx *ctx, const ig_desc *desc, const void *q, const v
                         const void *v_new, void *out, void *stream);
 
 /* ---- measurement --------------------------------------------------------------------------- */
+
+/* One slice of a decode step over a device-resident pool (Section 4.1, Fig. 3(d): the next layer
+ * is speculated while the current one computes): the rehearsal of the NEXT layer -- x, wq, bias,
+ * A_p, pos, slab as in ig_speculate, lists to sel_idx_next / sel_cnt_next -- and the one-pass
+ * prefetch + attention of THIS layer -- q, Kpool, Vpool, sel_idx, sel_cnt, K_sel, V_sel, k_new,
+ * v_new, out as in ig_gather_attention.  Both list pairs use sel_stride; the two must not
+ * alias.  Same results, bit for bit, as ig_speculate (without score dump) followed by
+ * ig_gather_attention.  The projection goes out first; the next layer's scan and this layer's
+ * attention are independent and, for sequences of at most 4 tiles (2048 half-precision tokens)
+ * with enough (sequence, head) pairs, leave as ONE launch; other shapes get the two launches one
+ * after the other. */
+int ig_layer_step(ig_ctx *ctx, const ig_desc *desc, const void *x, const void *wq, const float *bias,
+                  const float *A_p, const int32_t *pos, const void *slab, int32_t *sel_idx_next,
+                  int32_t *sel_cnt_next, const void *q, const void *Kpool, const void *Vpool,
+                  const int32_t *sel_idx, const int32_t *sel_cnt, int32_t sel_stride, void *K_sel,
+                  void *V_sel, const void *k_new, const void *v_new, void *out, void *stream);
 
 /* Between ig_profile_begin and ig_profile_end every kernel the context launches carries a pair of
  * HIP events that take the kernel's own start and stop timestamps.  ig_profile_end synchronises

@@ -16,7 +16,7 @@ __all__ = [
     "IG_OK", "IG_EINVAL", "IG_ESHAPE", "IG_EDTYPE", "IG_ECAPACITY", "IG_EHIP", "IG_ENOCONV",
     "IG_ENOMEM", "IG_F32", "IG_F16", "IG_MEM_DEVICE", "IG_MEM_HOST_PINNED", "IG_K_PROJECT",
     "IG_K_FINALIZE", "IG_K_SCAN", "IG_K_SELECT", "IG_K_GATHER", "IG_K_ATTENTION", "IG_K_BUILD",
-    "IG_K_COPY", "IG_K_READ", "IgDesc", "IgError", "Context", "lib", "lib_path", "ig_skew_offline",
+    "IG_K_COPY", "IG_K_READ", "IG_K_LAYER", "IgDesc", "IgError", "Context", "lib", "lib_path", "ig_skew_offline",
     "ig_partial_index", "ig_wq_bytes", "ig_slab_bytes", "EXPORTS",
 ]
 
@@ -24,7 +24,7 @@ IG_OK, IG_EINVAL, IG_ESHAPE, IG_EDTYPE, IG_ECAPACITY, IG_EHIP, IG_ENOCONV, IG_EN
 IG_F32, IG_F16 = 0, 1
 IG_MEM_DEVICE, IG_MEM_HOST_PINNED = 0, 1
 (IG_K_PROJECT, IG_K_FINALIZE, IG_K_SCAN, IG_K_SELECT, IG_K_GATHER, IG_K_ATTENTION, IG_K_BUILD,
- IG_K_COPY, IG_K_READ) = range(9)
+ IG_K_COPY, IG_K_READ, IG_K_LAYER) = range(10)
 
 # every symbol include/infinigen.h declares
 EXPORTS = [
@@ -34,7 +34,7 @@ EXPORTS = [
     "ig_pool_touch", "ig_pool_victim", "ig_pool_replace",
     "ig_speculate", "ig_project", "ig_scan_select", "ig_project_indexed", "ig_speculate_indexed",
     "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention",
-    "ig_sparse_attention_indexed", "ig_gather_attention", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
+    "ig_sparse_attention_indexed", "ig_gather_attention", "ig_layer_step", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
     "ig_copy_bytes", "ig_read_bytes",
 ]
 
@@ -100,6 +100,7 @@ def lib():
             "ig_scan_select": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
             "ig_project_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp]),
             "ig_speculate_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
+            "ig_layer_step": (ctypes.c_int, [_vp, _dp] + [_vp] * 13 + [_i32] + [_vp] * 6),
             "ig_equalize_heads": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_double, _vp, _i32, _vp, _vp]),
             "ig_gather_kv": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_int, _vp, _i32, _vp, _vp, _vp, _vp]),
             "ig_sparse_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
@@ -287,6 +288,14 @@ class Context:
                                             _ptr(idx_dev), _ptr(bias), _ptr(slab), _ptr(sel_idx),
                                             sel_stride, _ptr(sel_cnt), _ptr(scores_opt),
                                             _stream(stream)))
+
+    def ig_layer_step(self, desc, x, wq, bias, A_p, pos, slab, sel_idx_next, sel_cnt_next, q, Kpool,
+                      Vpool, sel_idx, sel_cnt, sel_stride, K_sel, V_sel, k_new, v_new, out, stream=None):
+        self._ck(lib().ig_layer_step(self._h, ctypes.byref(desc), _ptr(x), _ptr(wq), _ptr(bias),
+                                     _ptr(A_p), _ptr(pos), _ptr(slab), _ptr(sel_idx_next),
+                                     _ptr(sel_cnt_next), _ptr(q), _ptr(Kpool), _ptr(Vpool),
+                                     _ptr(sel_idx), _ptr(sel_cnt), sel_stride, _ptr(K_sel), _ptr(V_sel),
+                                     _ptr(k_new), _ptr(v_new), _ptr(out), _stream(stream)))
 
     def ig_gather_kv(self, desc, Kpool, Vpool, pool_space, sel_idx, sel_stride, sel_cnt, K_sel,
                      V_sel, stream=None):

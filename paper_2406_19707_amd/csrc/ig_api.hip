@@ -534,6 +534,44 @@ int ig_gather_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
                              v_new, out, K_sel, V_sel, (hipStream_t)stream);
 }
 
+int ig_layer_step(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, const float *bias,
+                  const float *A_p, const int32_t *pos, const void *slab, int32_t *sel_idx_next,
+                  int32_t *sel_cnt_next, const void *q, const void *Kpool, const void *Vpool,
+                  const int32_t *sel_idx, const int32_t *sel_cnt, int32_t sel_stride, void *K_sel,
+                  void *V_sel, const void *k_new, const void *v_new, void *out, void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!slab || !q || !Kpool || !Vpool || !K_sel || !V_sel || !out)
+    return ig_fail(ctx, IG_EINVAL, "ig_layer_step: NULL argument");
+  if ((k_new == nullptr) != (v_new == nullptr)) return ig_fail(ctx, IG_EINVAL, "k_new and v_new go together");
+  if ((rc = check_sel(ctx, sel_idx_next, sel_stride, sel_cnt_next))) return rc;
+  if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
+  if (sel_idx_next == sel_idx || sel_cnt_next == sel_cnt)
+    return ig_fail(ctx, IG_EINVAL, "ig_layer_step: the next layer's lists must not alias this layer's");
+  ProjGeom g;
+  hipStream_t s = (hipStream_t)stream;
+  if ((rc = project_partials(ctx, d, x, wq, A_p, pos, &g, s))) return rc;
+  if (!ig_layer_step_is_joint(d)) {
+    // other shapes: the two launches one after the other
+    if (d->rope && !ig_scan_is_fused(d)) {
+      if ((rc = ig_launch_finalize(ctx, d, g, ctx->part, bias, A_p, pos, ctx->qp, s))) return rc;
+      QSource qs{ctx->qp, 1, 0, (long)d->H * d->r, nullptr};
+      rc = ig_launch_scan_select(ctx, d, qs, slab, sel_idx_next, sel_stride, sel_cnt_next, nullptr, s);
+    } else {
+      QSource qs{ctx->part, g.KS, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias, d->rope ? A_p : nullptr,
+                 d->rope ? pos : nullptr};
+      rc = ig_launch_scan_select(ctx, d, qs, slab, sel_idx_next, sel_stride, sel_cnt_next, nullptr, s);
+    }
+    if (rc) return rc;
+    return ig_launch_attention(ctx, d, q, Kpool, Vpool, sel_idx, sel_stride, sel_cnt, d->N_cap, k_new,
+                               v_new, out, K_sel, V_sel, s);
+  }
+  QSource qs{ctx->part, g.KS, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias, d->rope ? A_p : nullptr,
+             d->rope ? pos : nullptr};
+  return ig_launch_scan_attend(ctx, d, qs, slab, sel_idx_next, sel_cnt_next, q, Kpool, Vpool, sel_idx,
+                               sel_cnt, sel_stride, k_new, v_new, out, K_sel, V_sel, s);
+}
+
 int ig_profile_begin(ig_ctx *ctx) {
   if (!ctx) return IG_EINVAL;
   int rc = set_device(ctx);

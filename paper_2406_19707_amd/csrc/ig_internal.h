@@ -167,6 +167,13 @@ size_t ig_partial_index_workspace(int H, int d);
 size_t ig_skew_workspace(int H, int d);
 int ig_launch_skew(ig_ctx *ctx, int D, int H, int n_cal, const float *Qcal, double *ws, float *A,
                    float *sigma, hipStream_t s);
+// scan of the next layer + one-pass prefetch/attention of this layer in one launch
+bool ig_layer_step_is_joint(const ig_desc *d);
+int ig_launch_scan_attend(ig_ctx *ctx, const ig_desc *d, const QSource &qs, const void *slab,
+                          int32_t *sel_idx_next, int32_t *sel_cnt_next, const void *q,
+                          const void *Kpool, const void *Vpool, const int32_t *sel_idx,
+                          const int32_t *sel_cnt, int32_t sel_stride, const void *k_new,
+                          const void *v_new, void *out, void *K_sel, void *V_sel, hipStream_t s);
 int ig_launch_copy(ig_ctx *ctx, const void *src, void *dst, size_t bytes, hipStream_t s);
 int ig_launch_read(ig_ctx *ctx, const void *src, size_t bytes, hipStream_t s);
 

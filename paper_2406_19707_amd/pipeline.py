@@ -279,6 +279,28 @@ class Rehearsal:
             self.speculate(l)
             self.gather_attend(l)
 
+    def step_joint(self):
+        """HBM-pool decode step on one stream with ig_layer_step: after the first layer's rehearsal,
+        every call issues the next layer's projection and then ONE launch that holds the next
+        layer's scan / threshold / lists and this layer's prefetch + attention (Fig. 3(d): the next
+        layer is speculated while the current one computes).  The index lists and fetched rows are
+        double-buffered."""
+        self._use(0)
+        self.speculate(0)
+        for l in range(self.L):
+            cur, nxt = self.sets[l % self.n_sets], self.sets[(l + 1) % self.n_sets]
+            p = l % self.n_pool
+            if l + 1 < self.L:
+                self.ctx.ig_layer_step(self.desc, self.x[l + 1], self.wq, None, self.A_p, self.pos,
+                                       self.slab[l + 1], nxt["sel_idx"], nxt["sel_cnt"], self.q[l],
+                                       self.K[p], self.V[p], cur["sel_idx"], cur["sel_cnt"], self.stride,
+                                       cur["K_sel"], cur["V_sel"], None, None, self.out)
+            else:
+                self.ctx.ig_gather_attention(self.desc, self.q[l], self.K[p], self.V[p], cur["sel_idx"],
+                                             self.stride, cur["sel_cnt"], cur["K_sel"], cur["V_sel"],
+                                             None, None, self.out)
+        self._use(self.L - 1)
+
     def step_index_only(self):
         """step_one_pass() with the index-only partial weight (host pool: the rehearsals only, the
         prefetch over PCIe does not depend on where the weight columns come from)."""
