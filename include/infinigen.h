@@ -89,6 +89,10 @@ int ig_destroy(ig_ctx *ctx);
 const char *ig_last_error(const ig_ctx *ctx);
 /* Size the context's workspaces for `desc` now (allocates; synchronous). */
 int ig_reserve(ig_ctx *ctx, const ig_desc *desc);
+/* Device memory the context's workspaces hold at the moment, in bytes (host-side bookkeeping, no
+ * device call).  Unchanged by the per-layer calls once ig_reserve has sized them for the largest
+ * shape (N_cap, B) they will see. */
+size_t ig_workspace_bytes(const ig_ctx *ctx);
 /* Synchronise the device and report sticky device-side conditions: IG_ECAPACITY if any list was
  * clamped to sel_stride since the last check, IG_ENOCONV if ig_skew_device did not converge, else
  * IG_OK.  Clears the conditions. */

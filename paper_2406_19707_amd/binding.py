@@ -28,7 +28,8 @@ IG_MEM_DEVICE, IG_MEM_HOST_PINNED = 0, 1
 
 # every symbol include/infinigen.h declares
 EXPORTS = [
-    "ig_create", "ig_destroy", "ig_last_error", "ig_reserve", "ig_check_status", "ig_skew_offline",
+    "ig_create", "ig_destroy", "ig_last_error", "ig_reserve", "ig_workspace_bytes", "ig_check_status",
+    "ig_skew_offline",
     "ig_partial_index", "ig_skew_device", "ig_partial_index_device", "ig_wq_bytes", "ig_wq_build", "ig_slab_bytes",
     "ig_slab_build", "ig_append_token",
     "ig_pool_touch", "ig_pool_victim", "ig_pool_replace",
@@ -80,6 +81,7 @@ def lib():
             "ig_destroy": (ctypes.c_int, [_vp]),
             "ig_last_error": (ctypes.c_char_p, [_vp]),
             "ig_reserve": (ctypes.c_int, [_vp, _dp]),
+            "ig_workspace_bytes": (ctypes.c_size_t, [_vp]),
             "ig_check_status": (ctypes.c_int, [_vp]),
             "ig_skew_offline": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int] + [_vp] * 11),
             "ig_partial_index": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp,
@@ -223,6 +225,9 @@ class Context:
 
     def ig_reserve(self, desc):
         self._ck(lib().ig_reserve(self._h, ctypes.byref(desc)))
+
+    def ig_workspace_bytes(self) -> int:
+        return int(lib().ig_workspace_bytes(self._h))
 
     def ig_check_status(self) -> int:
         return lib().ig_check_status(self._h)

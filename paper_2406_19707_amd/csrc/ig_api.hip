@@ -204,6 +204,12 @@ int ig_reserve(ig_ctx *ctx, const ig_desc *desc) {
   return reserve_for(ctx, desc, true);
 }
 
+size_t ig_workspace_bytes(const ig_ctx *ctx) {
+  if (!ctx) return 0;
+  return ctx->part_bytes + ctx->qp_bytes + ctx->scores_bytes + ctx->tmax_bytes + ctx->pcount_bytes +
+         ctx->attn_part_bytes + ctx->attn_cnt_bytes + ctx->skew_ws_bytes;
+}
+
 int ig_check_status(ig_ctx *ctx) {
   if (!ctx) return IG_EINVAL;
   int rc = set_device(ctx);
