@@ -223,7 +223,29 @@ def _random_shapes():
     return cases
 
 
-@pytest.mark.parametrize("shape,N_cap,gain,bias", _random_shapes())
+def _random_long_shapes():
+    # many pairs and long sequences: random draws around the switches between the scan's forms
+    # (16-wave registers / LDS-parked scores / one wave per tile; 64 pairs; 32768 tokens)
+    rng = np.random.default_rng(19707)
+    cases = []
+    for i in range(8):
+        f16 = bool(rng.integers(0, 2))
+        rope = bool(rng.integers(0, 2))
+        d = int(rng.choice([8, 16, 32]))
+        B = int(rng.integers(2, 12))
+        H = int(rng.integers(4, 17))
+        tile = 512 if f16 else 256
+        N = int(rng.integers(12 * tile, 40 * tile if f16 else 70 * tile))
+        N_cap = N + int(rng.integers(0, 2)) * int(rng.integers(1, 3000))
+        ratio = float(rng.choice([0.3, 0.5, 1.0]))
+        cases.append(pytest.param(dict(B=B, H=H, d=d, N=N, dtype="f16" if f16 else "f32", rope=rope,
+                                       ratio=ratio, n_cal=64, heavy_count=16),
+                                  N_cap, float(rng.choice([4.0, 8.0, 16.0])), bool(rng.integers(0, 2)),
+                                  id=f"l{i}-B{B}H{H}d{d}N{N}-{'f16' if f16 else 'f32'}"))
+    return cases
+
+
+@pytest.mark.parametrize("shape,N_cap,gain,bias", _random_shapes() + _random_long_shapes())
 def test_seeded_random_shapes(ctx, shape, N_cap, gain, bias):
     w = wl.shrink(wl.WORKLOADS[2], **shape)
     check_case(ctx, make_case(w, gain=gain, N_cap=N_cap, bias=bias))
