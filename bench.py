@@ -27,7 +27,7 @@ sys.path.insert(0, os.path.join(ROOT, "tests"))
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per scan launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the counter
 # reads for a plain 256 MiB copy (profiles/cfgN_hbm_traffic_counters.txt); None = not collected.
-SCAN_TRAFFIC_BYTES = {2: 41.19e6, 3: 162.66e6, 4: 179.69e6, 5: 263.52e6}
+SCAN_TRAFFIC_BYTES = {2: 41.19e6, 3: 162.66e6, 4: 179.69e6, 5: 264.01e6}
 
 
 def log(*a):
