@@ -118,6 +118,18 @@ int ig_skew_offline(ig_ctx *ctx, int D, int H, int n_cal, const float *Wq, const
 int ig_partial_index(ig_ctx *ctx, int H, int d, int n, const float *Qs, const float *Ks,
                      double ratio, int32_t *idx, int32_t *r_out);
 
+/* Skewed image of a set of rows (Section 4.2, Eq. 2: Q~ = Q A per head): Y[i, h*d:(h+1)*d] =
+ * X[i, h*d:(h+1)*d] * A_h.  X, Y host float32 [n, H*d] (Y may be X), A host float32 [H,d,d].
+ * Used for the inputs of ig_partial_index (the prompt's skewed queries / keys). */
+int ig_apply_skew(ig_ctx *ctx, int H, int d, int n, const float *X, const float *A, float *Y);
+
+/* Rotary embedding of host rows q [n, H, d] in place, row i at position pos[i] (host int32 [n]),
+ * with the pairing and angle the rehearsal of a rotary model applies itself (pairs (c, c + d/2),
+ * angle pos * theta^(-2c/d), double arithmetic): what a caller needs to prepare calibration queries
+ * for ig_skew_offline or a real query on the host for a model with desc->rope == 1
+ * (Section 4.2 decomposes the query matrix the model really produces). */
+int ig_rope_rows(ig_ctx *ctx, int n, int H, int d, const int32_t *pos, double theta, float *q);
+
 /* Offline skewing on the GPU: the same A [H,d,d] and sigma [H,d] (may be NULL) as ig_skew_offline,
  * from device arrays (Qcal float32 [n_cal, D]); d even, at most 256.  All arithmetic in double;
  * a fixed number of parallel Jacobi sweeps; if they leave off-diagonal mass above tolerance the

@@ -17,7 +17,7 @@ __all__ = [
     "IG_ENOMEM", "IG_F32", "IG_F16", "IG_MEM_DEVICE", "IG_MEM_HOST_PINNED", "IG_K_PROJECT",
     "IG_K_FINALIZE", "IG_K_SCAN", "IG_K_SELECT", "IG_K_GATHER", "IG_K_ATTENTION", "IG_K_BUILD",
     "IG_K_COPY", "IG_K_READ", "IG_K_LAYER", "IgDesc", "IgError", "Context", "lib", "lib_path", "ig_skew_offline",
-    "ig_partial_index", "ig_wq_bytes", "ig_slab_bytes", "EXPORTS",
+    "ig_partial_index", "ig_apply_skew", "ig_rope_rows", "ig_wq_bytes", "ig_slab_bytes", "EXPORTS",
 ]
 
 IG_OK, IG_EINVAL, IG_ESHAPE, IG_EDTYPE, IG_ECAPACITY, IG_EHIP, IG_ENOCONV, IG_ENOMEM = range(8)
@@ -29,7 +29,7 @@ IG_MEM_DEVICE, IG_MEM_HOST_PINNED = 0, 1
 # every symbol include/infinigen.h declares
 EXPORTS = [
     "ig_create", "ig_destroy", "ig_last_error", "ig_reserve", "ig_workspace_bytes", "ig_check_status",
-    "ig_skew_offline",
+    "ig_skew_offline", "ig_apply_skew", "ig_rope_rows",
     "ig_partial_index", "ig_skew_device", "ig_partial_index_device", "ig_wq_bytes", "ig_wq_build", "ig_slab_bytes",
     "ig_slab_build", "ig_append_token",
     "ig_pool_touch", "ig_pool_victim", "ig_pool_replace",
@@ -84,6 +84,8 @@ def lib():
             "ig_workspace_bytes": (ctypes.c_size_t, [_vp]),
             "ig_check_status": (ctypes.c_int, [_vp]),
             "ig_skew_offline": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int] + [_vp] * 11),
+            "ig_apply_skew": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp, _vp]),
+            "ig_rope_rows": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, ctypes.c_double, _vp]),
             "ig_partial_index": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp,
                                                 ctypes.c_double, _vp, ctypes.POINTER(_i32)]),
             "ig_skew_device": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, _vp, _vp, _vp, _vp]),
@@ -172,6 +174,29 @@ def ig_skew_offline(Wq, Wk, Qcal, H, bq=None, bk=None, ctx=None):
     if rc not in (IG_OK, IG_ENOCONV):
         raise IgError(rc, ctx.last_error() if ctx else "ig_skew_offline")
     return dict(A=A, sigma=sigma, rc=rc, **out)
+
+
+def ig_apply_skew(X, A, ctx=None):
+    """Host call. X [n, H*d], A [H, d, d] -> Y [n, H*d] with every head block multiplied by A_h."""
+    X, A = _host_f32(X), _host_f32(A)
+    H, d = A.shape[0], A.shape[1]
+    n = X.shape[0]
+    Y = np.empty_like(X)
+    rc = lib().ig_apply_skew(ctx._h if ctx else None, H, d, n, _ptr(X), _ptr(A), _ptr(Y))
+    if rc != IG_OK:
+        raise IgError(rc, ctx.last_error() if ctx else "ig_apply_skew")
+    return Y
+
+
+def ig_rope_rows(q, pos, theta=10000.0, ctx=None):
+    """Host call. q [n, H, d] float32, pos int32 [n] -> rotated copy."""
+    q = np.array(q, dtype=np.float32, order="C", copy=True)
+    pos = np.ascontiguousarray(pos, dtype=np.int32)
+    n, H, d = q.shape
+    rc = lib().ig_rope_rows(ctx._h if ctx else None, n, H, d, _ptr(pos), float(theta), _ptr(q))
+    if rc != IG_OK:
+        raise IgError(rc, ctx.last_error() if ctx else "ig_rope_rows")
+    return q
 
 
 def ig_partial_index(Qs, Ks, H, ratio, ctx=None):

@@ -119,6 +119,8 @@ int reserve_for(ig_ctx *ctx, const ig_desc *d, bool scores) {
   if (rc) return rc;
   rc = ig_ensure(ctx, (void **)&ctx->qp, &ctx->qp_bytes, (size_t)d->B * d->H * d->r * sizeof(float));
   if (rc) return rc;
+  rc = ig_ensure_zeroed(ctx, &ctx->pair_sync, &ctx->pair_sync_bytes, (size_t)d->B * d->H * IG_PAIR_SYNC_BYTES);
+  if (rc) return rc;
   if (scores) {
     const int tile = ig_tile_tokens(d->dtype);
     const int nTiles = (d->N_cap + tile - 1) / tile;
@@ -158,6 +160,9 @@ int ig_create(int device, ig_ctx **out) {
   ctx->pcount_bytes = 0;
   ctx->skew_ws = nullptr;
   ctx->skew_ws_bytes = 0;
+  ctx->pair_sync = nullptr;
+  ctx->pair_sync_bytes = 0;
+  ctx->spin_limit = IG_WAIT_LIMIT_DEFAULT;
   ctx->attn_part_bytes = ctx->attn_cnt_bytes = 0;
   ctx->part_bytes = ctx->qp_bytes = ctx->scores_bytes = ctx->tmax_bytes = 0;
   ctx->status = nullptr;
@@ -188,6 +193,7 @@ int ig_destroy(ig_ctx *ctx) {
   if (ctx->tmax) (void)hipFree(ctx->tmax);
   if (ctx->pcount) (void)hipFree(ctx->pcount);
   if (ctx->skew_ws) (void)hipFree(ctx->skew_ws);
+  if (ctx->pair_sync) (void)hipFree(ctx->pair_sync);
   if (ctx->attn_part) (void)hipFree(ctx->attn_part);
   if (ctx->attn_cnt) (void)hipFree(ctx->attn_cnt);
   if (ctx->status) (void)hipFree(ctx->status);
@@ -207,7 +213,7 @@ int ig_reserve(ig_ctx *ctx, const ig_desc *desc) {
 size_t ig_workspace_bytes(const ig_ctx *ctx) {
   if (!ctx) return 0;
   return ctx->part_bytes + ctx->qp_bytes + ctx->scores_bytes + ctx->tmax_bytes + ctx->pcount_bytes +
-         ctx->attn_part_bytes + ctx->attn_cnt_bytes + ctx->skew_ws_bytes;
+         ctx->attn_part_bytes + ctx->attn_cnt_bytes + ctx->skew_ws_bytes + ctx->pair_sync_bytes;
 }
 
 int ig_check_status(ig_ctx *ctx) {

@@ -151,3 +151,35 @@ extern "C" int ig_partial_index(ig_ctx *ctx, int H, int d, int n, const float *Q
   }
   return IG_OK;
 }
+
+// Y[:, head h] = X[:, head h] * A_h for every row of X (Eq. 2: the skewed query / key matrix of a
+// set of rows, e.g. the prompt's queries that ig_partial_index ranks).  In place when Y == X.
+extern "C" int ig_apply_skew(ig_ctx *ctx, int H, int d, int n, const float *X, const float *A, float *Y) {
+  if (H < 1 || d < 1 || n < 1) return ig_fail(ctx, IG_ESHAPE, "ig_apply_skew: bad shape");
+  if (!X || !A || !Y) return ig_fail(ctx, IG_EINVAL, "ig_apply_skew: NULL argument");
+  skew_rows(n, H * d, H, X, A, Y);   // a row's head block is read in full before it is written
+  return IG_OK;
+}
+
+// Rotary embedding of rows [n, H, d] in place, row i at position pos[i]: pairs (c, c + d/2) are
+// rotated by pos * theta^(-2c/d) (the convention of the rehearsal's own rotation, so that queries a
+// caller prepares on the host -- calibration queries, a layer's real query -- match the keys).
+extern "C" int ig_rope_rows(ig_ctx *ctx, int n, int H, int d, const int32_t *pos, double theta, float *q) {
+  if (n < 1 || H < 1 || d < 2 || d % 2) return ig_fail(ctx, IG_ESHAPE, "ig_rope_rows: bad shape (d must be even)");
+  if (!pos || !q) return ig_fail(ctx, IG_EINVAL, "ig_rope_rows: NULL argument");
+  if (!(theta > 0.0)) return ig_fail(ctx, IG_EINVAL, "ig_rope_rows: theta must be positive");
+  const int half = d / 2;
+  std::vector<double> freq(half);
+  for (int c = 0; c < half; ++c) freq[c] = pow(theta, -2.0 * (double)c / (double)d);
+  for (int i = 0; i < n; ++i)
+    for (int c = 0; c < half; ++c) {
+      const double ang = (double)pos[i] * freq[c], cs = cos(ang), sn = sin(ang);
+      for (int h = 0; h < H; ++h) {
+        float *row = q + ((size_t)i * H + h) * d;
+        const double a = row[c], b = row[c + half];
+        row[c] = (float)(a * cs - b * sn);
+        row[c + half] = (float)(b * cs + a * sn);
+      }
+    }
+  return IG_OK;
+}

@@ -41,6 +41,9 @@ constexpr int IG_WAVE = 64;
 constexpr int IG_KS_MAX = 16;     // split-K partial sums a consumer adds up at most
 constexpr int IG_STATUS_CAPACITY = 1;
 constexpr int IG_STATUS_NOCONV = 2;    // Jacobi sweeps of ig_skew_device left too much off the diagonal
+constexpr int IG_SPLIT_MAX = 28;         // workgroups a (b,h) pair's tiles are split over at most (scan)
+constexpr int IG_PAIR_SYNC_BYTES = 512;
+constexpr long IG_WAIT_LIMIT_DEFAULT = 2000000;   // 20 ms of the 100 MHz clock  // per-pair record through which the splits of a pair meet
 constexpr int IG_SLICE_MAX = 16;   // slices a selected-token list is cut into at most (gather, attention)
 
 // Slab geometry: tokens are grouped in tiles of 64 lanes x TPL tokens; inside a tile the r kept
@@ -78,6 +81,8 @@ struct ig_ctx {
   int32_t *pcount;  size_t pcount_bytes;  // long-sequence path: kept tokens per 4096-token part
   float *attn_part; size_t attn_part_bytes;  // attention: per-slice softmax states [B*H][16][d+2]
   int32_t *attn_cnt; size_t attn_cnt_bytes;  // attention: per-(b,h) arrival counters, zero between calls
+  void *pair_sync;  size_t pair_sync_bytes;  // scan: per-(b,h) records of pairs split over workgroups, zero between calls
+  long spin_limit;                           // scan: bound of a split's wait for its partners, 100 MHz ticks
   double *skew_ws;  size_t skew_ws_bytes;   // ig_skew_device: Gram matrices and eigenvectors [2][H][d][d]
   int32_t *status;                        // device status word (sticky flags)
   bool profiling;
@@ -176,6 +181,32 @@ int ig_launch_scan_attend(ig_ctx *ctx, const ig_desc *d, const QSource &qs, cons
                           const void *v_new, void *out, void *K_sel, void *V_sel, hipStream_t s);
 int ig_launch_copy(ig_ctx *ctx, const void *src, void *dst, size_t bytes, hipStream_t s);
 int ig_launch_read(ig_ctx *ctx, const void *src, size_t bytes, hipStream_t s);
+
+// ---- rotary embedding angle ---------------------------------------------------------------------
+// sin and cos of pos * theta^(-2c/d) in double (positions reach 1e5, where float loses the phase).
+// Quadrant reduction with a two-part pi/2 (the fused multiply-adds keep the products exact), then
+// the Taylor polynomials of sin and cos on [-pi/4, pi/4] to x^19 / x^18 (truncation below 1e-21):
+// a few dozen double FMAs and a handful of registers, where the library routine carries a
+// large-argument path the kernel never needs.
+__device__ __forceinline__ void rope_sincos(double ang, double *sn, double *cs) {
+  const double k = rint(ang * 0.63661977236758134308);          // 2 / pi
+  double x = fma(-k, 1.57079632679489655800e+00, ang);          // pi/2 rounded to double ...
+  x = fma(-k, 6.12323399573676603587e-17, x);                   // ... and what the rounding left
+  const double x2 = x * x;
+  double ps = 1.0, pc = 1.0;
+#pragma unroll
+  for (int n = 9; n >= 1; --n) {
+    ps = fma(-x2 * (1.0 / (double)((2 * n) * (2 * n + 1))), ps, 1.0);
+    pc = fma(-x2 * (1.0 / (double)((2 * n - 1) * (2 * n))), pc, 1.0);
+  }
+  const double s = x * ps, c = pc;
+  const int q = (int)k & 3;
+  *sn = q == 0 ? s : (q == 1 ? c : (q == 2 ? -s : -c));
+  *cs = q == 0 ? c : (q == 1 ? -s : (q == 2 ? -c : s));
+}
+__device__ __forceinline__ double rope_angle(int pos, int c, int d, float theta) {
+  return (double)pos * exp2(-2.0 * (double)c / (double)d * log2((double)theta));
+}
 
 // ---- wave helpers -------------------------------------------------------------------------------
 // Cross-lane moves inside a 16-lane row through DPP (no LDS crossbar traffic).

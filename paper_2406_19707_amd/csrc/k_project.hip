@@ -380,9 +380,8 @@ __global__ __launch_bounds__(256) void finalize_query(const float *__restrict__ 
   __syncthreads();
   const int half = d / 2;
   for (int c = t; c < half; c += 256) {
-    double ang = (double)pos[b] * exp2(-2.0 * (double)c / (double)d * log2((double)theta));
     double sn, cs;
-    sincos(ang, &sn, &cs);
+    rope_sincos(rope_angle(pos[b], c, d, theta), &sn, &cs);
     float a = q[c], bb = q[c + half];
     qr[c] = (float)((double)a * cs - (double)bb * sn);
     qr[c + half] = (float)((double)bb * cs + (double)a * sn);

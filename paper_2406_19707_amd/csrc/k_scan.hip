@@ -208,6 +208,329 @@ __global__ __launch_bounds__(1024) void select_write(ScanArgs a, const int32_t *
   }
 }
 
+// ---- streaming form: rolling load window, pairs optionally split over several workgroups ---------
+// For the kept-channel counts the workloads use (R is a template parameter) a wave's tiles are one
+// contiguous run of TPW*R KiB, read as a flat stream through a window of WIN 1 KiB loads: every
+// load is consumed in issue order and its register is refilled at once with the load WIN places
+// ahead, so a wave keeps WIN KiB in flight from its first instruction to its last, across tile
+// boundaries, with no clamped re-reads and no per-block drain.  A workgroup of NW waves covers
+// NW*TPW consecutive tiles of one (b,h); the scores stay in registers.
+//
+// A pair with more tiles than that is split over S consecutive workgroups (so that long sequences
+// with few (b,h) pairs still put every compute unit to work).  The splits meet twice through a
+// small per-pair record in device memory: once for the pair's maximum, once for the kept-token
+// counts that give each split its offset in the ascending list.  Every split publishes one
+// self-validating 8-byte word per meeting (relaxed agent-scope atomic store) and polls its
+// partners' words (relaxed agent-scope atomic loads); both waits are bounded.  A workgroup whose wait runs out (its partners were not scheduled in time) takes
+// the slow, self-sufficient route: it rescans the whole pair on its own and writes the whole list.
+// Every store on either route is the exact final value, so the routes can mix freely within a
+// pair; the last workgroup of a pair to finish zeroes the record for the next call.
+struct PairSync {
+  int done;            // splits that have finished with the record
+  int pad[3];
+  unsigned long long smax[IG_SPLIT_MAX];   // per split: bit 63 = published, low word = image of its maximum
+  unsigned long long scnt[IG_SPLIT_MAX];   // per split: bit 63 = published, low word = its kept-token count
+  int tail[12];
+};
+static_assert(sizeof(PairSync) == IG_PAIR_SYNC_BYTES, "PairSync size");
+constexpr unsigned long long PUBLISHED = 1ull << 63;
+
+__device__ __forceinline__ unsigned order_bits(float v) {
+  const unsigned u = __float_as_uint(v);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float order_float(unsigned k) {
+  return __uint_as_float((k & 0x80000000u) ? (k & 0x7fffffffu) : ~k);
+}
+
+// Wave 0 only.  Lane j < S polls slot j until every split has published; each slot carries its
+// own "published" bit, so nothing has to be ordered against anything else and plain (relaxed)
+// agent-scope atomics suffice -- no cache write-back or invalidation.  Returns false when `limit`
+// ticks of the 100 MHz clock pass first (limit < 0: gives up without looking, which forces the
+// slow route); *val is the lane's slot value (lanes >= S: just the bit).
+__device__ __forceinline__ bool poll_slots(const unsigned long long *slots, int S, int lane, long limit,
+                                           unsigned long long *val) {
+  *val = PUBLISHED;
+  if (limit < 0) return false;
+  const long t0 = wall_clock64();
+  while (true) {
+    unsigned long long v = PUBLISHED;
+    if (lane < S) v = __hip_atomic_load(slots + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (__ballot((v & PUBLISHED) != 0) == ~0ull) {
+      *val = v;
+      return true;
+    }
+    if (wall_clock64() - t0 > limit) return false;
+    __builtin_amdgcn_s_sleep(2);
+  }
+}
+
+// Threshold + ordered compaction for a workgroup whose wave w holds, in registers, the scores of
+// tiles tile0 + w*TPW + i (i < TPW); token order is (w, i, lane, e).  count_only: returns the
+// workgroup's number of kept tokens and writes nothing.
+template <int TPL, int NW, int TPW>
+__device__ __forceinline__ int compact_tiles(const float (&sc)[TPW][TPL], float thr, int base, int32_t *list,
+                                             int sel_stride, int t_first /* first token of wave 0, tile 0 */,
+                                             int *lds_cnt /* [NW*TPW] */, int w, int lane, bool count_only) {
+  constexpr int TILE = IG_WAVE * TPL;
+  unsigned mask[TPW];
+  int below[TPW], total[TPW];
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+    mask[i] = 0;
+    below[i] = total[i] = 0;
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) {
+      const bool keep = sc[i][e] >= thr;        // masked tokens hold -inf
+      const unsigned long long bal = __ballot(keep);
+      below[i] += lanes_below(bal);
+      total[i] += __popcll(bal);
+      mask[i] |= (keep ? 1u : 0u) << e;
+    }
+    if (lane == 0) lds_cnt[w * TPW + i] = total[i];
+  }
+  __syncthreads();
+  int before = 0, all = 0;
+#pragma unroll
+  for (int k = 0; k < NW * TPW; ++k) {
+    const int c = lds_cnt[k];
+    before += (k < w * TPW) ? c : 0;
+    all += c;
+  }
+  __syncthreads();   // lds_cnt is reused
+  if (count_only) return all;
+  int pos = base + before;
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+    int p = pos + below[i];
+    const int t0 = t_first + (w * TPW + i) * TILE + lane * TPL;
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) {
+      if (mask[i] & (1u << e)) {
+        if (p < sel_stride) list[p] = t0 + e;
+        ++p;
+      }
+    }
+    pos += total[i];
+  }
+  return all;
+}
+
+// The slow route, step by step: 16-byte loads in blocks of 8 channels, NW tiles per round in token
+// order, by this workgroup alone.  pair_max: the pair's maximum; rescan_pair: scores again, then
+// threshold and the whole ascending list and its count.
+template <typename T, int NW>
+__device__ __forceinline__ float pair_max(const ScanArgs &a, int bh, float q_lane, float *lds_max) {
+  constexpr int TPL = SlabElem<T>::TPL;
+  constexpr int TILE = IG_WAVE * TPL;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const T *head = static_cast<const T *>(a.slab) + (long)bh * a.nTiles * a.r * TILE;
+  const float qv[4] = {q_lane, 0.f, 0.f, 0.f};
+  typename SlabElem<T>::vec v[8];
+  float m = -INFINITY;
+  for (int ti = w; ti < a.nValid; ti += NW) {
+    const T *tile = head + (long)ti * a.r * TILE;
+    float acc[TPL];
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
+    load_block<T, 8>(tile, a.r, 0, lane, v);
+    scan_tile_given_q<T, 8>(a, tile, lane, v, qv, acc);
+#pragma unroll
+    for (int e = 0; e < TPL; ++e)
+      if (ti * TILE + lane * TPL + e < a.N) m = fmaxf(m, acc[e]);
+  }
+  m = wave_max(m);
+  __syncthreads();
+  if (lane == 0) lds_max[w] = m;
+  __syncthreads();
+  float mm = lds_max[0];
+#pragma unroll
+  for (int k = 1; k < NW; ++k) mm = fmaxf(mm, lds_max[k]);
+  return mm;
+}
+
+template <typename T, int NW>
+__device__ __forceinline__ void rescan_pair(const ScanArgs &a, int bh, float q_lane, float thr, int *lds_cnt) {
+  constexpr int TPL = SlabElem<T>::TPL;
+  constexpr int TILE = IG_WAVE * TPL;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const T *head = static_cast<const T *>(a.slab) + (long)bh * a.nTiles * a.r * TILE;
+  const float qv[4] = {q_lane, 0.f, 0.f, 0.f};
+  typename SlabElem<T>::vec v[8];
+  int base = 0;
+  for (int t0w = 0; t0w < a.nValid; t0w += NW) {
+    const int ti = t0w + w;
+    float acc[TPL];
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
+    if (ti < a.nValid) {
+      const T *tile = head + (long)ti * a.r * TILE;
+      load_block<T, 8>(tile, a.r, 0, lane, v);
+      scan_tile_given_q<T, 8>(a, tile, lane, v, qv, acc);
+    }
+    base += compact_block<TPL, NW>(acc, ti * TILE, a.N, thr, base, a.sel_idx + (long)bh * a.sel_stride,
+                                   a.sel_stride, lds_cnt, w, lane);
+  }
+  if (threadIdx.x == 0) {
+    a.sel_cnt[bh] = min(base, a.sel_stride);
+    if (base > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
+  }
+}
+
+template <int NW> struct StreamWindow { static constexpr int WIN = 16; };
+
+template <typename T, int R, int NW, int TPW, bool ROPE>
+__global__ __launch_bounds__(NW * 64) void scan_select_stream(ScanArgs a, int S, PairSync *sync, long spin_limit) {
+  constexpr int TPL = SlabElem<T>::TPL;
+  constexpr int TILE = IG_WAVE * TPL;
+  constexpr int WIN = StreamWindow<NW>::WIN;
+  constexpr int NLOAD = TPW * R;              // 1 KiB loads of a wave with all its tiles valid
+  typedef typename SlabElem<T>::vec vec;
+  __shared__ float lds_max[NW];
+  __shared__ int lds_cnt[NW * TPW];
+  __shared__ int lds_flag[2];
+  __shared__ float lds_gmax;
+  const int bh = blockIdx.x / S, s = blockIdx.x - bh * S;
+  const int b = bh / a.H, h = bh - b * a.H;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int tile0 = s * (NW * TPW);                       // first tile of this workgroup
+  const int my0 = tile0 + w * TPW;                        // first tile of this wave
+  const int nact = max(0, min(TPW, a.nValid - my0));      // valid tiles of this wave (wave-uniform)
+  // a wave with fewer valid tiles re-reads its last valid one in their place (masked below), so the
+  // load sequence is the same for every wave that has work
+  const char *tbase[TPW];
+#pragma unroll
+  for (int i = 0; i < TPW; ++i)
+    tbase[i] = reinterpret_cast<const char *>(static_cast<const T *>(a.slab) +
+                                              ((long)bh * a.nTiles + my0 + max(0, min(i, nact - 1))) * R * TILE);
+  const int lane_off = lane * (int)sizeof(vec);
+  constexpr int PLANE = TILE * (int)sizeof(T);            // bytes of one channel plane (1 KiB)
+  vec v[WIN];
+  QueryLoads ql;
+  if constexpr (!ROPE) query_issue(a, b, h, lane, 0, ql);
+  __builtin_amdgcn_sched_barrier(0);
+  if (nact > 0) {
+#pragma unroll
+    for (int k = 0; k < WIN && k < NLOAD; ++k)
+      v[k] = *reinterpret_cast<const vec *>(tbase[k / R] + (k % R) * PLANE + lane_off);
+  }
+  __builtin_amdgcn_sched_barrier(0);
+  float q_lane;
+  if constexpr (ROPE) {
+    __shared__ float q_lds[512], qr_lds[512], psum[NW * 64], qp_lds[256];
+    rope_query<NW * 64>(a, b, h, q_lds, qr_lds, psum, qp_lds);
+    q_lane = lane < R ? qp_lds[lane] * a.scale : 0.f;
+  } else {
+    q_lane = query_finish(a, ql);
+  }
+  float sc[TPW][TPL];
+#pragma unroll
+  for (int i = 0; i < TPW; ++i)
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) sc[i][e] = 0.f;
+  if (nact > 0) {
+    const int qbits = __float_as_int(q_lane);
+#pragma unroll
+    for (int k = 0; k < NLOAD; ++k) {
+      const int i = k / R, j = k % R;
+      const float qj = __int_as_float(__builtin_amdgcn_readlane(qbits, j));
+#pragma unroll
+      for (int e = 0; e < TPL; ++e) sc[i][e] = fmaf((float)v[k % WIN][e], qj, sc[i][e]);
+      if (k + WIN < NLOAD)
+        v[k % WIN] = *reinterpret_cast<const vec *>(tbase[(k + WIN) / R] + ((k + WIN) % R) * PLANE + lane_off);
+      __builtin_amdgcn_sched_barrier(0);     // keeps issue order = consumption order: WIN - 1 loads stay in flight
+    }
+  }
+  // mask, optional dump, workgroup maximum
+  float m = -INFINITY;
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+    const int t0 = (my0 + i) * TILE + lane * TPL;
+    if (a.scores_out && i < nact) store_scores<TPL>(a.scores_out, (long)bh * a.N, t0, a.N, sc[i]);
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) {
+      if (i >= nact || t0 + e >= a.N) sc[i][e] = -INFINITY;
+      m = fmaxf(m, sc[i][e]);
+    }
+  }
+  m = wave_max(m);
+  if (lane == 0) lds_max[w] = m;
+  __syncthreads();
+  float mm = lds_max[0];
+#pragma unroll
+  for (int k = 1; k < NW; ++k) mm = fmaxf(mm, lds_max[k]);
+  int32_t *list = a.sel_idx + (long)bh * a.sel_stride;
+  if (S == 1) {
+    const int all = compact_tiles<TPL, NW, TPW>(sc, mm - a.alpha, 0, list, a.sel_stride, 0, lds_cnt, w, lane, false);
+    if (threadIdx.x == 0) {
+      a.sel_cnt[bh] = min(all, a.sel_stride);
+      if (all > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
+    }
+    return;
+  }
+  // ---- the pair's splits meet: maximum ----
+  PairSync *ps = sync + bh;
+  if (w == 0) {
+    if (lane == 0)
+      __hip_atomic_store(&ps->smax[s], PUBLISHED | order_bits(mm), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned long long v;
+    const bool ok = poll_slots(ps->smax, S, lane, spin_limit, &v);
+    const float g = wave_max((ok && lane < S) ? order_float((unsigned)v) : -INFINITY);
+    if (lane == 0) {
+      lds_flag[0] = ok;
+      lds_gmax = g;
+    }
+  }
+  __syncthreads();
+  const bool slow = lds_flag[0] == 0;
+  // the partners' maxima did not arrive in time: find the pair's maximum alone (this split's
+  // count can then be published all the same, so that partners which are only late are not held up)
+  const float gmax = slow ? pair_max<T, NW>(a, bh, q_lane, lds_max) : lds_gmax;
+  const float thr = gmax - a.alpha;
+  // ---- the pair's splits meet: counts ----
+  const int mine = compact_tiles<TPL, NW, TPW>(sc, thr, 0, list, a.sel_stride, 0, lds_cnt, w, lane, true);
+  if (w == 0) {
+    if (lane == 0)
+      __hip_atomic_store(&ps->scnt[s], PUBLISHED | (unsigned)mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned long long v = 0;
+    const bool ok = !slow && poll_slots(ps->scnt, S, lane, spin_limit, &v);
+    const int c = (ok && lane < S) ? (int)(unsigned)v : 0;
+    const int all = wave_sum(c), base = wave_sum(lane < s ? c : 0);
+    if (lane == 0) {
+      lds_flag[1] = ok;
+      lds_cnt[0] = base;
+      lds_flag[0] = all;
+    }
+    // a split that goes on alone makes sure its own slots have landed before it reports "done"
+    if (!ok) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  }
+  __syncthreads();
+  if (lds_flag[1]) {
+    const int base = lds_cnt[0], all = lds_flag[0];
+    __syncthreads();
+    compact_tiles<TPL, NW, TPW>(sc, thr, base, list, a.sel_stride, tile0 * TILE, lds_cnt, w, lane, false);
+    if (s == S - 1 && threadIdx.x == 0) {
+      a.sel_cnt[bh] = min(all, a.sel_stride);
+      if (all > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
+    }
+  } else {
+    rescan_pair<T, NW>(a, bh, q_lane, thr, lds_cnt);
+  }
+  // ---- done with the record; the last split to get here clears it for the next call ----
+  if (w == 0) {
+    int prev = 0;
+    if (lane == 0) prev = __hip_atomic_fetch_add(&ps->done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    prev = __builtin_amdgcn_readfirstlane(prev);
+    if (prev == S - 1) {
+      if (lane < S) {
+        __hip_atomic_store(&ps->smax[lane], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&ps->scnt[lane], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      if (lane == 0) __hip_atomic_store(&ps->done, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
 // channel block size: the smallest multiple of 4 (<= 40) whose multiples cover r with least waste
 int pick_ch(int r, int cap) {
   return ig_pick_ch(r, cap);
@@ -261,6 +584,42 @@ int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
   }
 #undef CASE
   return ig_fail(ctx, IG_ESHAPE, "scan: unsupported channel block %d", ch);
+}
+
+// streaming form: (kept channels, waves per workgroup, tiles per wave) combinations that are built
+template <typename T, int R, int NW, int TPW>
+int launch_stream_one(ig_ctx *ctx, const ScanArgs &a, int BH, int S, hipStream_t s) {
+  dim3 grid((unsigned)(BH * S)), block(NW * 64);
+  PairSync *sync = static_cast<PairSync *>(ctx->pair_sync);
+  if (a.A_p) {
+    auto k = scan_select_stream<T, R, NW, TPW, true>;
+    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, S, sync, ctx->spin_limit);
+  } else {
+    auto k = scan_select_stream<T, R, NW, TPW, false>;
+    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, S, sync, ctx->spin_limit);
+  }
+  return IG_OK;
+}
+
+template <typename T, int R>
+int launch_stream_r(ig_ctx *ctx, const ScanArgs &a, int BH, int NW, int TPW, int S, hipStream_t s) {
+  if (NW == 4 && TPW == 1) return launch_stream_one<T, R, 4, 1>(ctx, a, BH, S, s);
+  if (NW == 4 && TPW == 2) return launch_stream_one<T, R, 4, 2>(ctx, a, BH, S, s);
+  if (NW == 4 && TPW == 4) return launch_stream_one<T, R, 4, 4>(ctx, a, BH, S, s);
+  if (NW == 8 && TPW == 1) return launch_stream_one<T, R, 8, 1>(ctx, a, BH, S, s);
+  if (NW == 8 && TPW == 2) return launch_stream_one<T, R, 8, 2>(ctx, a, BH, S, s);
+  return ig_fail(ctx, IG_ESHAPE, "scan: streaming form %d x %d is not built", NW, TPW);
+}
+
+int launch_stream(ig_ctx *ctx, const ScanArgs &a, int BH, int NW, int TPW, int S, hipStream_t s) {
+  if (S < 1 || S > IG_SPLIT_MAX) return ig_fail(ctx, IG_ESHAPE, "scan: %d splits per pair", S);
+  if (S > 1) {
+    int rc = ig_ensure_zeroed(ctx, &ctx->pair_sync, &ctx->pair_sync_bytes, (size_t)BH * IG_PAIR_SYNC_BYTES);
+    if (rc) return rc;
+  }
+  if (a.r == 38) return launch_stream_r<half_t, 38>(ctx, a, BH, NW, TPW, S, s);
+  if (a.r == 25) return launch_stream_r<half_t, 25>(ctx, a, BH, NW, TPW, S, s);
+  return ig_fail(ctx, IG_ESHAPE, "scan: streaming form is not built for r = %d", a.r);
 }
 
 template <typename T>

@@ -171,27 +171,35 @@ __device__ __forceinline__ void rope_query(const ScanArgs &a, int b, int h, floa
     for (int s = 0; s < IG_KS_MAX; ++s) acc += v[s];
     q_lds[c] = acc;
   }
+  // the thread's rows of A_p do not depend on the query: they are put in flight now and travel
+  // while the rotation is worked out (up to PF rows per thread; longer runs are read in the loop)
+  const int RK = r <= 64 ? 64 : (r <= 128 ? 128 : 256);
+  const int G = THREADS / RK;
+  const int k = t % RK, g = t / RK;
+  const int per = (d + G - 1) / G;
+  const int c0 = min(d, g * per), c1 = min(d, (g + 1) * per);
+  constexpr int PF = THREADS >= 512 ? 8 : 16;
+  __builtin_amdgcn_sched_barrier(0);      // not before the partial sums above have been consumed
+  float apf[PF];
+  const float *ap = a.A_p + (long)h * d * r + min(k, r - 1);
+#pragma unroll
+  for (int i = 0; i < PF; ++i) apf[i] = (c0 + i < c1) ? ap[(long)(c0 + i) * r] : 0.f;
   __syncthreads();
   const int half = d / 2;
   for (int c = t; c < half; c += THREADS) {
-    const double ang = (double)a.pos[b] * exp2(-2.0 * (double)c / (double)d * log2((double)a.theta));
     double sn, cs;
-    sincos(ang, &sn, &cs);
+    rope_sincos(rope_angle(a.pos[b], c, d, a.theta), &sn, &cs);
     const float x0 = q_lds[c], x1 = q_lds[c + half];
     qr_lds[c] = (float)((double)x0 * cs - (double)x1 * sn);
     qr_lds[c + half] = (float)((double)x1 * cs + (double)x0 * sn);
   }
   __syncthreads();
-  const int RK = r <= 64 ? 64 : (r <= 128 ? 128 : 256);
-  const int G = THREADS / RK;
-  const int k = t % RK, g = t / RK;
-  const int per = (d + G - 1) / G;
   float acc = 0.f;
   if (k < r) {
-    const float *ap = a.A_p + (long)h * d * r + k;
-    const int c1 = min(d, (g + 1) * per);
-#pragma unroll 8
-    for (int c = min(d, g * per); c < c1; ++c) acc = fmaf(qr_lds[c], ap[(long)c * r], acc);
+#pragma unroll
+    for (int i = 0; i < PF; ++i)
+      if (c0 + i < c1) acc = fmaf(qr_lds[c0 + i], apf[i], acc);
+    for (int c = c0 + PF; c < c1; ++c) acc = fmaf(qr_lds[c], ap[(long)c * r], acc);
   }
   psum[t] = acc;
   __syncthreads();

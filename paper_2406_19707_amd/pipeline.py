@@ -17,16 +17,6 @@ import ig_workloads as wl
 from . import binding as ig
 
 
-def _rope_rows(q: np.ndarray, pos: np.ndarray, theta: float = 10000.0) -> np.ndarray:
-    """Model-side rotary embedding of query rows [rows, H, d] (rotate-half pairing)."""
-    rows, H, d = q.shape
-    half = d // 2
-    ang = pos.astype(np.float64)[:, None] * theta ** (-2.0 * np.arange(half) / d)[None, :]
-    c, s = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
-    a, b = q[..., :half].astype(np.float64), q[..., half:].astype(np.float64)
-    return np.concatenate([a * c - b * s, b * c + a * s], -1).astype(np.float32)
-
-
 class Rehearsal:
     """State of `layers` decoder layers of one workload and the hot-path call sequence over them."""
 
@@ -44,7 +34,7 @@ class Rehearsal:
             # same model (weights, skewing, partial index, weight blob), other layers / capacity
             o_ = offline_from
             assert o_.w is w and o_.gain == self.gain
-            for name in ("A", "idx_host", "r", "idx", "W_host", "wq", "A_p", "pos", "_Wd", "_A_dev"):
+            for name in ("A", "idx_host", "r", "idx", "W_host", "wq", "A_p", "pos", "_Wd"):
                 setattr(self, name, getattr(o_, name))
             self.desc = ig.IgDesc(B=w.B, H=w.H, d=w.d, r=self.r, N=w.N, N_cap=self.N_cap,
                                   dtype=o_.desc.dtype, scale=o_.desc.scale, alpha=w.alpha,
@@ -58,14 +48,14 @@ class Rehearsal:
         Xcal = wl.calibration_input(w)
         Qcal = Xcal @ Wq
         if w.rope:
-            Qcal = _rope_rows(Qcal.reshape(w.n_cal, w.H, w.d),
-                              np.arange(w.n_cal)).reshape(w.n_cal, w.D)
+            Qcal = ig.ig_rope_rows(Qcal.reshape(w.n_cal, w.H, w.d), np.arange(w.n_cal),
+                                   ctx=ctx).reshape(w.n_cal, w.D)
         log("weights drawn")
         sk = ig.ig_skew_offline(Wq, None, Qcal, w.H, ctx=ctx)
         self.A = sk["A"]
         log("skewed")
         # ---- prefill: partial weight index (Section 4.3), query-only ranking on Q~ = Qcal A ----
-        Qs = np.einsum("nhk,hkj->nhj", Qcal.reshape(w.n_cal, w.H, w.d), self.A).reshape(w.n_cal, w.D)
+        Qs = ig.ig_apply_skew(Qcal, self.A, ctx=ctx)
         self.idx_host = ig.ig_partial_index(Qs, None, w.H, w.ratio, ctx=ctx)
         self.r = self.idx_host.shape[1]
         self.desc = ig.IgDesc(B=w.B, H=w.H, d=w.d, r=self.r, N=w.N, N_cap=self.N_cap,
@@ -84,7 +74,6 @@ class Rehearsal:
             self.A_p = torch.from_numpy(np.ascontiguousarray(A_p)).to(dev)
             self.pos = torch.full((w.B,), w.N, dtype=torch.int32, device=dev)
         self._Wd = Wd                      # weight the stand-in model uses for the layer's real query
-        self._A_dev = torch.from_numpy(self.A).to(dev)
         ctx.ig_reserve(self.desc)
         log("partial weight built")
         self._build_layers(host_layers, sets, log)
@@ -93,7 +82,7 @@ class Rehearsal:
         """Per-layer state: layer inputs, the layer's real query, KV pool, partial key cache."""
         ctx, w, dev, tdt = self.ctx, self.w, "cuda", self.tdt
         extra_tokens = self.N_cap - w.N
-        Wq_model, A_dev = self._Wd, self._A_dev
+        Wq_model = self._Wd
         self.host_pool = w.pool == "host"
         self.n_pool = min(self.L, host_layers) if self.host_pool else self.L
         self.x, self.q, self.slab, self.K, self.V = [], [], [], [], []
@@ -122,8 +111,9 @@ class Rehearsal:
             # the layer's real (skewed) query: the stand-in model's projection of its own input
             qf = (xn.to(tdt) @ Wq_model).float().reshape(w.B, w.H, w.d)
             if w.rope:
-                qf = torch.from_numpy(_rope_rows(qf.cpu().numpy(), np.full(w.B, w.N))).to(dev)
-                qf = torch.einsum("bhk,hkj->bhj", qf, A_dev)
+                qh = ig.ig_rope_rows(qf.cpu().numpy(), np.full(w.B, w.N), ctx=ctx)
+                qf = torch.from_numpy(ig.ig_apply_skew(qh.reshape(w.B, w.D), self.A, ctx=ctx)
+                                      ).to(dev).reshape(w.B, w.H, w.d)
             q = qf.to(tdt).contiguous()
             slab = torch.empty(slab_bytes, dtype=torch.uint8, device=dev)
             ctx.ig_slab_build(self.desc, K, ig.IG_MEM_DEVICE, self.idx, slab)

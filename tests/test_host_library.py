@@ -100,3 +100,18 @@ def test_product_package_does_not_import_the_oracle():
             if f.endswith((".py", ".hip", ".cpp", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert "oracle" not in text.lower().replace("no fallback", ""), f
+
+
+def test_apply_skew_and_rope_rows_match_oracle(ig):
+    rng = np.random.default_rng(7)
+    H, d, n = 3, 8, 5
+    X = rng.standard_normal((n, H * d)).astype(np.float32)
+    A = np.stack([np.linalg.qr(rng.standard_normal((d, d)))[0] for _ in range(H)]).astype(np.float32)
+    assert np.abs(ig.ig_apply_skew(X, A) - o.apply_skew(X, A)).max() <= 1e-6
+    pos = np.array([0, 1, 77, 4096, 100000], np.int32)
+    q = X.reshape(n, H, d)
+    assert np.abs(ig.ig_rope_rows(q, pos) - o.rope(q, pos)).max() <= 1e-6
+    assert np.array_equal(ig.ig_rope_rows(q, np.zeros(n, np.int32)), q)      # position 0: identity
+    L = ig.lib()
+    assert L.ig_apply_skew(None, 0, d, n, None, None, None) == ig.IG_ESHAPE
+    assert L.ig_rope_rows(None, n, H, 7, None, 10000.0, None) == ig.IG_ESHAPE  # odd head dimension
