@@ -308,6 +308,13 @@ int ig_layer_step(ig_ctx *ctx, const ig_desc *desc, const void *x, const void *w
                   const int32_t *sel_idx, const int32_t *sel_cnt, int32_t sel_stride, void *K_sel,
                   void *V_sel, const void *k_new, const void *v_new, void *out, void *stream);
 
+/* Long sequences are scanned by several workgroups per (sequence, head), which meet through device
+ * memory; each waits for its partners at most `ticks` periods of the GPU's 100 MHz clock (10 ns)
+ * and then finishes the pair on its own (slower, same result bit for bit).  0 restores the
+ * default (20 ms); a negative value makes every such workgroup take the self-sufficient route
+ * without waiting at all -- the hook the tests use to exercise that route. */
+int ig_set_wait_limit(ig_ctx *ctx, int64_t ticks);
+
 /* Between ig_profile_begin and ig_profile_end every kernel the context launches carries a pair of
  * HIP events that take the kernel's own start and stop timestamps.  ig_profile_end synchronises
  * the device and stops recording; ig_profile_read then returns, for kernel id `which`

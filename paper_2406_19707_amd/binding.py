@@ -35,7 +35,7 @@ EXPORTS = [
     "ig_pool_touch", "ig_pool_victim", "ig_pool_replace",
     "ig_speculate", "ig_project", "ig_scan_select", "ig_project_indexed", "ig_speculate_indexed",
     "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention",
-    "ig_sparse_attention_indexed", "ig_gather_attention", "ig_layer_step", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
+    "ig_sparse_attention_indexed", "ig_gather_attention", "ig_layer_step", "ig_set_wait_limit", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
     "ig_copy_bytes", "ig_read_bytes",
 ]
 
@@ -110,6 +110,7 @@ def lib():
             "ig_sparse_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
             "ig_sparse_attention_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
             "ig_gather_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+            "ig_set_wait_limit": (ctypes.c_int, [_vp, ctypes.c_int64]),
             "ig_profile_begin": (ctypes.c_int, [_vp]),
             "ig_profile_end": (ctypes.c_int, [_vp]),
             "ig_profile_read": (ctypes.c_int, [_vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
@@ -358,6 +359,9 @@ class Context:
                                            _ptr(Vpool), _ptr(sel_idx), sel_stride, _ptr(sel_cnt),
                                            _ptr(K_sel), _ptr(V_sel), _ptr(k_new), _ptr(v_new),
                                            _ptr(out), _stream(stream)))
+
+    def ig_set_wait_limit(self, ticks: int):
+        self._ck(lib().ig_set_wait_limit(self._h, int(ticks)))
 
     def ig_profile_begin(self):
         self._ck(lib().ig_profile_begin(self._h))

@@ -456,13 +456,8 @@ int ig_speculate(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, c
   ProjGeom g;
   hipStream_t s = (hipStream_t)stream;
   if ((rc = project_partials(ctx, d, x, wq, A_p, pos, &g, s))) return rc;
-  if (d->rope && ig_scan_is_fused(d)) {
-    // rotary embedding and the partial skew sit between the projection and the scan: the scan's
-    // workgroups work them out themselves while their first slab loads are in flight
-    QSource q{ctx->part, g.KS, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias, A_p, pos};
-    return ig_launch_scan_select(ctx, d, q, slab, sel_idx, sel_stride, sel_cnt, scores_opt, s);
-  }
   if (d->rope) {
+    // rotary embedding and the partial skew sit between the projection and the scan
     if ((rc = ig_launch_finalize(ctx, d, g, ctx->part, bias, A_p, pos, ctx->qp, s))) return rc;
     QSource q{ctx->qp, 1, 0, (long)d->H * d->r, nullptr};
     return ig_launch_scan_select(ctx, d, q, slab, sel_idx, sel_stride, sel_cnt, scores_opt, s);
@@ -563,25 +558,25 @@ int ig_layer_step(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, 
   ProjGeom g;
   hipStream_t s = (hipStream_t)stream;
   if ((rc = project_partials(ctx, d, x, wq, A_p, pos, &g, s))) return rc;
+  QSource qs{ctx->part, g.KS, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias};
+  if (d->rope) {
+    if ((rc = ig_launch_finalize(ctx, d, g, ctx->part, bias, A_p, pos, ctx->qp, s))) return rc;
+    qs = QSource{ctx->qp, 1, 0, (long)d->H * d->r, nullptr};
+  }
   if (!ig_layer_step_is_joint(d)) {
     // other shapes: the two launches one after the other
-    if (d->rope && !ig_scan_is_fused(d)) {
-      if ((rc = ig_launch_finalize(ctx, d, g, ctx->part, bias, A_p, pos, ctx->qp, s))) return rc;
-      QSource qs{ctx->qp, 1, 0, (long)d->H * d->r, nullptr};
-      rc = ig_launch_scan_select(ctx, d, qs, slab, sel_idx_next, sel_stride, sel_cnt_next, nullptr, s);
-    } else {
-      QSource qs{ctx->part, g.KS, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias, d->rope ? A_p : nullptr,
-                 d->rope ? pos : nullptr};
-      rc = ig_launch_scan_select(ctx, d, qs, slab, sel_idx_next, sel_stride, sel_cnt_next, nullptr, s);
-    }
-    if (rc) return rc;
+    if ((rc = ig_launch_scan_select(ctx, d, qs, slab, sel_idx_next, sel_stride, sel_cnt_next, nullptr, s))) return rc;
     return ig_launch_attention(ctx, d, q, Kpool, Vpool, sel_idx, sel_stride, sel_cnt, d->N_cap, k_new,
                                v_new, out, K_sel, V_sel, s);
   }
-  QSource qs{ctx->part, g.KS, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias, d->rope ? A_p : nullptr,
-             d->rope ? pos : nullptr};
   return ig_launch_scan_attend(ctx, d, qs, slab, sel_idx_next, sel_cnt_next, q, Kpool, Vpool, sel_idx,
                                sel_cnt, sel_stride, k_new, v_new, out, K_sel, V_sel, s);
+}
+
+int ig_set_wait_limit(ig_ctx *ctx, int64_t ticks) {
+  if (!ctx) return IG_EINVAL;
+  ctx->spin_limit = ticks == 0 ? IG_WAIT_LIMIT_DEFAULT : (long)ticks;
+  return IG_OK;
 }
 
 int ig_profile_begin(ig_ctx *ctx) {

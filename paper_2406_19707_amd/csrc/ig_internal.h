@@ -140,12 +140,9 @@ struct QSource {
   long ks_stride;
   long b_stride;
   const float *bias;
-  // rotary models, fused scan only: qsrc holds the full projection's partial sums ([ks][b][D]
-  // columns) and the scan derives the partial query from them with A_p [H,d,r] and pos [B]
-  const float *A_p = nullptr;
-  const int32_t *pos = nullptr;
 };
 bool ig_scan_is_fused(const ig_desc *d);
+bool ig_scan_stream_form(const ig_desc *d, int *tiles_per_wave, int *splits);
 int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const void *slab,
                           int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
                           float *scores_opt, hipStream_t s);

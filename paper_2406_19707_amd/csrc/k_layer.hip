@@ -12,10 +12,10 @@
 
 namespace {
 
-template <typename T, int CH, bool ROPE>
+template <typename T, int CH>
 __global__ __launch_bounds__(256) void scan_next_attend_this(ScanArgs sa, AttnArgs aa, int scan_blocks) {
   if ((int)blockIdx.x < scan_blocks)
-    scan_select_fused_body<T, CH, 4, ROPE>(sa, blockIdx.x);
+    scan_select_fused_body<T, CH, 4>(sa, blockIdx.x);
   else
     sparse_attention_body<T, true>(aa, (int)blockIdx.x - scan_blocks);
 }
@@ -25,13 +25,8 @@ int launch_t(ig_ctx *ctx, const ScanArgs &sa, const AttnArgs &aa, int BH, int ch
   dim3 grid(BH + BH * SLICE_MAX), block(256);
 #define CASE(CHV)                                                              \
   case CHV: {                                                                  \
-    if (sa.A_p) {                                                              \
-      auto k = scan_next_attend_this<T, CHV, true>;                            \
-      IG_LAUNCH(ctx, IG_K_LAYER, k, grid, block, s, sa, aa, BH);               \
-    } else {                                                                   \
-      auto k = scan_next_attend_this<T, CHV, false>;                           \
-      IG_LAUNCH(ctx, IG_K_LAYER, k, grid, block, s, sa, aa, BH);               \
-    }                                                                          \
+    auto k = scan_next_attend_this<T, CHV>;                                    \
+    IG_LAUNCH(ctx, IG_K_LAYER, k, grid, block, s, sa, aa, BH);                 \
     return IG_OK;                                                              \
   }
   switch (ch) {

@@ -352,6 +352,7 @@ __global__ __launch_bounds__(256) void project_columns_mfma(const half_t *__rest
 // rope:   q[c] = bias[h*d+c] + sum_s part[s][b][h*d+c]; rotate pairs (c, c+d/2) by
 //         pos[b]*theta^(-2c/d) (angle in double: positions reach 1e5 where float loses the phase);
 //         q_p[b,h,k] = sum_c q_rot[c] * A_p[h][c][k]
+// (Section 4.3 "Decoding Stage" for models whose skew cannot be folded into W_Q.)
 __global__ __launch_bounds__(256) void finalize_query(const float *__restrict__ part,
                                                       const float *__restrict__ bias,
                                                       const float *__restrict__ A_p,
@@ -364,41 +365,69 @@ __global__ __launch_bounds__(256) void finalize_query(const float *__restrict__ 
   __shared__ float psum[256];
   const int bh = blockIdx.x, b = bh / H, h = bh % H;
   const int t = threadIdx.x;
-  const int width = rope ? d : r;          // columns of this head in the partial-sum buffer
-  // split-K partial sums: all loads of a column issued together, added in a fixed order
-  for (int c = t; c < width; c += 256) {
-    const float *p = part + (long)b * Cpad + (long)h * width + c;
-    float v[IG_KS_MAX];
+  if (!rope) {
+    // split-K partial sums: all loads of a column issued together, added in a fixed order
+    for (int c = t; c < r; c += 256) {
+      const float *p = part + (long)b * Cpad + (long)h * r + c;
+      float v[IG_KS_MAX];
 #pragma unroll
-    for (int s = 0; s < IG_KS_MAX; ++s) v[s] = (s < KS) ? p[s * ks_stride] : 0.f;
-    float acc = bias ? bias[h * width + c] : 0.f;
+      for (int s = 0; s < IG_KS_MAX; ++s) v[s] = (s < KS) ? p[s * ks_stride] : 0.f;
+      float acc = bias ? bias[h * r + c] : 0.f;
 #pragma unroll
-    for (int s = 0; s < IG_KS_MAX; ++s) acc += v[s];
-    if (rope) q[c] = acc; else q_p[(long)bh * r + c] = acc;
+      for (int s = 0; s < IG_KS_MAX; ++s) acc += v[s];
+      q_p[(long)bh * r + c] = acc;
+    }
+    return;
   }
-  if (!rope) return;
-  __syncthreads();
-  const int half = d / 2;
-  for (int c = t; c < half; c += 256) {
-    double sn, cs;
-    rope_sincos(rope_angle(pos[b], c, d, theta), &sn, &cs);
-    float a = q[c], bb = q[c + half];
-    qr[c] = (float)((double)a * cs - (double)bb * sn);
-    qr[c + half] = (float)((double)bb * cs + (double)a * sn);
+  // Rotary model.  The block is one chain of dependent steps, so everything it reads is put in
+  // flight before the first step: the partial sums of its (up to two) columns, the position, and
+  // the thread's rows of A_p, which do not depend on the query at all.
+  float v[2][IG_KS_MAX], bs[2];
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int c = min(t + 256 * u, d - 1);
+    const float *p = part + (long)b * Cpad + (long)h * d + c;
+#pragma unroll
+    for (int s = 0; s < IG_KS_MAX; ++s) v[u][s] = (s < KS) ? p[s * ks_stride] : 0.f;
+    bs[u] = bias ? bias[h * d + c] : 0.f;
   }
-  __syncthreads();
+  const int position = pos[b];
   // q_p[k] = sum_c qr[c] * A_p[h][c][k]: the 256 threads are G groups of RK; group g sums its share
   // of the rows c for output k (reads of A_p coalesce over k), then the groups are added in order
   const int RK = r <= 64 ? 64 : (r <= 128 ? 128 : 256);
   const int G = 256 / RK;
   const int k = t % RK, g = t / RK;
   const int per = (d + G - 1) / G;
+  const int c0 = min(d, g * per), c1 = min(d, (g + 1) * per);
+  constexpr int PF = 32;
+  const float *ap = A_p + (long)h * d * r + min(k, r - 1);
+  float apf[PF];
+#pragma unroll
+  for (int i = 0; i < PF; ++i) apf[i] = (c0 + i < c1) ? ap[(long)(c0 + i) * r] : 0.f;
+#pragma unroll
+  for (int u = 0; u < 2; ++u) {
+    const int c = t + 256 * u;
+    float acc = bs[u];
+#pragma unroll
+    for (int s = 0; s < IG_KS_MAX; ++s) acc += v[u][s];
+    if (c < d) q[c] = acc;
+  }
+  __syncthreads();
+  const int half = d / 2;
+  for (int c = t; c < half; c += 256) {
+    double sn, cs;
+    rope_sincos(rope_angle(position, c, d, theta), &sn, &cs);
+    float a = q[c], bb = q[c + half];
+    qr[c] = (float)((double)a * cs - (double)bb * sn);
+    qr[c + half] = (float)((double)bb * cs + (double)a * sn);
+  }
+  __syncthreads();
   float acc = 0.f;
   if (k < r) {
-    const float *ap = A_p + (long)h * d * r + k;
-    const int c1 = min(d, (g + 1) * per);
-#pragma unroll 8
-    for (int c = g * per; c < c1; ++c) acc = fmaf(qr[c], ap[(long)c * r], acc);
+#pragma unroll
+    for (int i = 0; i < PF; ++i)
+      if (c0 + i < c1) acc = fmaf(qr[c0 + i], apf[i], acc);
+    for (int c = c0 + PF; c < c1; ++c) acc = fmaf(qr[c], ap[(long)c * r], acc);
   }
   psum[t] = acc;
   __syncthreads();

@@ -10,16 +10,16 @@
 // one lane without any cross-lane reduction.  The kernel is HBM-bound (1 FMA per 2 bytes).
 //
 // The partial query comes from the projection's split-K partial sums, added here in a fixed order
-// (no separate reduction kernel); for rotary models on the fused path the workgroup also applies
-// the rotation and the partial skew itself (rope_query) while its first slab loads are in flight.
+// (no separate reduction kernel), or, for rotary models, finished from the finalisation kernel
+// that applies the rotation and the partial skew between projection and scan.
 #include "scan_device.h"
 
 namespace {
 
 // One workgroup per (b,h); wave w scans tile w (nValid <= NW) and keeps its scores in registers.
-template <typename T, int CH, int NW, bool ROPE>
+template <typename T, int CH, int NW>
 __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
-  scan_select_fused_body<T, CH, NW, ROPE>(a, blockIdx.x);
+  scan_select_fused_body<T, CH, NW>(a, blockIdx.x);
 }
 
 // Sequences of up to LDS_SCORES tokens that do not fit 16 waves at once: still one workgroup of
@@ -28,7 +28,7 @@ __global__ __launch_bounds__(NW * 64) void scan_select_fused(ScanArgs a) {
 // kernels.  The waves run through their tiles without meeting; they meet once for the maximum.
 constexpr int LDS_SCORES = 32768;
 
-template <typename T, int CH, bool ROPE>
+template <typename T, int CH>
 __global__ __launch_bounds__(1024) void scan_select_lds(ScanArgs a) {
   constexpr int TPL = SlabElem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
@@ -40,23 +40,16 @@ __global__ __launch_bounds__(1024) void scan_select_lds(ScanArgs a) {
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const T *head = static_cast<const T *>(a.slab) + (long)bh * a.nTiles * a.r * TILE;
   typename SlabElem<T>::vec v[CH];
-  // first channel block of the wave's first tile in flight while the partial query is worked out
+  // first channel block of the wave's first tile in flight while the partial query arrives
   if (w < a.nValid) load_block<T, CH>(head + (long)w * a.r * TILE, a.r, 0, lane, v);
   float qv[4];
-  if constexpr (ROPE) {
-    __shared__ float q_lds[512], qr_lds[512], psum[NW * 64], qp_lds[256];
-    rope_query<NW * 64>(a, b, h, q_lds, qr_lds, psum, qp_lds);
 #pragma unroll
-    for (int k = 0; k < 4; ++k) qv[k] = (lane + 64 * k < a.r) ? qp_lds[lane + 64 * k] * a.scale : 0.f;
-  } else {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      qv[k] = 0.f;
-      if (64 * k < a.r) {
-        QueryLoads ql;
-        query_issue(a, b, h, lane, k, ql);
-        qv[k] = query_finish(a, ql);
-      }
+  for (int k = 0; k < 4; ++k) {
+    qv[k] = 0.f;
+    if (64 * k < a.r) {
+      QueryLoads ql;
+      query_issue(a, b, h, lane, k, ql);
+      qv[k] = query_finish(a, ql);
     }
   }
   float m = -INFINITY;
@@ -266,53 +259,59 @@ __device__ __forceinline__ bool poll_slots(const unsigned long long *slots, int 
 }
 
 // Threshold + ordered compaction for a workgroup whose wave w holds, in registers, the scores of
-// tiles tile0 + w*TPW + i (i < TPW); token order is (w, i, lane, e).  count_only: returns the
-// workgroup's number of kept tokens and writes nothing.
+// tiles w*TPW + i (i < TPW) counted from token t_first; token order is (w, i, lane, e).
+// count_only: returns the workgroup's number of kept tokens and writes nothing.  Otherwise every
+// wave first packs its kept token ids into its own LDS row (stage, TPW*TILE entries per wave) and
+// then copies the row out with whole-wave stores: a handful of coalesced store instructions per
+// wave instead of one scattered store per score register, which matters because every memory
+// instruction of the epilogue queues behind the other workgroups' streaming loads.
 template <int TPL, int NW, int TPW>
-__device__ __forceinline__ int compact_tiles(const float (&sc)[TPW][TPL], float thr, int base, int32_t *list,
-                                             int sel_stride, int t_first /* first token of wave 0, tile 0 */,
-                                             int *lds_cnt /* [NW*TPW] */, int w, int lane, bool count_only) {
+__device__ __forceinline__ int compact_tiles(const float (&sc)[TPW][TPL], float thr, int N, int base,
+                                             int32_t *list, int sel_stride, int t_first, int *lds_cnt /* [NW] */,
+                                             int32_t *stage, int w, int lane, bool count_only) {
   constexpr int TILE = IG_WAVE * TPL;
   unsigned mask[TPW];
-  int below[TPW], total[TPW];
+  int rank[TPW], mine = 0;
 #pragma unroll
   for (int i = 0; i < TPW; ++i) {
+    const int t0 = t_first + (w * TPW + i) * TILE + lane * TPL;
     mask[i] = 0;
-    below[i] = total[i] = 0;
+    int below = 0, total = 0;
 #pragma unroll
     for (int e = 0; e < TPL; ++e) {
-      const bool keep = sc[i][e] >= thr;        // masked tokens hold -inf
+      const bool keep = t0 + e < N && sc[i][e] >= thr;
       const unsigned long long bal = __ballot(keep);
-      below[i] += lanes_below(bal);
-      total[i] += __popcll(bal);
+      below += lanes_below(bal);
+      total += __popcll(bal);
       mask[i] |= (keep ? 1u : 0u) << e;
     }
-    if (lane == 0) lds_cnt[w * TPW + i] = total[i];
+    rank[i] = mine + below;
+    mine += total;
   }
+  if (lane == 0) lds_cnt[w] = mine;
   __syncthreads();
   int before = 0, all = 0;
 #pragma unroll
-  for (int k = 0; k < NW * TPW; ++k) {
+  for (int k = 0; k < NW; ++k) {
     const int c = lds_cnt[k];
-    before += (k < w * TPW) ? c : 0;
+    before += (k < w) ? c : 0;
     all += c;
   }
   __syncthreads();   // lds_cnt is reused
   if (count_only) return all;
-  int pos = base + before;
+  int32_t *row = stage + w * (TPW * TILE);
 #pragma unroll
   for (int i = 0; i < TPW; ++i) {
-    int p = pos + below[i];
     const int t0 = t_first + (w * TPW + i) * TILE + lane * TPL;
+    int p = rank[i];
 #pragma unroll
     for (int e = 0; e < TPL; ++e) {
-      if (mask[i] & (1u << e)) {
-        if (p < sel_stride) list[p] = t0 + e;
-        ++p;
-      }
+      if (mask[i] & (1u << e)) row[p++] = t0 + e;
     }
-    pos += total[i];
   }
+  const int out0 = base + before;
+  for (int j = lane; j < mine; j += IG_WAVE)
+    if (out0 + j < sel_stride) list[out0 + j] = row[j];
   return all;
 }
 
@@ -377,18 +376,16 @@ __device__ __forceinline__ void rescan_pair(const ScanArgs &a, int bh, float q_l
   }
 }
 
-template <int NW> struct StreamWindow { static constexpr int WIN = 16; };
-
-template <typename T, int R, int NW, int TPW, bool ROPE>
-__global__ __launch_bounds__(NW * 64) void scan_select_stream(ScanArgs a, int S, PairSync *sync, long spin_limit) {
+template <typename T, int R, int NW, int TPW, int WIN, int MINW>
+__global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, int S, PairSync *sync, long spin_limit) {
   constexpr int TPL = SlabElem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
-  constexpr int WIN = StreamWindow<NW>::WIN;
   constexpr int NLOAD = TPW * R;              // 1 KiB loads of a wave with all its tiles valid
   typedef typename SlabElem<T>::vec vec;
   __shared__ float lds_max[NW];
-  __shared__ int lds_cnt[NW * TPW];
+  __shared__ int lds_cnt[NW];
   __shared__ int lds_flag[2];
+  __shared__ int32_t stage[NW * TPW * TILE];
   __shared__ float lds_gmax;
   const int bh = blockIdx.x / S, s = blockIdx.x - bh * S;
   const int b = bh / a.H, h = bh - b * a.H;
@@ -406,8 +403,9 @@ __global__ __launch_bounds__(NW * 64) void scan_select_stream(ScanArgs a, int S,
   const int lane_off = lane * (int)sizeof(vec);
   constexpr int PLANE = TILE * (int)sizeof(T);            // bytes of one channel plane (1 KiB)
   vec v[WIN];
+  // the query's own loads go out first, so that they head the wave's memory queue
   QueryLoads ql;
-  if constexpr (!ROPE) query_issue(a, b, h, lane, 0, ql);
+  query_issue(a, b, h, lane, 0, ql);
   __builtin_amdgcn_sched_barrier(0);
   if (nact > 0) {
 #pragma unroll
@@ -415,14 +413,7 @@ __global__ __launch_bounds__(NW * 64) void scan_select_stream(ScanArgs a, int S,
       v[k] = *reinterpret_cast<const vec *>(tbase[k / R] + (k % R) * PLANE + lane_off);
   }
   __builtin_amdgcn_sched_barrier(0);
-  float q_lane;
-  if constexpr (ROPE) {
-    __shared__ float q_lds[512], qr_lds[512], psum[NW * 64], qp_lds[256];
-    rope_query<NW * 64>(a, b, h, q_lds, qr_lds, psum, qp_lds);
-    q_lane = lane < R ? qp_lds[lane] * a.scale : 0.f;
-  } else {
-    q_lane = query_finish(a, ql);
-  }
+  const float q_lane = query_finish(a, ql);
   float sc[TPW][TPL];
 #pragma unroll
   for (int i = 0; i < TPW; ++i)
@@ -461,7 +452,7 @@ __global__ __launch_bounds__(NW * 64) void scan_select_stream(ScanArgs a, int S,
   for (int k = 1; k < NW; ++k) mm = fmaxf(mm, lds_max[k]);
   int32_t *list = a.sel_idx + (long)bh * a.sel_stride;
   if (S == 1) {
-    const int all = compact_tiles<TPL, NW, TPW>(sc, mm - a.alpha, 0, list, a.sel_stride, 0, lds_cnt, w, lane, false);
+    const int all = compact_tiles<TPL, NW, TPW>(sc, mm - a.alpha, a.N, 0, list, a.sel_stride, 0, lds_cnt, stage, w, lane, false);
     if (threadIdx.x == 0) {
       a.sel_cnt[bh] = min(all, a.sel_stride);
       if (all > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
@@ -488,7 +479,7 @@ __global__ __launch_bounds__(NW * 64) void scan_select_stream(ScanArgs a, int S,
   const float gmax = slow ? pair_max<T, NW>(a, bh, q_lane, lds_max) : lds_gmax;
   const float thr = gmax - a.alpha;
   // ---- the pair's splits meet: counts ----
-  const int mine = compact_tiles<TPL, NW, TPW>(sc, thr, 0, list, a.sel_stride, 0, lds_cnt, w, lane, true);
+  const int mine = compact_tiles<TPL, NW, TPW>(sc, thr, a.N, 0, list, a.sel_stride, tile0 * TILE, lds_cnt, stage, w, lane, true);
   if (w == 0) {
     if (lane == 0)
       __hip_atomic_store(&ps->scnt[s], PUBLISHED | (unsigned)mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -508,7 +499,7 @@ __global__ __launch_bounds__(NW * 64) void scan_select_stream(ScanArgs a, int S,
   if (lds_flag[1]) {
     const int base = lds_cnt[0], all = lds_flag[0];
     __syncthreads();
-    compact_tiles<TPL, NW, TPW>(sc, thr, base, list, a.sel_stride, tile0 * TILE, lds_cnt, w, lane, false);
+    compact_tiles<TPL, NW, TPW>(sc, thr, a.N, base, list, a.sel_stride, tile0 * TILE, lds_cnt, stage, w, lane, false);
     if (s == S - 1 && threadIdx.x == 0) {
       a.sel_cnt[bh] = min(all, a.sel_stride);
       if (all > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
@@ -555,13 +546,8 @@ int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
   dim3 grid(BH), block(NW * 64);
 #define CASE(CHV)                                                              \
   case CHV: {                                                                  \
-    if (a.A_p) {                                                               \
-      auto k = scan_select_fused<T, CHV, NW, true>;                            \
-      IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                         \
-    } else {                                                                   \
-      auto k = scan_select_fused<T, CHV, NW, false>;                           \
-      IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                         \
-    }                                                                          \
+    auto k = scan_select_fused<T, CHV, NW>;                                    \
+    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                           \
     return IG_OK;                                                              \
   }
   // registers per wave shrink as the workgroup grows: 4 waves allow 40 loads in flight, 8 waves 24,
@@ -586,39 +572,34 @@ int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
   return ig_fail(ctx, IG_ESHAPE, "scan: unsupported channel block %d", ch);
 }
 
-// streaming form: (kept channels, waves per workgroup, tiles per wave) combinations that are built
-template <typename T, int R, int NW, int TPW>
+// streaming form: the (kept channels, tiles per wave) combinations that are built; 4 waves per
+// workgroup, 8 loads of 1 KiB in flight per wave (deeper windows measured the same), registers held
+// to 96 so that five workgroups share a compute unit (one tile or two per wave) or to 128 (four)
+template <typename T, int R, int NW, int TPW, int WIN, int MINW>
 int launch_stream_one(ig_ctx *ctx, const ScanArgs &a, int BH, int S, hipStream_t s) {
   dim3 grid((unsigned)(BH * S)), block(NW * 64);
   PairSync *sync = static_cast<PairSync *>(ctx->pair_sync);
-  if (a.A_p) {
-    auto k = scan_select_stream<T, R, NW, TPW, true>;
-    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, S, sync, ctx->spin_limit);
-  } else {
-    auto k = scan_select_stream<T, R, NW, TPW, false>;
-    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, S, sync, ctx->spin_limit);
-  }
+  auto k = scan_select_stream<T, R, NW, TPW, WIN, MINW>;
+  IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, S, sync, ctx->spin_limit);
   return IG_OK;
 }
 
 template <typename T, int R>
-int launch_stream_r(ig_ctx *ctx, const ScanArgs &a, int BH, int NW, int TPW, int S, hipStream_t s) {
-  if (NW == 4 && TPW == 1) return launch_stream_one<T, R, 4, 1>(ctx, a, BH, S, s);
-  if (NW == 4 && TPW == 2) return launch_stream_one<T, R, 4, 2>(ctx, a, BH, S, s);
-  if (NW == 4 && TPW == 4) return launch_stream_one<T, R, 4, 4>(ctx, a, BH, S, s);
-  if (NW == 8 && TPW == 1) return launch_stream_one<T, R, 8, 1>(ctx, a, BH, S, s);
-  if (NW == 8 && TPW == 2) return launch_stream_one<T, R, 8, 2>(ctx, a, BH, S, s);
-  return ig_fail(ctx, IG_ESHAPE, "scan: streaming form %d x %d is not built", NW, TPW);
+int launch_stream_r(ig_ctx *ctx, const ScanArgs &a, int BH, int TPW, int S, hipStream_t s) {
+  if (TPW == 1) return launch_stream_one<T, R, 4, 1, 8, 5>(ctx, a, BH, S, s);
+  if (TPW == 2) return launch_stream_one<T, R, 4, 2, 8, 5>(ctx, a, BH, S, s);
+  if (TPW == 4) return launch_stream_one<T, R, 4, 4, 8, 4>(ctx, a, BH, S, s);
+  return ig_fail(ctx, IG_ESHAPE, "scan: streaming form with %d tiles per wave is not built", TPW);
 }
 
-int launch_stream(ig_ctx *ctx, const ScanArgs &a, int BH, int NW, int TPW, int S, hipStream_t s) {
+int launch_stream(ig_ctx *ctx, const ScanArgs &a, int BH, int TPW, int S, hipStream_t s) {
   if (S < 1 || S > IG_SPLIT_MAX) return ig_fail(ctx, IG_ESHAPE, "scan: %d splits per pair", S);
   if (S > 1) {
     int rc = ig_ensure_zeroed(ctx, &ctx->pair_sync, &ctx->pair_sync_bytes, (size_t)BH * IG_PAIR_SYNC_BYTES);
     if (rc) return rc;
   }
-  if (a.r == 38) return launch_stream_r<half_t, 38>(ctx, a, BH, NW, TPW, S, s);
-  if (a.r == 25) return launch_stream_r<half_t, 25>(ctx, a, BH, NW, TPW, S, s);
+  if (a.r == 38) return launch_stream_r<half_t, 38>(ctx, a, BH, TPW, S, s);
+  if (a.r == 25) return launch_stream_r<half_t, 25>(ctx, a, BH, TPW, S, s);
   return ig_fail(ctx, IG_ESHAPE, "scan: streaming form is not built for r = %d", a.r);
 }
 
@@ -627,13 +608,8 @@ int launch_lds(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) {
   dim3 grid(BH), block(1024);
 #define CASE(CHV)                                                              \
   case CHV: {                                                                  \
-    if (a.A_p) {                                                               \
-      auto k = scan_select_lds<T, CHV, true>;                                  \
-      IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                         \
-    } else {                                                                   \
-      auto k = scan_select_lds<T, CHV, false>;                                 \
-      IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                         \
-    }                                                                          \
+    auto k = scan_select_lds<T, CHV>;                                          \
+    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a);                           \
     return IG_OK;                                                              \
   }
   switch (ch) {
@@ -674,6 +650,8 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
   const int nTiles = a.nValid;     // the work, not the capacity, picks the kernel
   // One workgroup per (b,h) when it fits and there are enough (b,h) pairs to fill the chip;
   // otherwise one wave per tile so that long sequences spread over all compute units.
+  int tpw = 0, S = 0;
+  if (ig_scan_stream_form(d, &tpw, &S)) return launch_stream(ctx, a, BH, tpw, S, s);
   const bool fused = ig_scan_is_fused(d);
   if (fused) {
     // When all workgroups fit on the chip at once (one round) a wave should have all its channels
@@ -702,6 +680,33 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
 }
 
 }  // namespace
+
+// The streaming form (rolling load window, one kernel, pairs split over workgroups when they are
+// long) takes half-precision slabs with the kept-channel counts it is built for, where it measured
+// faster than the forms below: sequences of 5 to 8 tiles with enough pairs to fill the chip (no
+// split), and every sequence beyond 16 tiles (8 tiles per workgroup, 16 when that would need more
+// than IG_SPLIT_MAX workgroups per pair; 4 when there are few pairs, to get more workgroups).
+bool ig_scan_stream_form(const ig_desc *d, int *tpw, int *S) {
+  if (d->dtype != IG_F16 || (d->r != 38 && d->r != 25)) return false;
+  const int tile = ig_tile_tokens(d->dtype);
+  const int nValid = (d->N + tile - 1) / tile;
+  const int BH = d->B * d->H;
+  if (nValid <= 4) return false;
+  if (nValid <= 8) {
+    if (BH < 128) return false;
+    *tpw = 2;
+    *S = 1;
+    return true;
+  }
+  if (nValid <= 16) return false;
+  int t = BH * ((nValid + 7) / 8) >= 512 ? 2 : 1;
+  if ((nValid + 4 * t - 1) / (4 * t) > IG_SPLIT_MAX) t = 2;
+  if ((nValid + 4 * t - 1) / (4 * t) > IG_SPLIT_MAX) t = 4;
+  if ((nValid + 4 * t - 1) / (4 * t) > IG_SPLIT_MAX) return false;
+  *tpw = t;
+  *S = (nValid + 4 * t - 1) / (4 * t);
+  return true;
+}
 
 // One workgroup per (b,h) and a single kernel when a pair fits 16 waves (scores stay in registers)
 // or 32768 tokens (scores parked in LDS) and there are enough pairs to fill the chip; otherwise
@@ -737,12 +742,6 @@ int ig_scan_args(ig_ctx *ctx, const ig_desc *d, const QSource &q, const void *sl
   a.sel_stride = sel_stride;
   a.scale = d->scale;
   a.alpha = d->alpha;
-  a.A_p = q.A_p;
-  a.pos = q.pos;
-  a.d = d->d;
-  a.theta = d->rope_theta;
-  if (q.A_p && !ig_scan_is_fused(d)) return ig_fail(ctx, IG_EINVAL, "scan: rotary query source needs the fused path");
-  if (q.A_p && d->d > 512) return ig_fail(ctx, IG_ESHAPE, "rope: d = %d exceeds 512", d->d);
   if (d->r > 256) return ig_fail(ctx, IG_ESHAPE, "r = %d exceeds 256", d->r);
   if (q.ks < 1 || q.ks > IG_KS_MAX) return ig_fail(ctx, IG_ESHAPE, "split-K %d out of range", q.ks);
   return IG_OK;

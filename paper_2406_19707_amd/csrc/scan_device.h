@@ -1,7 +1,7 @@
 // Device side of the partial key cache scan: argument block, the per-wave tile scan, the partial
-// query (split-K sums; rotary prologue), ordered compaction, and the body of the one-workgroup-per-
-// (b,h) kernel.  Shared by the scan kernels and by the kernel that runs a layer's scan next to the
-// previous layer's attention in one launch.
+// query (split-K sums), ordered compaction, and the body of the one-workgroup-per-(b,h) kernel.
+// Shared by the scan kernels and by the kernel that runs a layer's scan next to the previous
+// layer's attention in one launch.
 #ifndef IG_SCAN_DEVICE_H
 #define IG_SCAN_DEVICE_H
 #include "ig_internal.h"
@@ -23,12 +23,6 @@ struct ScanArgs {
   int nValid;   // tiles that hold valid tokens (from N): the only ones read
   int sel_stride;
   float scale, alpha;
-  // rotary models, fused path: the workgroup derives its partial query itself from the full
-  // projection's split-K partial sums (qsrc: [ks][b][D] columns), see rope_query()
-  const float *A_p;    // [H, d, r] kept columns of the skewing matrices, or NULL (not this mode)
-  const int32_t *pos;  // [B]
-  int d;
-  float theta;
 };
 
 namespace {
@@ -150,67 +144,6 @@ __device__ __forceinline__ void scan_tile_given_q(const ScanArgs &a, const T *ti
   }
 }
 
-// Partial query of a rotary model, computed by the whole workgroup (THREADS threads) into LDS
-// (Section 4.3 "Decoding Stage" for models whose skew cannot be folded into W_Q):
-//   q[c]   = bias[h*d+c] + sum_s part[s][b][h*d+c]            (split-K sums in a fixed order)
-//   rotate pairs (c, c+d/2) by pos[b]*theta^(-2c/d)            (angle in double)
-//   q_p[k] = sum_c q_rot[c] * A_p[h][c][k]                     (rows split over thread groups, added in order)
-// Same arithmetic as the stand-alone finalisation kernel; only the number of row groups differs.
-// q_lds, qr_lds: d floats each; psum: THREADS floats; result: qp_lds[k], k < r (unscaled).
-template <int THREADS>
-__device__ __forceinline__ void rope_query(const ScanArgs &a, int b, int h, float *q_lds, float *qr_lds,
-                                           float *psum, float *qp_lds) {
-  const int t = threadIdx.x, d = a.d, r = a.r;
-  for (int c = t; c < d; c += THREADS) {
-    const float *p = a.qsrc + (long)b * a.b_stride + (long)h * d + c;
-    float v[IG_KS_MAX];
-#pragma unroll
-    for (int s = 0; s < IG_KS_MAX; ++s) v[s] = (s < a.ks) ? p[(long)s * a.ks_stride] : 0.f;
-    float acc = a.bias ? a.bias[h * d + c] : 0.f;
-#pragma unroll
-    for (int s = 0; s < IG_KS_MAX; ++s) acc += v[s];
-    q_lds[c] = acc;
-  }
-  // the thread's rows of A_p do not depend on the query: they are put in flight now and travel
-  // while the rotation is worked out (up to PF rows per thread; longer runs are read in the loop)
-  const int RK = r <= 64 ? 64 : (r <= 128 ? 128 : 256);
-  const int G = THREADS / RK;
-  const int k = t % RK, g = t / RK;
-  const int per = (d + G - 1) / G;
-  const int c0 = min(d, g * per), c1 = min(d, (g + 1) * per);
-  constexpr int PF = THREADS >= 512 ? 8 : 16;
-  __builtin_amdgcn_sched_barrier(0);      // not before the partial sums above have been consumed
-  float apf[PF];
-  const float *ap = a.A_p + (long)h * d * r + min(k, r - 1);
-#pragma unroll
-  for (int i = 0; i < PF; ++i) apf[i] = (c0 + i < c1) ? ap[(long)(c0 + i) * r] : 0.f;
-  __syncthreads();
-  const int half = d / 2;
-  for (int c = t; c < half; c += THREADS) {
-    double sn, cs;
-    rope_sincos(rope_angle(a.pos[b], c, d, a.theta), &sn, &cs);
-    const float x0 = q_lds[c], x1 = q_lds[c + half];
-    qr_lds[c] = (float)((double)x0 * cs - (double)x1 * sn);
-    qr_lds[c + half] = (float)((double)x1 * cs + (double)x0 * sn);
-  }
-  __syncthreads();
-  float acc = 0.f;
-  if (k < r) {
-#pragma unroll
-    for (int i = 0; i < PF; ++i)
-      if (c0 + i < c1) acc = fmaf(qr_lds[c0 + i], apf[i], acc);
-    for (int c = c0 + PF; c < c1; ++c) acc = fmaf(qr_lds[c], ap[(long)c * r], acc);
-  }
-  psum[t] = acc;
-  __syncthreads();
-  if (t < r) {
-    float tot = 0.f;
-    for (int gg = 0; gg < G; ++gg) tot += psum[gg * RK + t];
-    qp_lds[t] = tot;
-  }
-  __syncthreads();
-}
-
 // A lane's TPL consecutive scores go out as 16-byte stores when the run is whole and aligned.
 template <int TPL>
 __device__ __forceinline__ void store_scores(float *dst /* score of token 0 of the head */, long head_off,
@@ -271,7 +204,7 @@ __device__ __forceinline__ int compact_block(const float (&sc)[TPL], int t0, int
 }
 
 // One workgroup per (b,h); wave w scans tile w (nValid <= NW) and keeps its scores in registers.
-template <typename T, int CH, int NW, bool ROPE>
+template <typename T, int CH, int NW>
 __device__ __forceinline__ void scan_select_fused_body(const ScanArgs &a, const int bh) {
   constexpr int TPL = SlabElem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
@@ -285,22 +218,7 @@ __device__ __forceinline__ void scan_select_fused_body(const ScanArgs &a, const 
   float acc[TPL];
 #pragma unroll
   for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
-  if constexpr (ROPE) {
-    // rotary model: the first channel block is put in flight, then all waves work out the
-    // partial query together while it travels
-    __shared__ float q_lds[512], qr_lds[512], psum[NW * 64], qp_lds[256];
-    typename SlabElem<T>::vec v[CH];
-    if (active) load_block<T, CH>(tile, a.r, 0, lane, v);
-    rope_query<NW * 64>(a, b, h, q_lds, qr_lds, psum, qp_lds);
-    if (active) {
-      float qv[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) qv[k] = (lane + 64 * k < a.r) ? qp_lds[lane + 64 * k] * a.scale : 0.f;
-      scan_tile_given_q<T, CH>(a, tile, lane, v, qv, acc);
-    }
-  } else if (active) {
-    scan_tile<T, CH>(a, tile, b, h, lane, acc);
-  }
+  if (active) scan_tile<T, CH>(a, tile, b, h, lane, acc);
   const int t0 = w * TILE;
   float m = -INFINITY;
 #pragma unroll
