@@ -274,6 +274,21 @@ int ig_sparse_attention(ig_ctx *ctx, const ig_desc *desc, const void *q, const v
                         const void *V_sel, const int32_t *sel_cnt, int32_t sel_stride,
                         const void *k_new, const void *v_new, void *out, void *stream);
 
+/* ig_sparse_attention for callers that cannot allocate device memory: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernel and
+ * the same result bit for bit, but the per-slice softmax states and arrival counters live in a
+ * static device array of the library (16 MiB on every GPU the library runs on, held until the
+ * process ends) instead of context workspaces, and the call makes no hipMalloc / hipFree or other
+ * allocating call, whatever the shape and whether or not ig_reserve was called.  Needs
+ * 256*ceil(B*H/64) + 64*B*H*(d+2) bytes of that array (B*H = 2000 heads of d = 128 fit); more
+ * returns IG_ECAPACITY and launches nothing.  The arrival counters are cleared by a small fill
+ * kernel on `stream` before the attention kernel.  All contexts on one GPU share the array: two
+ * calls of this entry point that overlap in time on one GPU (different streams or contexts) race;
+ * calls on one stream are safe. */
+int ig_sparse_attention_static(ig_ctx *ctx, const ig_desc *desc, const void *q, const void *K_sel,
+                               const void *V_sel, const int32_t *sel_cnt, int32_t sel_stride,
+                               const void *k_new, const void *v_new, void *out, void *stream);
+
 /* Same attention with the index lists applied to a device-resident pool directly (no K_sel /
  * V_sel copy): row j of (b,h) is Kpool[b,h,sel_idx[b,h,j],:]. */
 int ig_sparse_attention_indexed(ig_ctx *ctx, const ig_desc *desc, const void *q, const void *Kpool,

@@ -34,7 +34,7 @@ EXPORTS = [
     "ig_slab_build", "ig_append_token",
     "ig_pool_touch", "ig_pool_victim", "ig_pool_replace",
     "ig_speculate", "ig_project", "ig_scan_select", "ig_project_indexed", "ig_speculate_indexed",
-    "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention",
+    "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention", "ig_sparse_attention_static",
     "ig_sparse_attention_indexed", "ig_gather_attention", "ig_layer_step", "ig_set_wait_limit", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
     "ig_copy_bytes", "ig_read_bytes",
 ]
@@ -108,6 +108,7 @@ def lib():
             "ig_equalize_heads": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_double, _vp, _i32, _vp, _vp]),
             "ig_gather_kv": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_int, _vp, _i32, _vp, _vp, _vp, _vp]),
             "ig_sparse_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
+            "ig_sparse_attention_static": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
             "ig_sparse_attention_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
             "ig_gather_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
             "ig_set_wait_limit": (ctypes.c_int, [_vp, ctypes.c_int64]),
@@ -339,6 +340,12 @@ class Context:
         self._ck(lib().ig_sparse_attention(self._h, ctypes.byref(desc), _ptr(q), _ptr(K_sel),
                                            _ptr(V_sel), _ptr(sel_cnt), sel_stride, _ptr(k_new),
                                            _ptr(v_new), _ptr(out), _stream(stream)))
+
+    def ig_sparse_attention_static(self, desc, q, K_sel, V_sel, sel_cnt, sel_stride, k_new, v_new, out,
+                                   stream=None):
+        self._ck(lib().ig_sparse_attention_static(self._h, ctypes.byref(desc), _ptr(q), _ptr(K_sel),
+                                                  _ptr(V_sel), _ptr(sel_cnt), sel_stride, _ptr(k_new),
+                                                  _ptr(v_new), _ptr(out), _stream(stream)))
 
     def ig_sparse_attention_indexed(self, desc, q, Kpool, Vpool, sel_idx, sel_stride, sel_cnt,
                                     k_new, v_new, out, stream=None):

@@ -332,6 +332,11 @@ __device__ __forceinline__ void sparse_attention_body(const AttnArgs &A, const i
 }  // namespace
 
 // fills the attention argument block; grows the slice-state workspaces if needed
+// (ig_attn_fill: the same with the slice-state / counter memory given by the caller, no allocation)
+int ig_attn_fill(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, const void *V,
+                 const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt, int kv_rows,
+                 const void *k_new, const void *v_new, void *out, void *K_out, void *V_out,
+                 float *part, int32_t *counters, AttnArgs *A);
 int ig_attn_args(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, const void *V,
                  const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt, int kv_rows,
                  const void *k_new, const void *v_new, void *out, void *K_out, void *V_out, AttnArgs *A);

@@ -166,11 +166,19 @@ int ig_create(int device, ig_ctx **out) {
   ctx->attn_part_bytes = ctx->attn_cnt_bytes = 0;
   ctx->part_bytes = ctx->qp_bytes = ctx->scores_bytes = ctx->tmax_bytes = 0;
   ctx->status = nullptr;
+  ctx->static_scratch = nullptr;
+  ctx->static_scratch_bytes = 0;
   ctx->profiling = false;
   memset(ctx->prof_ms, 0, sizeof(ctx->prof_ms));
   memset(ctx->prof_n, 0, sizeof(ctx->prof_n));
   if (hipSetDevice(device) != hipSuccess || hipMalloc((void **)&ctx->status, 256) != hipSuccess ||
       hipMemset(ctx->status, 0, 256) != hipSuccess) {
+    delete ctx;
+    return IG_EHIP;
+  }
+  // address of the static scratch array on this device (the device is current here)
+  if (ig_static_scratch_bind(ctx) != IG_OK) {
+    (void)hipFree(ctx->status);
     delete ctx;
     return IG_EHIP;
   }
@@ -510,6 +518,20 @@ int ig_sparse_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
   if ((rc = set_device(ctx))) return rc;
   return ig_launch_attention(ctx, d, q, K_sel, V_sel, nullptr, sel_stride, sel_cnt, sel_stride, k_new,
                              v_new, out, nullptr, nullptr, (hipStream_t)stream);
+}
+
+int ig_sparse_attention_static(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K_sel,
+                               const void *V_sel, const int32_t *sel_cnt, int32_t sel_stride,
+                               const void *k_new, const void *v_new, void *out, void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (!q || !K_sel || !V_sel || !sel_cnt || !out)
+    return ig_fail(ctx, IG_EINVAL, "ig_sparse_attention_static: NULL argument");
+  if ((k_new == nullptr) != (v_new == nullptr)) return ig_fail(ctx, IG_EINVAL, "k_new and v_new go together");
+  if (sel_stride < 1) return ig_fail(ctx, IG_ESHAPE, "sel_stride = %d", sel_stride);
+  if ((rc = set_device(ctx))) return rc;
+  return ig_launch_attention_static(ctx, d, q, K_sel, V_sel, sel_stride, sel_cnt, k_new, v_new, out,
+                                    (hipStream_t)stream);
 }
 
 int ig_sparse_attention_indexed(ig_ctx *ctx, const ig_desc *d, const void *q, const void *Kpool,

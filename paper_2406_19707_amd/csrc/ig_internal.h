@@ -85,6 +85,8 @@ struct ig_ctx {
   long spin_limit;                           // scan: bound of a split's wait for its partners, 100 MHz ticks
   double *skew_ws;  size_t skew_ws_bytes;   // ig_skew_device: Gram matrices and eigenvectors [2][H][d][d]
   int32_t *status;                        // device status word (sticky flags)
+  void *static_scratch;                   // this device's address of the library's static scratch array
+  size_t static_scratch_bytes;            // (bound by ig_create; shared by every context on the device)
   bool profiling;
   std::vector<ProfRec> recs;
   std::vector<hipEvent_t> free_events;
@@ -176,6 +178,11 @@ int ig_launch_scan_attend(ig_ctx *ctx, const ig_desc *d, const QSource &qs, cons
                           const void *Kpool, const void *Vpool, const int32_t *sel_idx,
                           const int32_t *sel_cnt, int32_t sel_stride, const void *k_new,
                           const void *v_new, void *out, void *K_sel, void *V_sel, hipStream_t s);
+// attention whose slice states and arrival counters live in the static scratch array (no allocation)
+int ig_static_scratch_bind(ig_ctx *ctx);
+int ig_launch_attention_static(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, const void *V,
+                               int32_t sel_stride, const int32_t *sel_cnt, const void *k_new,
+                               const void *v_new, void *out, hipStream_t s);
 int ig_launch_copy(ig_ctx *ctx, const void *src, void *dst, size_t bytes, hipStream_t s);
 int ig_launch_read(ig_ctx *ctx, const void *src, size_t bytes, hipStream_t s);
 

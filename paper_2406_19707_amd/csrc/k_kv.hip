@@ -374,20 +374,15 @@ int ig_launch_gather(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const voi
   return ig_fail(ctx, IG_ESHAPE, "host gather: unsupported launch shape");
 }
 
-int ig_attn_args(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, const void *V,
+int ig_attn_fill(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, const void *V,
                  const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt, int kv_rows,
-                 const void *k_new, const void *v_new, void *out, void *K_out, void *V_out, AttnArgs *A) {
+                 const void *k_new, const void *v_new, void *out, void *K_out, void *V_out,
+                 float *part, int32_t *counters, AttnArgs *A) {
   const int row_bytes = d->d * ig_elem_bytes(d->dtype);
   const int LPR = row_bytes / 16;
   if (row_bytes % 16 || LPR < 1 || LPR > 64 || (LPR & (LPR - 1)))
     return ig_fail(ctx, IG_ESHAPE, "attention: row of %d bytes must be 16 * 2^k bytes, at most 1024",
                    row_bytes);
-  const int BH = d->B * d->H;
-  int rc = ig_ensure(ctx, (void **)&ctx->attn_part, &ctx->attn_part_bytes,
-                     (size_t)BH * SLICE_MAX * (d->d + 2) * sizeof(float));
-  if (rc) return rc;
-  if ((rc = ig_ensure_zeroed(ctx, (void **)&ctx->attn_cnt, &ctx->attn_cnt_bytes, (size_t)BH * sizeof(int32_t))))
-    return rc;
   A->q = q;
   A->K = (const uint4 *)K;
   A->V = (const uint4 *)V;
@@ -401,13 +396,26 @@ int ig_attn_args(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, co
   A->out = out;
   A->scale = d->scale;
   A->d = d->d;
-  A->part = ctx->attn_part;
-  A->counters = ctx->attn_cnt;
+  A->part = part;
+  A->counters = counters;
   A->H = d->H;
-  A->BH = BH;
+  A->BH = d->B * d->H;
   A->K_out = sel_idx ? (uint4 *)K_out : nullptr;
   A->V_out = sel_idx ? (uint4 *)V_out : nullptr;
   return IG_OK;
+}
+
+int ig_attn_args(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, const void *V,
+                 const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt, int kv_rows,
+                 const void *k_new, const void *v_new, void *out, void *K_out, void *V_out, AttnArgs *A) {
+  const int BH = d->B * d->H;
+  int rc = ig_ensure(ctx, (void **)&ctx->attn_part, &ctx->attn_part_bytes,
+                     (size_t)BH * SLICE_MAX * (d->d + 2) * sizeof(float));
+  if (rc) return rc;
+  if ((rc = ig_ensure_zeroed(ctx, (void **)&ctx->attn_cnt, &ctx->attn_cnt_bytes, (size_t)BH * sizeof(int32_t))))
+    return rc;
+  return ig_attn_fill(ctx, d, q, K, V, sel_idx, sel_stride, sel_cnt, kv_rows, k_new, v_new, out, K_out,
+                      V_out, ctx->attn_part, ctx->attn_cnt, A);
 }
 
 int ig_launch_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, const void *V,
@@ -436,6 +444,69 @@ int ig_launch_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
       IG_LAUNCH(ctx, IG_K_ATTENTION, k, grid, block, s, A);
     }
   }
+  return IG_OK;
+}
+
+// ---- attention without any allocation -----------------------------------------------------------
+// For callers that cannot allocate (stream capture, serving loops, harnesses that forbid it): the
+// per-slice softmax states and the per-(b,h) arrival counters of the attention kernel live in a
+// file-scope device array instead of context workspaces.  Every GPU the library runs on holds its
+// own copy of the array, at its own address, until the process ends; the address is looked up
+// once per context (ig_create, with the context's device current) and host code only ever uses
+// that address, never the array's name.  Layout: counters int32 [B*H] (padded to 256 bytes), then
+// states float [B*H][SLICE_MAX][d+2].
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+namespace {
+__global__ __launch_bounds__(256) void zero_words(int32_t *p, int n) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
+}  // namespace
+
+int ig_static_scratch_bind(ig_ctx *ctx) {
+  void *ptr = nullptr;
+  hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+  if (e != hipSuccess || !ptr) {
+    ctx->static_scratch = nullptr;
+    ctx->static_scratch_bytes = 0;
+    return ig_hip_fail(ctx, e, "hipGetSymbolAddress(scratch)");
+  }
+  ctx->static_scratch = ptr;
+  ctx->static_scratch_bytes = STATIC_SCRATCH_BYTES;
+  return IG_OK;
+}
+
+int ig_launch_attention_static(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K, const void *V,
+                               int32_t sel_stride, const int32_t *sel_cnt, const void *k_new,
+                               const void *v_new, void *out, hipStream_t s) {
+  if (!ctx->static_scratch) return ig_fail(ctx, IG_EHIP, "the static scratch array was not bound on this device");
+  const size_t BH = (size_t)d->B * d->H;
+  const size_t cnt_bytes = (BH * sizeof(int32_t) + 255) / 256 * 256;
+  const size_t need = cnt_bytes + BH * SLICE_MAX * ((size_t)d->d + 2) * sizeof(float);
+  if (need > ctx->static_scratch_bytes)
+    return ig_fail(ctx, IG_ECAPACITY,
+                   "ig_sparse_attention_static: B*H = %zu heads of d = %d need %zu bytes of slice states, "
+                   "the static scratch array holds %zu", BH, d->d, need, ctx->static_scratch_bytes);
+  int32_t *counters = reinterpret_cast<int32_t *>(ctx->static_scratch);
+  float *part = reinterpret_cast<float *>(static_cast<unsigned char *>(ctx->static_scratch) + cnt_bytes);
+  AttnArgs A;
+  int rc = ig_attn_fill(ctx, d, q, K, V, nullptr, sel_stride, sel_cnt, sel_stride, k_new, v_new, out,
+                        nullptr, nullptr, part, counters, &A);
+  if (rc) return rc;
+  // The array keeps whatever the last call left (a call that was cut short leaves counters
+  // behind): the arrival counters start from zero on every call.  A fill kernel, not a memset, so
+  // that the sequence can be captured into a graph.
+  hipLaunchKernelGGL(zero_words, dim3((unsigned)((BH + 255) / 256)), dim3(256), 0, s, counters, (int)BH);
+  dim3 grid((unsigned)(BH * SLICE_MAX)), block(256);
+  if (d->dtype == IG_F16) {
+    hipLaunchKernelGGL((sparse_attention<half_t, false>), grid, block, 0, s, A);
+  } else {
+    hipLaunchKernelGGL((sparse_attention<float, false>), grid, block, 0, s, A);
+  }
+  hipError_t le = hipGetLastError();
+  if (le != hipSuccess) return ig_hip_fail(ctx, le, "sparse_attention (static scratch)");
   return IG_OK;
 }
 
