@@ -3,20 +3,26 @@
 
 A step is one decode step: for each of the model's L layers, the rehearsal (ig_speculate), the
 prefetch of the selected rows and the attention over them, on that layer's own slab / KV pool
-(distinct memory per layer, so the 256 MB last-level cache cannot serve the scan).  The step is
-timed as issued eagerly call by call (ig_speculate, ig_gather_kv, ig_sparse_attention) and as HIP
-graph replays of that sequence, of the sequence with prefetch and attention in one pass
-(ig_gather_attention), and of the latter with the next layer's rehearsal on a side stream; `value`
-is the fastest of these in microseconds per layer per decode step, with all inputs resident in HBM
-(host-pool workloads: the KV pool in pinned host memory, the two-stream pipeline).  The roofline object prices the partial-K scan kernel against the HBM
-peak from its algorithmic bytes 2*B*H*N*r and its average duration, taken from HIP events attached
-to each launch.  The cpu_baseline object is the CPU oracle timed on one layer.
+(distinct memory per layer, so the 256 MB last-level cache cannot serve the scan).  `value` is
+microseconds per layer per decode step of the fastest launch sequence with all inputs resident in
+HBM (host-pool workloads: the KV pool in pinned host memory by definition of the workload, the
+two-stream pipeline).  The `roofline` object prices the partial-K scan kernel against the HBM peak
+from its algorithmic bytes 2*B*H*N*r and its average duration, taken from HIP events attached to
+each launch; `roofline_value_path` does the same for the dominant kernel of the sequence `value`
+was measured on.  `cpu_baseline` is the CPU oracle timed on the host.
+
+Without --workload the headline is the largest workload (cfg 5: long context, host KV pool) and
+the same figures for cfg 2, 3 and 4 are carried in `workloads`; every workload runs in a child
+process of its own (`bench.py --workload N`), so memory is returned in between and one failing
+workload cannot take the others' figures with it.
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import re
+import subprocess
 import sys
 import time
 
@@ -25,36 +31,36 @@ sys.path.insert(0, ROOT)
 sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per scan launch from rocprofv3 FETCH_SIZE + WRITE_SIZE, each scaled by what the counter
-# reads for a plain 256 MiB copy (profiles/cfgN_hbm_traffic_counters.txt); None = not collected.
-SCAN_TRAFFIC_BYTES = {2: 41.19e6, 3: 162.66e6, 4: 179.69e6, 5: 264.01e6}
+METRIC = "rehearsal+sparse-attn us/layer/decode step; partial-K scan GB/s vs HBM peak"
+HEADLINE, OTHERS = 5, (2, 3, 4)
 
 
 def log(*a):
     print("[bench]", *a, file=sys.stderr, flush=True)
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", type=int, default=2, help="index into the documented workloads (2..5)")
-    ap.add_argument("--layers", type=int, default=0, help="layers per step (0 = the model's)")
-    ap.add_argument("--gain", type=float, default=0.0, help="logit gain (0 = the workload's calibrated one)")
-    ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-literal", action="store_true", help="skip the gain-1 (select everything) variant")
-    ap.add_argument("--no-decode-loop", action="store_true", help="skip the growing-cache decode loop")
-    ap.add_argument("--copy-reference", action="store_true",
-                    help="also launch a plain 256 MiB device copy (reference for scaling hardware counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (--gpus 1); the path would shard over "
-              "(sequence, head) pairs without communication, but no multi-GPU run is part of it",
-              file=sys.stderr)
-        sys.exit(2)
+def scan_traffic_from_profile(cfg: int):
+    """HBM bytes per scan launch as the committed rocprofv3 counter summary of this workload states
+    them (FETCH_SIZE + WRITE_SIZE, scaled by a plain copy of known size); None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"cfg{cfg}_hbm_traffic_counters.txt")
+    try:
+        m = re.search(r"=\s*([0-9.]+) MB of HBM traffic per launch", open(path).read())
+    except OSError:
+        return None, None
+    return (float(m.group(1)) * 1e6, os.path.relpath(path, ROOT)) if m else (None, None)
 
+
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def run_workload(args) -> dict:
     import numpy as np
     import torch
     import ig_workloads as wl
@@ -70,6 +76,7 @@ def main():
                   log=lambda *a: log(*a, f"({time.time() - t0:.1f}s)"))
     L = R.L
     K, W = args.steps, args.warmup
+    brief = args.brief
 
     def timed(fn, steps):
         torch.cuda.synchronize()
@@ -81,6 +88,7 @@ def main():
 
     # ---- eager ----
     pcie = None
+    one_stream_ms = None
     if R.host_pool:
         # host pool: PCIe ceiling from a plain pinned -> device copy, then the side-stream pipeline
         src = torch.empty(1 << 30, dtype=torch.uint8, pin_memory=True)
@@ -121,24 +129,23 @@ def main():
         one_stream_ms = timed(R.step, K)
         pcie["one_stream_us_per_layer"] = one_stream_ms * 1e3 / L
         log("pcie", pcie)
-        args.no_graph = True
     else:
         for _ in range(W):
             R.step()
         assert ctx.ig_check_status() == ig.IG_OK
         eager_ms = timed(R.step, K)
-    cnt = R.sel_cnt.cpu().numpy()            # last layer of the step
     log(f"eager {eager_ms:.3f} ms/step = {eager_ms * 1e3 / L:.2f} us/layer")
 
     # ---- HIP graphs of the whole step (HBM pools): the four calls in sequence; prefetch and
     # attention in one pass; and that with the rehearsal of the next layer on a side stream ----
     variants = {}
     launch = "eager, two streams" if R.host_pool else "eager"
+    value_path = "overlapped" if R.host_pool else "step"
     ms_per_step = eager_ms
     if R.host_pool and one_stream_ms < ms_per_step:
-        ms_per_step, launch = one_stream_ms, "eager, one stream"
+        ms_per_step, launch, value_path = one_stream_ms, "eager, one stream", "step"
 
-    if not args.no_graph:
+    if not args.no_graph and not R.host_pool:
         def graphed(fn):
             g = torch.cuda.CUDAGraph()
             s = torch.cuda.Stream()
@@ -154,12 +161,12 @@ def main():
         R.step()
         torch.cuda.synchronize()
         out_ref = R.out.clone()
-        for name, fn in (("speculate, gather, attention", R.step),
-                         ("speculate, gather+attention in one pass", R.step_one_pass),
-                         ("rehearsal of the next layer on a side stream, gather+attention in one pass",
-                          R.step_two_stream),
-                         ("projection, then the next layer's scan and this layer's gather+attention in one launch",
-                          R.step_joint)):
+        for name, fn, path in (("speculate, gather, attention", R.step, "step"),
+                               ("speculate, gather+attention in one pass", R.step_one_pass, "one_pass"),
+                               ("rehearsal of the next layer on a side stream, gather+attention in one pass",
+                                R.step_two_stream, "one_pass"),
+                               ("projection, then the next layer's scan and this layer's gather+attention in one launch",
+                                R.step_joint, "joint")):
             try:
                 g = graphed(fn)
                 for _ in range(W):
@@ -176,14 +183,13 @@ def main():
                 variants[name] = ms * 1e3 / L
                 log(f"graph [{name}] {ms:.3f} ms/step = {ms * 1e3 / L:.2f} us/layer")
                 if ms < ms_per_step:
-                    ms_per_step, launch = ms, "hip graph replay: " + name
+                    ms_per_step, launch, value_path = ms, "hip graph replay: " + name, path
             except Exception as e:   # noqa: BLE001 -- report and keep the eager number
                 log(f"graph [{name}] unavailable:", repr(e))
-    graph_ms = variants.get("speculate, gather, attention")
 
     # ---- fused-attention variant (no K_sel / V_sel copy), eager ----
     fused_ms = None
-    if not R.host_pool:
+    if not R.host_pool and not brief:
         for _ in range(W):
             R.step_fused_attention()
         fused_ms = timed(R.step_fused_attention, K)
@@ -213,19 +219,20 @@ def main():
         return out
 
     kernels_overlapped = None
+    pk = max(1, min(K, 8))
     if R.host_pool:
         # each stream's kernels on their own (the roofline figures), then the overlapped pipeline
         def gather_only():
             with torch.cuda.stream(R.side):
                 R.step_gather_only()
-        kernels = profiled([R.step_without_gather, gather_only], max(1, K // 2))
-        kernels_overlapped = profiled([R.step_overlapped], max(1, K // 2))
+        kernels = profiled([R.step_without_gather, gather_only], max(1, pk // 2))
+        kernels_overlapped = profiled([R.step_overlapped], max(1, pk // 2))
     else:
-        kernels = profiled([R.step], K)
-        one = profiled([R.step_one_pass], K)
+        kernels = profiled([R.step], pk)
+        one = profiled([R.step_one_pass], pk)
         kernels["gather+attention in one pass"] = one["attention"]
         names[ig.IG_K_LAYER] = "joint"
-        joint = profiled([R.step_joint], K)
+        joint = profiled([R.step_joint], pk)
         if "joint" in joint:
             kernels["next layer's scan + this layer's gather+attention in one launch"] = joint["joint"]
         del names[ig.IG_K_LAYER]
@@ -261,7 +268,7 @@ def main():
 
     # ---- head-equalised variant (every head of a sequence fetches the mean count, 20 % cap) ----
     equalized = None
-    if not R.host_pool:
+    if not R.host_pool and not brief:
         R._use(0)
         for _ in range(2):
             R.step_equalized()
@@ -275,11 +282,11 @@ def main():
 
     # ---- index-only partial weight (columns read out of the full weight at run time) ----
     index_only = None
-    if not w.rope:
+    if not w.rope and not brief:
         R._use(0)
         R.speculate(L - 1)
         torch.cuda.synchronize()
-        blob_idx, blob_cnt = R.sel_idx.clone(), R.sel_cnt.clone()
+        blob_cnt = R.sel_cnt.clone()
         for _ in range(2):
             R.step_index_only()
         torch.cuda.synchronize()
@@ -297,11 +304,10 @@ def main():
                       "project_GBps": D_ * D_ * eb / (ki["project"]["avg_us"] * 1e-6) / 1e9,
                       "blob_bytes_saved_MB": R.wq.numel() / 1e6,
                       "lists_with_other_count_than_stored_blob_last_layer": differing}
-        del blob_idx
 
     # ---- decode loop with a growing cache: append of the decoded token after every layer ----
     decode_loop = None
-    if not args.no_decode_loop:
+    if not args.no_decode_loop and not brief:
         T, L2 = 8, min(L, 8)
         R2 = Rehearsal(ig.Context(0), w, gain=args.gain or None, layers=L2, host_layers=2,
                        extra_tokens=T, offline_from=R)
@@ -321,7 +327,7 @@ def main():
 
     # ---- literal variant (gain 1: every token selected), eager, a few steps ----
     literal = None
-    if R.gain != 1.0 and not args.no_literal and not R.host_pool:
+    if R.gain != 1.0 and not args.no_literal and not R.host_pool and not brief:
         scale = R.desc.scale
         R.desc.scale = 1.0 / (w.d ** 0.5)
         for _ in range(2):
@@ -332,20 +338,29 @@ def main():
         R.desc.scale = scale
 
     # ---- CPU oracle on layer 0 (one layer, whole batch), and parity of the GPU result ----
-    cpu = None
+    cpu = cpu_all = None
     parity = None
     if not args.no_cpu_baseline:
+        from concurrent.futures import ThreadPoolExecutor
         from oracle import ig_oracle as o
         h0 = R.layer0_host
         f32 = lambda a: np.ascontiguousarray(a, dtype=np.float32)   # noqa: E731
         x, Kt, V, q = f32(h0["x"]), f32(h0["K"]), f32(h0["V"]), f32(h0["q"])
         Wf = f32(R.W_host)
-        def oracle_layer(x, Kt, V, q):
+        posv = np.full(w.B, w.N, np.int32)
+
+        def oracle_layer(x, Kt, V, q, heads=None, pos=posv):
+            """One layer on the rows of x given; heads: (h0, h1) restricts scan ... attention to
+            those heads (the projection is that of all heads, cut afterwards)."""
             if w.rope:
-                q_p = o.project_rope(x, Wf, np.full(w.B, w.N, np.int32), R.A, R.idx_host)
+                q_p = o.project_rope(x, Wf, pos, R.A, R.idx_host)
             else:
                 q_p = o.project(x, Wf, R.idx_host)
-            s = o.scan(q_p, Kt, R.idx_host, R.desc.scale)
+            idx_h = R.idx_host
+            if heads is not None:
+                q_p = np.ascontiguousarray(q_p[:, heads[0]:heads[1]])
+                idx_h = np.ascontiguousarray(R.idx_host[heads[0]:heads[1]])
+            s = o.scan(q_p, Kt, idx_h, R.desc.scale)
             sel_idx, sel_cnt = o.select(s, w.alpha)
             m = int(sel_cnt.max())
             sel_small = np.ascontiguousarray(sel_idx[:, :m])
@@ -370,6 +385,27 @@ def main():
         cpu = {"value": cpu_s * 1e6 / n_cpu, "unit": "us/layer/decode step", "cores": 1, "kind": "oracle",
                "sample": f"{n_cpu} of {L} layers of one decode step, whole batch (project+scan+select+gather+"
                          f"attend, single thread, {cpu_s:.1f} s in total)"}
+        # the same oracle, untouched, on all host cores this job may use: layer 0 cut into
+        # (sequence, head group) slices that a thread pool runs side by side (the C calls release
+        # the interpreter lock); the slices' results are not used, only timed
+        nthreads = max(1, min(16, os.cpu_count() or 1))
+        hg = max(1, w.H // max(1, (2 * nthreads + w.B - 1) // w.B))
+        tasks = [(b, h_, min(w.H, h_ + hg)) for b in range(w.B) for h_ in range(0, w.H, hg)]
+
+        def slice_task(tk):
+            b, ha, hb = tk
+            oracle_layer(x[b:b + 1], np.ascontiguousarray(Kt[b:b + 1, ha:hb]),
+                         np.ascontiguousarray(V[b:b + 1, ha:hb]), np.ascontiguousarray(q[b:b + 1, ha:hb]),
+                         heads=(ha, hb), pos=posv[b:b + 1])
+        t = time.perf_counter()
+        with ThreadPoolExecutor(nthreads) as ex:
+            list(ex.map(slice_task, tasks))
+        par_s = time.perf_counter() - t
+        cpu_all = {"value": par_s * 1e6, "unit": "us/layer/decode step", "cores": nthreads,
+                   "kind": "oracle, one layer cut into (sequence, head group) slices on a thread pool",
+                   "nproc": os.cpu_count(), "cpu_model": cpu_model(),
+                   "sample": f"layer 0 of one decode step, {len(tasks)} slices of {hg} heads, {par_s:.2f} s; every "
+                             "slice repeats the layer's projection for its sequence"}
         # GPU result for the same layer
         R._use(0)
         R.layer(0)
@@ -388,7 +424,7 @@ def main():
                 and np.array_equal(g_idx[i, :g_cnt[i]], sel_idx[i, :sel_cnt[i]])]
         err = np.abs(g_out[same] - out[same])
         ok = bool(np.all(err <= 2e-2 + 1e-2 * np.abs(out[same])))
-        parity = {"layer": 0, "tokens_differing_outside_1e-3_band": outside,
+        parity = {"layer": 0, "pairs": w.B * w.H, "tokens_differing_outside_1e-3_band": outside,
                   "tokens_differing_inside_band": differing - outside,
                   "attention_max_abs_err": float(err.max()) if len(same) else None,
                   "attention_within_2e-2_abs_1e-2_rel": ok}
@@ -397,17 +433,32 @@ def main():
     # algorithmic bytes per launch of every kernel (layer average) and the rate they imply
     esz = 4 if w.dtype == "f32" else 2
     row_bytes = float(np.mean(fr)) * w.N * w.B * w.H * w.d * esz * 2          # K and V rows of a layer
+    joint_name = "next layer's scan + this layer's gather+attention in one launch"
     kbytes = {"project": ig.ig_wq_bytes(R.desc), "scan": scan_bytes, "gather": 2 * row_bytes,
               "attention": row_bytes, "gather+attention in one pass": 2 * row_bytes,
-              "next layer's scan + this layer's gather+attention in one launch": scan_bytes + 2 * row_bytes}
+              joint_name: scan_bytes + 2 * row_bytes}
     if R.host_pool:
         kbytes["gather"] = row_bytes                                          # over PCIe; the HBM write is extra
     for name, kb in kbytes.items():
         if name in kernels:
             kernels[name]["algorithmic_MB"] = kb / 1e6
             kernels[name]["GBps"] = kb / (kernels[name]["avg_us"] * 1e-6) / 1e9
+            if not (R.host_pool and name == "gather"):
+                kernels[name]["frac_of_hbm_peak"] = kernels[name]["GBps"] / HBM_PEAK_GBS
+    # the dominant kernel of the launch sequence `value` was measured on
+    if R.host_pool and value_path == "overlapped":
+        vp = {"kernel": "K/V row gather from the pinned host pool (side stream)", "bound": "pcie",
+              "achieved": pcie["gather_GBps"], "peak": pcie["h2d_memcpy_GBps"], "unit": "GB/s",
+              "frac": pcie["frac_of_memcpy"], "peak_is": "pinned->device hipMemcpyAsync rate measured in this run",
+              "algorithmic_bytes_per_launch": row_bytes, "avg_kernel_us": kernels["gather"]["avg_us"]}
+    else:
+        dom = joint_name if (value_path == "joint" and joint_name in kernels) else "scan"
+        vp = {"kernel": dom, "bound": "hbm", "achieved": kernels[dom]["GBps"], "peak": HBM_PEAK_GBS,
+              "unit": "GB/s", "frac": kernels[dom]["GBps"] / HBM_PEAK_GBS,
+              "algorithmic_bytes_per_launch": kbytes[dom], "avg_kernel_us": kernels[dom]["avg_us"]}
+    traffic, traffic_src = scan_traffic_from_profile(args.workload)
     res = {
-        "metric": "rehearsal+sparse-attn us/layer/decode step; partial-K scan GB/s vs HBM peak",
+        "metric": METRIC,
         "value": ms_per_step * 1e3 / L,
         "unit": "us/layer/decode step",
         "n_gpus": 1, "steps": K, "warmup": W,
@@ -436,15 +487,91 @@ def main():
         "decode_loop_growing_cache": decode_loop,
         "roofline": {"kernel": "partial-K scan + max + threshold + compaction", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": SCAN_TRAFFIC_BYTES.get(args.workload),
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "traffic_source": traffic_src and f"{traffic_src} (rocprofv3 FETCH_SIZE + WRITE_SIZE of an "
+                                                      "earlier run of this workload, not collected in this run)",
                      "algorithmic_bytes_per_launch": scan_bytes, "avg_kernel_us": scan_us,
+                     "target_frac": 0.70, "target_met": bool(achieved / HBM_PEAK_GBS >= 0.70),
                      "plain_read_same_size": {"GBps": read_gbs, "avg_kernel_us": read_us,
                                               "scan_over_plain_read": read_us / scan_us}},
+        "roofline_value_path": vp,
         "pcie": pcie,
         "cpu_baseline": cpu,
+        "cpu_baseline_all_cores": cpu_all,
         "parity": parity,
     }
-    print(json.dumps(res))
+    return res
+
+
+def child_flags(args, cfg):
+    f = ["--workload", str(cfg), "--steps", str(args.steps), "--warmup", str(args.warmup)]
+    if cfg != HEADLINE:
+        f.append("--brief")
+    for flag in ("no_graph", "no_cpu_baseline", "no_literal", "no_decode_loop"):
+        if getattr(args, flag):
+            f.append("--" + flag.replace("_", "-"))
+    return f
+
+
+def run_child(args, cfg):
+    """One workload in a process of its own; returns its result dict or {"error": ...}."""
+    cmd = [sys.executable, os.path.abspath(__file__)] + child_flags(args, cfg)
+    log("workload", cfg, ":", " ".join(cmd[1:]))
+    t = time.time()
+    try:
+        p = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=None, text=True, timeout=args.child_timeout)
+    except subprocess.TimeoutExpired:
+        return {"error": f"bench.py --workload {cfg} exceeded {args.child_timeout} s"}
+    log(f"workload {cfg} done in {time.time() - t:.0f} s, exit code {p.returncode}")
+    lines = [ln for ln in p.stdout.strip().splitlines() if ln.startswith("{")]
+    if p.returncode != 0 or not lines:
+        return {"error": f"bench.py --workload {cfg} exited with code {p.returncode}"}
+    return json.loads(lines[-1])
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=0,
+                    help="one documented workload (2..5) in this process; 0 = cfg 5 as the headline with "
+                         "cfg 2, 3 and 4 under `workloads`, each in a child process")
+    ap.add_argument("--only-headline", action="store_true", help="with --workload 0: skip cfg 2, 3 and 4")
+    ap.add_argument("--brief", action="store_true",
+                    help="skip the side variants (literal, head-equalised, index-only, decode loop)")
+    ap.add_argument("--layers", type=int, default=0, help="layers per step (0 = the model's)")
+    ap.add_argument("--gain", type=float, default=0.0, help="logit gain (0 = the workload's calibrated one)")
+    ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-literal", action="store_true", help="skip the gain-1 (select everything) variant")
+    ap.add_argument("--no-decode-loop", action="store_true", help="skip the growing-cache decode loop")
+    ap.add_argument("--copy-reference", action="store_true",
+                    help="also launch a plain 256 MiB device copy (reference for scaling hardware counters)")
+    ap.add_argument("--child-timeout", type=int, default=420, help="seconds a workload's child process may take")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); the path would shard over "
+              "(sequence, head) pairs without communication, but no multi-GPU run is part of it",
+              file=sys.stderr)
+        sys.exit(2)
+    if args.workload:
+        print(json.dumps(run_workload(args)))
+        return
+    # this process never touches the GPU: every workload runs in a child of its own
+    head = run_child(args, HEADLINE)
+    if "error" in head:
+        log(head["error"])
+        sys.exit(1)
+    if not args.only_headline:
+        keep = ("value", "unit", "ms_per_step", "steps", "warmup", "dtype", "config", "eager_us_per_layer",
+                "graph_us_per_layer", "scan_GBps", "kernels", "kernels_while_overlapped", "roofline",
+                "roofline_value_path", "pcie", "parity", "cpu_baseline", "cpu_baseline_all_cores", "error")
+        head["workloads"] = {}
+        for cfg in OTHERS:
+            r = run_child(args, cfg)
+            head["workloads"][f"cfg{cfg}"] = {k: r[k] for k in keep if k in r}
+    print(json.dumps(head))
 
 
 if __name__ == "__main__":
