@@ -464,8 +464,14 @@ int ig_speculate(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, c
   ProjGeom g;
   hipStream_t s = (hipStream_t)stream;
   if ((rc = project_partials(ctx, d, x, wq, A_p, pos, &g, s))) return rc;
+  if (d->rope && ig_scan_takes_rope(d)) {
+    // rotary embedding and the partial skew sit between the projection and the scan: the scan's
+    // workgroups work them out themselves while their first slab loads are in flight
+    QSource q{ctx->part, g.KS, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias, A_p, pos};
+    return ig_launch_scan_select(ctx, d, q, slab, sel_idx, sel_stride, sel_cnt, scores_opt, s);
+  }
   if (d->rope) {
-    // rotary embedding and the partial skew sit between the projection and the scan
+    // other shapes: a small kernel of its own between the two
     if ((rc = ig_launch_finalize(ctx, d, g, ctx->part, bias, A_p, pos, ctx->qp, s))) return rc;
     QSource q{ctx->qp, 1, 0, (long)d->H * d->r, nullptr};
     return ig_launch_scan_select(ctx, d, q, slab, sel_idx, sel_stride, sel_cnt, scores_opt, s);
@@ -581,7 +587,10 @@ int ig_layer_step(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, 
   hipStream_t s = (hipStream_t)stream;
   if ((rc = project_partials(ctx, d, x, wq, A_p, pos, &g, s))) return rc;
   QSource qs{ctx->part, g.KS, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias};
-  if (d->rope) {
+  if (d->rope && ig_scan_takes_rope(d)) {
+    qs.A_p = A_p;
+    qs.pos = pos;
+  } else if (d->rope) {
     if ((rc = ig_launch_finalize(ctx, d, g, ctx->part, bias, A_p, pos, ctx->qp, s))) return rc;
     qs = QSource{ctx->qp, 1, 0, (long)d->H * d->r, nullptr};
   }

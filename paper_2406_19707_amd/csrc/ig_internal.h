@@ -142,8 +142,14 @@ struct QSource {
   long ks_stride;
   long b_stride;
   const float *bias;
+  // rotary models, shapes for which ig_scan_takes_rope(): qsrc holds the full projection's partial
+  // sums ([ks][b][D] columns) and the scan derives the partial query from them with A_p [H,d,r]
+  // and pos [B]
+  const float *A_p = nullptr;
+  const int32_t *pos = nullptr;
 };
 bool ig_scan_is_fused(const ig_desc *d);
+bool ig_scan_takes_rope(const ig_desc *d);
 bool ig_scan_stream_form(const ig_desc *d, int *tiles_per_wave, int *splits);
 int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const void *slab,
                           int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
@@ -208,10 +214,6 @@ __device__ __forceinline__ void rope_sincos(double ang, double *sn, double *cs) 
   *sn = q == 0 ? s : (q == 1 ? c : (q == 2 ? -s : -c));
   *cs = q == 0 ? c : (q == 1 ? -s : (q == 2 ? -c : s));
 }
-__device__ __forceinline__ double rope_angle(int pos, int c, int d, float theta) {
-  return (double)pos * exp2(-2.0 * (double)c / (double)d * log2((double)theta));
-}
-
 // ---- wave helpers -------------------------------------------------------------------------------
 // Cross-lane moves inside a 16-lane row through DPP (no LDS crossbar traffic).
 template <int CTRL> __device__ __forceinline__ float dpp_move(float v) {

@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256) void finalize_query(const float *__restrict__ 
                                                       const int32_t *__restrict__ pos,
                                                       float *__restrict__ q_p, int H, int d, int r,
                                                       int KS, long ks_stride, int Cpad, int rope,
-                                                      float theta) {
+                                                      double freq_step /* -(2/d) log2(theta) */) {
   __shared__ float q[512];
   __shared__ float qr[512];
   __shared__ float psum[256];
@@ -385,25 +385,33 @@ __global__ __launch_bounds__(256) void finalize_query(const float *__restrict__ 
   float v[2][IG_KS_MAX], bs[2];
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
-    const int c = min(t + 256 * u, d - 1);
-    const float *p = part + (long)b * Cpad + (long)h * d + c;
+    const int c = t + 256 * u;
 #pragma unroll
-    for (int s = 0; s < IG_KS_MAX; ++s) v[u][s] = (s < KS) ? p[s * ks_stride] : 0.f;
-    bs[u] = bias ? bias[h * d + c] : 0.f;
+    for (int s = 0; s < IG_KS_MAX; ++s) v[u][s] = 0.f;
+    bs[u] = 0.f;
+    if (c < d) {
+      const float *p = part + (long)b * Cpad + (long)h * d + c;
+#pragma unroll
+      for (int s = 0; s < IG_KS_MAX; ++s)
+        if (s < KS) v[u][s] = p[s * ks_stride];
+      if (bias) bs[u] = bias[h * d + c];
+    }
   }
   const int position = pos[b];
-  // q_p[k] = sum_c qr[c] * A_p[h][c][k]: the 256 threads are G groups of RK; group g sums its share
-  // of the rows c for output k (reads of A_p coalesce over k), then the groups are added in order
-  const int RK = r <= 64 ? 64 : (r <= 128 ? 128 : 256);
-  const int G = 256 / RK;
-  const int k = t % RK, g = t / RK;
+  // q_p[k] = sum_c qr[c] * A_p[h][c][k]: the threads are G groups of r; group g sums its share of
+  // the rows c for output k (reads of A_p coalesce over k), then the groups are added in order
+  const int G = 256 / r;                      // r <= 256
+  const int k = t % r, g = t / r;
   const int per = (d + G - 1) / G;
-  const int c0 = min(d, g * per), c1 = min(d, (g + 1) * per);
-  constexpr int PF = 32;
-  const float *ap = A_p + (long)h * d * r + min(k, r - 1);
+  const int c0 = g < G ? min(d, g * per) : d, c1 = g < G ? min(d, (g + 1) * per) : d;
+  constexpr int PF = 24;
+  const float *ap = A_p + (long)h * d * r + k;
   float apf[PF];
 #pragma unroll
-  for (int i = 0; i < PF; ++i) apf[i] = (c0 + i < c1) ? ap[(long)(c0 + i) * r] : 0.f;
+  for (int i = 0; i < PF; ++i) {
+    apf[i] = 0.f;
+    if (c0 + i < c1) apf[i] = ap[(long)(c0 + i) * r];
+  }
 #pragma unroll
   for (int u = 0; u < 2; ++u) {
     const int c = t + 256 * u;
@@ -416,24 +424,22 @@ __global__ __launch_bounds__(256) void finalize_query(const float *__restrict__ 
   const int half = d / 2;
   for (int c = t; c < half; c += 256) {
     double sn, cs;
-    rope_sincos(rope_angle(position, c, d, theta), &sn, &cs);
+    rope_sincos((double)position * exp2((double)c * freq_step), &sn, &cs);
     float a = q[c], bb = q[c + half];
     qr[c] = (float)((double)a * cs - (double)bb * sn);
     qr[c + half] = (float)((double)bb * cs + (double)a * sn);
   }
   __syncthreads();
   float acc = 0.f;
-  if (k < r) {
 #pragma unroll
-    for (int i = 0; i < PF; ++i)
-      if (c0 + i < c1) acc = fmaf(qr[c0 + i], apf[i], acc);
-    for (int c = c0 + PF; c < c1; ++c) acc = fmaf(qr[c], ap[(long)c * r], acc);
-  }
+  for (int i = 0; i < PF; ++i)
+    if (c0 + i < c1) acc = fmaf(qr[c0 + i], apf[i], acc);
+  for (int c = c0 + PF; c < c1; ++c) acc = fmaf(qr[c], ap[(long)c * r], acc);
   psum[t] = acc;
   __syncthreads();
   if (t < r) {
     float tot = 0.f;
-    for (int gg = 0; gg < G; ++gg) tot += psum[gg * RK + t];
+    for (int gg = 0; gg < G; ++gg) tot += psum[gg * r + t];
     q_p[(long)bh * r + t] = tot;
   }
 }
@@ -579,6 +585,6 @@ int ig_launch_finalize(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const f
   auto k = finalize_query;
   IG_LAUNCH(ctx, IG_K_FINALIZE, k, dim3(d->B * d->H), dim3(256), s, part, bias, A_p, pos, q_p,
             (int)d->H, (int)d->d, (int)d->r, g.KS, (long)g.Bpad * g.Cpad, g.Cpad, (int)d->rope,
-            (float)d->rope_theta);
+            d->rope ? -2.0 / (double)d->d * log2((double)d->rope_theta) : 0.0);
   return IG_OK;
 }

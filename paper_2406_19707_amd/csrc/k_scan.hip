@@ -376,8 +376,92 @@ __device__ __forceinline__ void rescan_pair(const ScanArgs &a, int bh, float q_l
   }
 }
 
-template <typename T, int R, int NW, int TPW, int WIN, int MINW>
-__global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, int S, PairSync *sync, long spin_limit) {
+// Partial query of a rotary model inside the streaming kernel (Section 4.3 "Decoding Stage" for
+// models whose skew cannot be folded into W_Q): qsrc holds the split-K partial sums of the FULL
+// projection x W_Q ([ks][b][D] columns) and the workgroup finishes its head itself --
+//   q[c]   = bias[h*d+c] + sum_s part[s][b][h*d+c]            (split-K sums in a fixed order)
+//   rotate pairs (c, c+d/2) by pos[b]*theta^(-2c/d)            (angle in double)
+//   q_p[k] = sum_c q_rot[c] * A_p[h][c][k]                     (rows split over thread groups, added in order)
+// -- the arithmetic of the stand-alone finalisation kernel.  Loads return to a wave in the order
+// it issued them, so everything the prologue reads (partial sums, position, the thread's rows of
+// A_p) is issued by rope_issue BEFORE the wave's slab window; rope_finish then runs while the window
+// is still travelling.  Heads of up to 256 columns, at most ROPE_PF rows of A_p per thread.
+constexpr int ROPE_PF = 24;
+struct RopeArgs {
+  const float *A_p;     // [H, d, r]
+  const int32_t *pos;   // [B]
+  int d;
+  double freq_step;     // -(2/d) log2(theta)
+};
+struct RopeLoads {
+  float part[IG_KS_MAX];
+  float bias;
+  float apf[ROPE_PF];
+  int position;
+};
+template <int THREADS>
+__device__ __forceinline__ void rope_issue(const ScanArgs &a, const RopeArgs &ra, int b, int h, RopeLoads &L) {
+  // straight-line code, every load unconditional (addresses clamped, surplus values discarded
+  // later): the compiler can then count exactly how many loads may still be outstanding at each
+  // use, instead of waiting for all of them -- the slab window included -- after a branch
+  const int t = threadIdx.x, d = ra.d, r = a.r;
+  const float *p = a.qsrc + (long)b * a.b_stride + (long)h * d + min(t, d - 1);
+#pragma unroll
+  for (int s = 0; s < IG_KS_MAX; ++s) L.part[s] = p[(long)min(s, a.ks - 1) * a.ks_stride];
+  L.bias = a.bias ? a.bias[h * d + min(t, d - 1)] : 0.f;
+  L.position = ra.pos[b];
+  const int G = THREADS / r, k = t % r, g = min(t / r, G - 1);
+  const int per = (d + G - 1) / G;
+  const int c0 = min(d, g * per);
+  const float *ap = ra.A_p + (long)h * d * r + k;
+#pragma unroll
+  for (int i = 0; i < ROPE_PF; ++i) L.apf[i] = ap[(long)min(c0 + i, d - 1) * r];
+}
+template <int THREADS>
+__device__ __forceinline__ void rope_finish(const ScanArgs &a, const RopeArgs &ra, const RopeLoads &L,
+                                            float *q_lds, float *qr_lds, float *psum, float *qp_lds) {
+  const int t = threadIdx.x, d = ra.d, r = a.r;
+  {
+    float acc = L.bias;
+#pragma unroll
+    for (int s = 0; s < IG_KS_MAX; ++s) acc += s < a.ks ? L.part[s] : 0.f;
+    if (t < d) q_lds[t] = acc;
+  }
+  __syncthreads();
+  const int half = d / 2;
+  if (t < half) {
+    double sn, cs;
+    rope_sincos((double)L.position * exp2((double)t * ra.freq_step), &sn, &cs);
+    const float x0 = q_lds[t], x1 = q_lds[t + half];
+    qr_lds[t] = (float)((double)x0 * cs - (double)x1 * sn);
+    qr_lds[t + half] = (float)((double)x1 * cs + (double)x0 * sn);
+  }
+  __syncthreads();
+  const int G = THREADS / r, g = t / r;
+  const int per = (d + G - 1) / G;
+  const int c0 = g < G ? min(d, g * per) : d, c1 = g < G ? min(d, (g + 1) * per) : d;
+  float acc = 0.f;
+#pragma unroll
+  for (int i = 0; i < ROPE_PF; ++i)
+    if (c0 + i < c1) acc = fmaf(qr_lds[c0 + i], L.apf[i], acc);
+  psum[t] = acc;
+  __syncthreads();
+  if (t < r) {
+    float tot = 0.f;
+    for (int gg = 0; gg < G; ++gg) tot += psum[gg * r + t];
+    qp_lds[t] = tot;
+  }
+  __syncthreads();
+}
+// shapes the in-kernel prologue takes: one column per thread, every thread's rows of A_p prefetched
+static inline bool rope_prologue_fits(int threads, int d, int r) {
+  if (d > threads || d > 256 || r > threads) return false;
+  const int G = threads / r;
+  return (d + G - 1) / G <= ROPE_PF;
+}
+
+template <typename T, int R, int NW, int TPW, int WIN, int MINW, bool ROPE>
+__global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, RopeArgs ra, int S, PairSync *sync, long spin_limit) {
   constexpr int TPL = SlabElem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
   constexpr int NLOAD = TPW * R;              // 1 KiB loads of a wave with all its tiles valid
@@ -393,27 +477,36 @@ __global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, 
   const int tile0 = s * (NW * TPW);                       // first tile of this workgroup
   const int my0 = tile0 + w * TPW;                        // first tile of this wave
   const int nact = max(0, min(TPW, a.nValid - my0));      // valid tiles of this wave (wave-uniform)
-  // a wave with fewer valid tiles re-reads its last valid one in their place (masked below), so the
-  // load sequence is the same for every wave that has work
+  // a wave with fewer valid tiles re-reads its last valid one in their place (masked below), and a
+  // wave with none the pair's last valid tile, so the load sequence is the same for every wave
   const char *tbase[TPW];
 #pragma unroll
   for (int i = 0; i < TPW; ++i)
     tbase[i] = reinterpret_cast<const char *>(static_cast<const T *>(a.slab) +
-                                              ((long)bh * a.nTiles + my0 + max(0, min(i, nact - 1))) * R * TILE);
+                                              ((long)bh * a.nTiles + min(my0 + max(0, min(i, nact - 1)), a.nValid - 1)) * R * TILE);
   const int lane_off = lane * (int)sizeof(vec);
   constexpr int PLANE = TILE * (int)sizeof(T);            // bytes of one channel plane (1 KiB)
   vec v[WIN];
   // the query's own loads go out first, so that they head the wave's memory queue
   QueryLoads ql;
-  query_issue(a, b, h, lane, 0, ql);
+  RopeLoads rl;
+  if constexpr (ROPE) rope_issue<NW * 64>(a, ra, b, h, rl);
+  else query_issue(a, b, h, lane, 0, ql);
   __builtin_amdgcn_sched_barrier(0);
-  if (nact > 0) {
+  // (unconditional, like the query's loads: a branch here would make the compiler wait for the
+  // whole window wherever the query is first used)
 #pragma unroll
-    for (int k = 0; k < WIN && k < NLOAD; ++k)
-      v[k] = *reinterpret_cast<const vec *>(tbase[k / R] + (k % R) * PLANE + lane_off);
-  }
+  for (int k = 0; k < WIN && k < NLOAD; ++k)
+    v[k] = *reinterpret_cast<const vec *>(tbase[k / R] + (k % R) * PLANE + lane_off);
   __builtin_amdgcn_sched_barrier(0);
-  const float q_lane = query_finish(a, ql);
+  float q_lane;
+  if constexpr (ROPE) {
+    __shared__ float q_lds[256], qr_lds[256], psum[NW * 64], qp_lds[64];
+    rope_finish<NW * 64>(a, ra, rl, q_lds, qr_lds, psum, qp_lds);
+    q_lane = lane < R ? qp_lds[lane] * a.scale : 0.f;
+  } else {
+    q_lane = query_finish(a, ql);
+  }
   float sc[TPW][TPL];
 #pragma unroll
   for (int i = 0; i < TPW; ++i)
@@ -576,30 +669,37 @@ int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
 // workgroup, 8 loads of 1 KiB in flight per wave (deeper windows measured the same), registers held
 // to 96 so that five workgroups share a compute unit (one tile or two per wave) or to 128 (four)
 template <typename T, int R, int NW, int TPW, int WIN, int MINW>
-int launch_stream_one(ig_ctx *ctx, const ScanArgs &a, int BH, int S, hipStream_t s) {
+int launch_stream_one(ig_ctx *ctx, const ScanArgs &a, const RopeArgs *ra, int BH, int S, hipStream_t s) {
   dim3 grid((unsigned)(BH * S)), block(NW * 64);
   PairSync *sync = static_cast<PairSync *>(ctx->pair_sync);
-  auto k = scan_select_stream<T, R, NW, TPW, WIN, MINW>;
-  IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, S, sync, ctx->spin_limit);
+  if (ra) {
+    auto k = scan_select_stream<T, R, NW, TPW, WIN, 4, true>;    // the prologue's loads need the registers
+    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, *ra, S, sync, ctx->spin_limit);
+  } else {
+    auto k = scan_select_stream<T, R, NW, TPW, WIN, MINW, false>;
+    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, RopeArgs{}, S, sync, ctx->spin_limit);
+  }
   return IG_OK;
 }
 
 template <typename T, int R>
-int launch_stream_r(ig_ctx *ctx, const ScanArgs &a, int BH, int TPW, int S, hipStream_t s) {
-  if (TPW == 1) return launch_stream_one<T, R, 4, 1, 8, 5>(ctx, a, BH, S, s);
-  if (TPW == 2) return launch_stream_one<T, R, 4, 2, 8, 5>(ctx, a, BH, S, s);
-  if (TPW == 4) return launch_stream_one<T, R, 4, 4, 8, 4>(ctx, a, BH, S, s);
+int launch_stream_r(ig_ctx *ctx, const ScanArgs &a, const RopeArgs *ra, int BH, int TPW, int S, hipStream_t s) {
+  if (TPW == 1) return launch_stream_one<T, R, 4, 1, 8, 5>(ctx, a, ra, BH, S, s);
+  if (TPW == 2) return launch_stream_one<T, R, 4, 2, 8, 5>(ctx, a, ra, BH, S, s);
+  if constexpr (R <= 32) {   // (with more channels the unrolled stream of 4 tiles no longer stays in registers)
+    if (TPW == 4) return launch_stream_one<T, R, 4, 4, 8, 4>(ctx, a, ra, BH, S, s);
+  }
   return ig_fail(ctx, IG_ESHAPE, "scan: streaming form with %d tiles per wave is not built", TPW);
 }
 
-int launch_stream(ig_ctx *ctx, const ScanArgs &a, int BH, int TPW, int S, hipStream_t s) {
+int launch_stream(ig_ctx *ctx, const ScanArgs &a, const RopeArgs *ra, int BH, int TPW, int S, hipStream_t s) {
   if (S < 1 || S > IG_SPLIT_MAX) return ig_fail(ctx, IG_ESHAPE, "scan: %d splits per pair", S);
   if (S > 1) {
     int rc = ig_ensure_zeroed(ctx, &ctx->pair_sync, &ctx->pair_sync_bytes, (size_t)BH * IG_PAIR_SYNC_BYTES);
     if (rc) return rc;
   }
-  if (a.r == 38) return launch_stream_r<half_t, 38>(ctx, a, BH, TPW, S, s);
-  if (a.r == 25) return launch_stream_r<half_t, 25>(ctx, a, BH, TPW, S, s);
+  if (a.r == 38) return launch_stream_r<half_t, 38>(ctx, a, ra, BH, TPW, S, s);
+  if (a.r == 25) return launch_stream_r<half_t, 25>(ctx, a, ra, BH, TPW, S, s);
   return ig_fail(ctx, IG_ESHAPE, "scan: streaming form is not built for r = %d", a.r);
 }
 
@@ -645,13 +745,18 @@ int launch_tiles(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
 }
 
 template <typename T>
-int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
+int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, const QSource *rope, hipStream_t s) {
   const int BH = d->B * d->H;
   const int nTiles = a.nValid;     // the work, not the capacity, picks the kernel
   // One workgroup per (b,h) when it fits and there are enough (b,h) pairs to fill the chip;
   // otherwise one wave per tile so that long sequences spread over all compute units.
   int tpw = 0, S = 0;
-  if (ig_scan_stream_form(d, &tpw, &S)) return launch_stream(ctx, a, BH, tpw, S, s);
+  if (ig_scan_stream_form(d, &tpw, &S)) {
+    if (!rope) return launch_stream(ctx, a, nullptr, BH, tpw, S, s);
+    RopeArgs ra{rope->A_p, rope->pos, d->d, -2.0 / (double)d->d * log2((double)d->rope_theta)};
+    return launch_stream(ctx, a, &ra, BH, tpw, S, s);
+  }
+  if (rope) return ig_fail(ctx, IG_EINVAL, "scan: a rotary query source needs the streaming form");
   const bool fused = ig_scan_is_fused(d);
   if (fused) {
     // When all workgroups fit on the chip at once (one round) a wave should have all its channels
@@ -683,15 +788,24 @@ int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, hipStream_t s) {
 
 // The streaming form (rolling load window, one kernel, pairs split over workgroups when they are
 // long) takes half-precision slabs with the kept-channel counts it is built for, where it measured
-// faster than the forms below: sequences of 5 to 8 tiles with enough pairs to fill the chip (no
+// faster than the forms below: sequences of up to 8 tiles with enough pairs to fill the chip (no
 // split), and every sequence beyond 16 tiles (8 tiles per workgroup, 16 when that would need more
-// than IG_SPLIT_MAX workgroups per pair; 4 when there are few pairs, to get more workgroups).
+// than IG_SPLIT_MAX workgroups per pair and r <= 32; 4 when there are few pairs, to get more
+// workgroups).
 bool ig_scan_stream_form(const ig_desc *d, int *tpw, int *S) {
   if (d->dtype != IG_F16 || (d->r != 38 && d->r != 25)) return false;
   const int tile = ig_tile_tokens(d->dtype);
   const int nValid = (d->N + tile - 1) / tile;
   const int BH = d->B * d->H;
-  if (nValid <= 4) return false;
+  if (nValid <= 4) {
+    // one tile per wave: about a tenth faster than the block-loading form up to a few hundred
+    // pairs (9.3 against 10.5 us on 256 pairs of 2048 tokens); with a thousand pairs and more the
+    // block-loading form with its fewer resident workgroups is ahead (31.8 against 32.8 us)
+    if (BH < 128 || BH > 512) return false;
+    *tpw = 1;
+    *S = 1;
+    return true;
+  }
   if (nValid <= 8) {
     if (BH < 128) return false;
     *tpw = 2;
@@ -702,10 +816,18 @@ bool ig_scan_stream_form(const ig_desc *d, int *tpw, int *S) {
   int t = BH * ((nValid + 7) / 8) >= 512 ? 2 : 1;
   if ((nValid + 4 * t - 1) / (4 * t) > IG_SPLIT_MAX) t = 2;
   if ((nValid + 4 * t - 1) / (4 * t) > IG_SPLIT_MAX) t = 4;
-  if ((nValid + 4 * t - 1) / (4 * t) > IG_SPLIT_MAX) return false;
+  if ((nValid + 4 * t - 1) / (4 * t) > IG_SPLIT_MAX || (t == 4 && d->r > 32)) return false;
   *tpw = t;
   *S = (nValid + 4 * t - 1) / (4 * t);
   return true;
+}
+
+// Shapes whose scan finishes a rotary model's partial query itself (from the full projection's
+// split-K sums) instead of reading it from the finalisation kernel: the streaming form, heads that
+// fit its prologue.
+bool ig_scan_takes_rope(const ig_desc *d) {
+  int tpw = 0, S = 0;
+  return d->rope && ig_scan_stream_form(d, &tpw, &S) && rope_prologue_fits(256, d->d, d->r);
 }
 
 // One workgroup per (b,h) and a single kernel when a pair fits 16 waves (scores stay in registers)
@@ -753,5 +875,7 @@ int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const
   ScanArgs a;
   int rc = ig_scan_args(ctx, d, q, slab, sel_idx, sel_stride, sel_cnt, scores_opt, &a);
   if (rc) return rc;
-  return d->dtype == IG_F16 ? launch_scan<half_t>(ctx, d, a, s) : launch_scan<float>(ctx, d, a, s);
+  const QSource *rope = q.A_p ? &q : nullptr;
+  if (rope && !ig_scan_takes_rope(d)) return ig_fail(ctx, IG_EINVAL, "scan: this shape takes no rotary query source");
+  return d->dtype == IG_F16 ? launch_scan<half_t>(ctx, d, a, rope, s) : launch_scan<float>(ctx, d, a, rope, s);
 }

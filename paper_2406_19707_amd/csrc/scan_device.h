@@ -37,25 +37,24 @@ namespace {
 struct QueryLoads {
   float part[IG_KS_MAX];   // split-K partial sums of channel `lane` (r <= 64 needs only these)
   float bias;
+  bool live;               // the lane's channel exists (lane + 64*k < r)
 };
 __device__ __forceinline__ void query_issue(const ScanArgs &a, int b, int h, int lane, int k, QueryLoads &ql) {
-  const int j = lane + 64 * k;
+  // straight-line code, every load unconditional (channel and split clamped, surplus values dropped
+  // in query_finish): the compiler then keeps exact counts of the loads outstanding, where a branch
+  // around a load makes it wait for everything issued so far
+  const int j = min(lane + 64 * k, a.r - 1);
+  const float *p = a.qsrc + (long)b * a.b_stride + (long)h * a.r + j;
 #pragma unroll
-  for (int s = 0; s < IG_KS_MAX; ++s) ql.part[s] = 0.f;
-  ql.bias = 0.f;
-  if (j < a.r) {
-    const float *p = a.qsrc + (long)b * a.b_stride + (long)h * a.r + j;
-#pragma unroll
-    for (int s = 0; s < IG_KS_MAX; ++s)
-      if (s < a.ks) ql.part[s] = p[(long)s * a.ks_stride];
-    if (a.bias) ql.bias = a.bias[h * a.r + j];
-  }
+  for (int s = 0; s < IG_KS_MAX; ++s) ql.part[s] = p[(long)min(s, a.ks - 1) * a.ks_stride];
+  ql.bias = a.bias ? a.bias[h * a.r + j] : 0.f;
+  ql.live = lane + 64 * k < a.r;
 }
 __device__ __forceinline__ float query_finish(const ScanArgs &a, const QueryLoads &ql) {
   float acc = ql.bias;
 #pragma unroll
-  for (int s = 0; s < IG_KS_MAX; ++s) acc += ql.part[s];
-  return acc * a.scale;
+  for (int s = 0; s < IG_KS_MAX; ++s) acc += s < a.ks ? ql.part[s] : 0.f;
+  return ql.live ? acc * a.scale : 0.f;
 }
 // lane l (< CH) gets q[j0 + l] out of the four per-lane registers
 __device__ __forceinline__ float query_block(const float (&qv)[4], int j0, int lane) {
