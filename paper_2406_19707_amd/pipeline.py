@@ -234,9 +234,12 @@ class Rehearsal:
             self.speculate(l)
             self.attend_indexed(l)
 
-    def step_overlapped(self):
+    def step_overlapped(self, after_layer=None):
         """Host-pool decode step (Fig. 3(d)): the rows of layer l are prefetched over PCIe on a side
-        stream while the main stream already rehearses layer l+1 and attends layer l-1."""
+        stream while the main stream already rehearses layer l+1 and attends layer l-1.
+        after_layer(l), if given, is called right after layer l's attention has been enqueued and
+        before its buffer set is released to the side stream (whatever it enqueues on the current
+        stream sees that layer's lists, fetched rows and output)."""
         main = torch.cuda.current_stream()
         ev_spec = [None] * self.L
         ev_gath = [None] * self.L
@@ -260,6 +263,8 @@ class Rehearsal:
                 self._use(l - 1)
                 main.wait_event(ev_gath[l - 1])
                 self.attend(l - 1)
+                if after_layer is not None:
+                    after_layer(l - 1)
                 ev_attn[l - 1] = torch.cuda.Event()
                 ev_attn[l - 1].record(main)
 
@@ -347,12 +352,14 @@ class Rehearsal:
             ev_attn[l].record(main)
         main.wait_stream(side)
 
-    def decode(self, steps: int, dense_first_layer: bool = True):
+    def decode(self, steps: int, dense_first_layer: bool = True, after_layer=None):
         """`steps` decode steps over all layers with a growing cache (Section 2.1, Section 4.3):
         per layer the rehearsal, prefetch and attention over the cached tokens plus the token being
         decoded, then that token's key / value are appended to the layer's pool and slab.  The first
         layer attends every token (speculation starts at the second layer, Section 4.3).  Needs
-        extra_tokens >= steps.  Single stream; the synthetic new-token rows are fixed tensors."""
+        extra_tokens >= steps.  Single stream; the synthetic new-token rows are fixed tensors.
+        after_layer(step, l), if given, is called after a layer's attention has been enqueued and
+        before its append."""
         w = self.w
         assert self.w.N + steps <= self.N_cap, "construct with extra_tokens >= steps"
         if not hasattr(self, "k_new"):
@@ -380,6 +387,8 @@ class Rehearsal:
                     self.ctx.ig_gather_attention(d, self.q[l], self.K[p], self.V[p], self.sel_idx,
                                                  self.stride, self.sel_cnt, self.K_sel, self.V_sel,
                                                  self.k_new, self.v_new, self.out)
+                if after_layer is not None:
+                    after_layer(s_, l)
                 self.ctx.ig_append_token(d, self.k_new, self.v_new, self.idx, self.slab[l], self.K[p],
                                          self.V[p], self.space)
         self.desc.N = n0
