@@ -1,8 +1,9 @@
 """GPU parity at the benchmark's full size (configs[1]: B8 H32 d128 N2048 r38, f16 KV, HBM pool), in
-the launch configuration bench.py times: the oracle checks sampled (sequence, head) pairs one by
-one, and properties that hold at any size are checked on every pair.  The two other shapes whose
-kernels take different paths at full size (configs[2]: rotary, 512 pairs of 8 tiles; configs[3]:
-1120 pairs, pinned host pool) are compared with the oracle on every pair."""
+the launch configurations bench.py times: the oracle checks every (sequence, head) pair one by
+one, and properties that hold at any size are checked on every pair as well.  The other shapes
+(configs[2]: rotary, 512 pairs of 8 tiles; configs[3]: 1120 pairs, pinned host pool; configs[4]:
+160 pairs of 64 tiles split over 8 workgroups each, rotary, pinned host pool) are compared with the
+oracle on every pair at their full size."""
 import numpy as np
 import pytest
 import torch
@@ -13,7 +14,7 @@ from oracle import ig_oracle as o
 pytestmark = pytest.mark.gpu
 
 
-def test_cfg2_full_size_sampled_pairs_and_properties():
+def test_cfg2_full_size_every_pair_and_properties():
     import paper_2406_19707_amd as ig
     w = wl.WORKLOADS[2]
     print(f"full-size case {w.name}: B{w.B} H{w.H} d{w.d} N{w.N}", flush=True)
@@ -87,12 +88,10 @@ def test_cfg2_full_size_sampled_pairs_and_properties():
         assert np.array_equal(g_K[i, :n], K2[i, lst])             # gathered rows are bit-exact copies
     assert np.all(np.abs(g_out - g_out_idx) <= 2e-3 + 1e-2 * np.abs(g_out))   # both attention forms agree
 
-    # ---- oracle on sampled pairs ----
+    # ---- oracle on every pair ----
     q_p = o.project(x16.astype(np.float32), W16.astype(np.float32), idx)
-    rng = np.random.default_rng(5)
-    heavy = np.argsort(g_cnt)[-3:]                                  # the longest lists, plus random pairs
-    sample = sorted(set(heavy.tolist()) | set(rng.choice(BH, 9, replace=False).tolist()))
-    for i in sample:
+    in_band = 0
+    for i in range(BH):
         b, h = divmod(i, w.H)
         Kt = K16[b, h].astype(np.float32)[None, None]
         Vt = V16[b, h].astype(np.float32)[None, None]
@@ -103,22 +102,23 @@ def test_cfg2_full_size_sampled_pairs_and_properties():
         if diff.size:
             thr = np.float32(s.max()) - np.float32(w.alpha)
             assert np.all(np.abs(s[0, 0, diff] - thr) <= 1e-3), (i, diff)
+            in_band += 1
             continue
         Ks, Vs = o.gather(Kt, r_idx, r_cnt), o.gather(Vt, r_idx, r_cnt)
         ref = o.attend(q16[b, h].astype(np.float32)[None], Ks, Vs, r_cnt, scale)[0]
         assert np.all(np.abs(g_out[i] - ref) <= 2e-2 + 1e-2 * np.abs(ref)), (i, np.abs(g_out[i] - ref).max())
-    print(f"  oracle agrees on pairs {sample}", flush=True)
+    print(f"  oracle agrees on all {BH} pairs ({in_band} with in-band list differences)", flush=True)
     ctx.close()
 
 
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("cfg,host_pool,B", [(3, False, None), (4, True, None), (5, True, 2)])
+@pytest.mark.parametrize("cfg,host_pool,B", [(3, False, None), (4, True, None), (5, True, None)])
 def test_full_size_every_pair_against_the_oracle(cfg, host_pool, B):
     import paper_2406_19707_amd as ig
     from ig_case import make_case
     from test_gpu_parity import check_case
     w = wl.WORKLOADS[cfg]
-    if B is not None:            # configs[4] at its full length (32768 tokens, 64 tiles per pair), two sequences (80 pairs)
+    if B is not None:
         w = wl.shrink(w, B=B)
     print(f"full-size case {w.name}: building inputs", flush=True)
     c = make_case(w, gain=w.gain)
