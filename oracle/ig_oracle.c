@@ -450,6 +450,42 @@ int igo_pool_victim(int BH, int N, int N_cap, const int32_t *counters, int32_t *
 }
 
 /* ------------------------------------------------------------------------------------------
+ * The two comparison policies of Section 4.4 (Table 2): FIFO evicts the oldest residing entry
+ * regardless of its use; LRU evicts the entry whose last use lies furthest back (the paper names
+ * the usual doubly linked list that promotes accessed entries to the head; the victim such a list
+ * yields is the entry with the oldest last-use time, which is what is written out here).
+ * Readings: time is a step number the caller supplies (any non-decreasing int32); every pool slot
+ * carries one stamp, stamps [B*H, N_cap]: FIFO -- the step its entry was written (prefill entries:
+ * their token position, so that the prompt's first token is the oldest); LRU -- the step its entry
+ * was last prefetched or written.  "Use" is being prefetched, as for the counter policy.  Equal
+ * stamps: the lowest slot.  The overwritten slot gets the current step (done by the caller here).
+ * ------------------------------------------------------------------------------------------ */
+int igo_pool_touch_lru(int BH, int N, int N_cap, const int32_t *sel_idx, int32_t stride,
+                       const int32_t *sel_cnt, int32_t *stamps, int32_t now) {
+  for (int bh = 0; bh < BH; ++bh)
+    for (int j = 0; j < sel_cnt[bh]; ++j) {
+      int t = sel_idx[(size_t)bh * stride + j];
+      if (t < 0 || t >= N) return IGO_EINVAL;
+      stamps[(size_t)bh * N_cap + t] = now;
+    }
+  return IGO_OK;
+}
+
+/* oldest stamp among the first N slots of every pool: the FIFO victim when the stamps are
+ * insertion steps, the LRU victim when they are last-use steps */
+int igo_pool_victim_oldest(int BH, int N, int N_cap, const int32_t *stamps, int32_t *victim) {
+  if (N < 1) return IGO_EINVAL;
+  for (int bh = 0; bh < BH; ++bh) {
+    const int32_t *s = stamps + (size_t)bh * N_cap;
+    int oldest = 0;
+    for (int t = 1; t < N; ++t)
+      if (s[t] < s[oldest]) oldest = t;
+    victim[bh] = oldest;
+  }
+  return IGO_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
  * Prefetch of the selected rows (Section 4.1, Section 4.3): plain row copies out of the pool.
  * pool [B*H, N_cap, d] -> out [B*H, stride, d]; rows j >= sel_cnt are left untouched.
  * ------------------------------------------------------------------------------------------ */

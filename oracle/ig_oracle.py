@@ -198,6 +198,27 @@ def pool_victim(counters, N):
     return victim
 
 
+def pool_touch_lru(stamps, sel_idx, sel_cnt, N, now):
+    """LRU comparison policy: every prefetched slot's last-use stamp becomes `now`.
+    stamps int32 [B*H, N_cap], updated in place."""
+    assert stamps.dtype == np.int32 and stamps.flags.c_contiguous
+    sel_idx, sel_cnt = _i32(sel_idx), _i32(sel_cnt)
+    BH, N_cap = stamps.shape
+    _check(_load().igo_pool_touch_lru(BH, N, N_cap, _i(sel_idx), sel_idx.shape[1], _i(sel_cnt),
+                                      _i(stamps), int(now)), "pool_touch_lru")
+    return stamps
+
+
+def pool_victim_oldest(stamps, N):
+    """Slot with the oldest stamp among the first N of every pool (ties: the lowest slot): the FIFO
+    victim for insertion stamps, the LRU victim for last-use stamps."""
+    stamps = _i32(stamps)
+    BH, N_cap = stamps.shape
+    victim = np.zeros(BH, np.int32)
+    _check(_load().igo_pool_victim_oldest(BH, N, N_cap, _i(stamps), _i(victim)), "pool_victim_oldest")
+    return victim
+
+
 def gather(pool, sel_idx, sel_cnt):
     """Rows pool[bh, sel_idx[bh, j]] -> out [B*H, stride, d] (zeros beyond the count)."""
     pool, sel_idx, sel_cnt = _f32(pool), _i32(sel_idx), _i32(sel_cnt)

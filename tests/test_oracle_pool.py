@@ -69,3 +69,56 @@ def test_bad_arguments():
         o.pool_touch(c, idx, cnt, 4)                 # slot outside the pool
     with pytest.raises(RuntimeError):
         o.pool_touch(c, *lists([[0]], 4), 4, counter_max=0)
+
+
+# ---- the comparison policies of Section 4.4 / Table 2: FIFO and LRU --------------------------------
+# Pinned against the textbook structures the paper names: a queue for FIFO, an access-ordered list
+# for LRU (collections.OrderedDict.move_to_end is the "promote to the head" of the doubly linked
+# list), driven by the same random trace of prefetches and replacements.
+
+def test_fifo_and_lru_hand_worked():
+    # one pool of 4 entries written at steps 0..3 (prefill: token positions)
+    fifo = np.array([[0, 1, 2, 3]], np.int32)
+    lru = fifo.copy()
+    idx, cnt = lists([[0, 2]], 4)
+    o.pool_touch_lru(lru, idx, cnt, 4, now=4)              # step 4 prefetches entries 0 and 2
+    assert lru.tolist() == [[4, 1, 4, 3]]
+    assert o.pool_victim_oldest(fifo, 4).tolist() == [0]   # FIFO: the oldest resident, used or not
+    assert o.pool_victim_oldest(lru, 4).tolist() == [1]    # LRU: entry 1 was never used again
+    fifo[0, 0] = 4                                          # FIFO overwrote slot 0 at step 4
+    assert o.pool_victim_oldest(fifo, 4).tolist() == [1]
+    # equal stamps: the lowest slot; only the first N slots are candidates
+    assert o.pool_victim_oldest(np.array([[5, 5, 5], [7, 2, 2]], np.int32), 3).tolist() == [0, 1]
+    assert o.pool_victim_oldest(np.array([[5, 4, 0]], np.int32), 2).tolist() == [1]
+
+
+@settings(max_examples=40, deadline=None)
+@given(st.integers(2, 24), st.integers(0, 2 ** 31 - 1))
+def test_fifo_and_lru_match_queue_and_access_ordered_list(N, seed):
+    from collections import OrderedDict, deque
+    rng = np.random.default_rng(seed)
+    fifo = np.arange(N, dtype=np.int32)[None].copy()       # prefill: entry t written at time t (all before 2 N)
+    lru = fifo.copy()
+    queue = deque(range(N))                                 # oldest resident on the left
+    order = OrderedDict((t, None) for t in range(N))        # least recently used first
+    for step in range(N, N + 30):
+        used = np.sort(rng.choice(N, int(rng.integers(0, N)), replace=False))
+        idx, cnt = lists([used], N)
+        o.pool_touch_lru(lru, idx, cnt, N, now=2 * step)   # the step's prefetches come before its insertion
+        for t in used:                                      # ascending slot order within a step
+            order.move_to_end(int(t))
+        v_fifo, v_lru = int(o.pool_victim_oldest(fifo, N)[0]), int(o.pool_victim_oldest(lru, N)[0])
+        assert v_fifo == queue[0]
+        assert v_lru == next(iter(order))
+        # the new token replaces the victim of each policy in its own pool
+        queue.popleft()
+        queue.append(v_fifo)
+        fifo[0, v_fifo] = 2 * step + 1
+        order.move_to_end(v_lru)
+        lru[0, v_lru] = 2 * step + 1
+
+
+def test_lru_bad_slot_is_refused():
+    s = np.zeros((1, 4), np.int32)
+    with pytest.raises(RuntimeError):
+        o.pool_touch_lru(s, *lists([[9]], 4), 4, now=1)
