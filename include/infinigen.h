@@ -25,6 +25,15 @@
  *  - Calls on one context must not overlap in time on different streams: they share workspaces.
  *  - dtype IG_F16: x, weights, K, V, q, out are IEEE half; IG_F32: float.  Partial queries,
  *    scores and all accumulation are float32 in both cases.  Index arrays are int32.
+ *  - Every array of desc->dtype (x, weights, pools, fetched rows, queries, new-token rows) must be
+ *    16-byte aligned (IG_EINVAL otherwise) and a row of d elements a multiple of 16 bytes.  The four
+ *    attention entry points (ig_sparse_attention, ig_sparse_attention_static,
+ *    ig_sparse_attention_indexed, ig_gather_attention) and ig_layer_step need more: a row of
+ *    16 * 2^k bytes, at most 1024 (d = 8, 16, 32, 64, 128, 256, 512 in half precision); other head
+ *    dimensions (d = 96, 80) pass setup, ig_speculate and ig_gather_kv and get IG_ESHAPE there.
+ *  - Index values are never followed outside their array: a kept-column index outside [0, d) or a
+ *    selected slot outside [0, N_cap) is clamped into the range (the result is then wrong for that
+ *    entry, but no access leaves the caller's arrays).
  */
 #ifndef INFINIGEN_H
 #define INFINIGEN_H
@@ -49,6 +58,9 @@ enum {
 
 enum { IG_F32 = 0, IG_F16 = 1 };
 enum { IG_MEM_DEVICE = 0, IG_MEM_HOST_PINNED = 1 };
+/* Victim selection policies of the KV cache pool (Section 4.4): the counter-based one the paper
+ * adopts, and the two it is compared with (Table 2). */
+enum { IG_POLICY_COUNTER = 0, IG_POLICY_FIFO = 1, IG_POLICY_LRU = 2 };
 
 /* Kernel identifiers for ig_profile_read. */
 enum {
@@ -194,6 +206,29 @@ int ig_pool_victim(ig_ctx *ctx, const ig_desc *desc, const int32_t *counters, in
 int ig_pool_replace(ig_ctx *ctx, const ig_desc *desc, const int32_t *victim, const void *k_new,
                     const void *v_new, const int32_t *idx_dev, void *slab, void *Kpool, void *Vpool,
                     int pool_space, int32_t *counters, void *stream);
+
+/* The same management with a choice of policy (Section 4.4, Table 2: FIFO and LRU are the policies
+ * the counter-based one is compared with).  `state`: device int32 [B*H, N_cap], one word per slot:
+ *   IG_POLICY_COUNTER  the prefetch counters above (param = counter_max; now is ignored);
+ *   IG_POLICY_FIFO     the step at which the slot's entry was written (the caller initialises the
+ *                      prompt's entries with their token positions, so that the first token is the
+ *                      oldest); being prefetched changes nothing, ig_pool_touch_policy returns at
+ *                      once (param ignored);
+ *   IG_POLICY_LRU      the step at which the slot's entry was last prefetched or written
+ *                      (param = the current step).
+ * Steps are int32 values the caller supplies, non-decreasing; a step's prefetches should carry a
+ * smaller value than its insertion (2*step and 2*step + 1, say) if the new entry is to count as
+ * more recent than the entries prefetched in that step.  For FIFO and LRU the victim is the slot
+ * with the smallest stamp, i.e. ig_pool_victim on `state`: it is the same minimum, the lowest slot
+ * on ties.  ig_pool_replace_policy overwrites the victim like ig_pool_replace and restarts its word
+ * at 0 (counter) or `now` (FIFO, LRU). */
+int ig_pool_touch_policy(ig_ctx *ctx, const ig_desc *desc, int policy, const int32_t *sel_idx,
+                         int32_t sel_stride, const int32_t *sel_cnt, int32_t *state, int32_t param,
+                         void *stream);
+int ig_pool_replace_policy(ig_ctx *ctx, const ig_desc *desc, int policy, const int32_t *victim,
+                           const void *k_new, const void *v_new, const int32_t *idx_dev, void *slab,
+                           void *Kpool, void *Vpool, int pool_space, int32_t *state, int32_t now,
+                           void *stream);
 
 /* ---- hot path ----------------------------------------------------------------------------- */
 

@@ -14,7 +14,7 @@ import numpy as np
 
 __all__ = [
     "IG_OK", "IG_EINVAL", "IG_ESHAPE", "IG_EDTYPE", "IG_ECAPACITY", "IG_EHIP", "IG_ENOCONV",
-    "IG_ENOMEM", "IG_F32", "IG_F16", "IG_MEM_DEVICE", "IG_MEM_HOST_PINNED", "IG_K_PROJECT",
+    "IG_ENOMEM", "IG_F32", "IG_F16", "IG_MEM_DEVICE", "IG_MEM_HOST_PINNED", "IG_POLICY_COUNTER", "IG_POLICY_FIFO", "IG_POLICY_LRU", "IG_K_PROJECT",
     "IG_K_FINALIZE", "IG_K_SCAN", "IG_K_SELECT", "IG_K_GATHER", "IG_K_ATTENTION", "IG_K_BUILD",
     "IG_K_COPY", "IG_K_READ", "IG_K_LAYER", "IgDesc", "IgError", "Context", "lib", "lib_path", "ig_skew_offline",
     "ig_partial_index", "ig_apply_skew", "ig_rope_rows", "ig_wq_bytes", "ig_slab_bytes", "EXPORTS",
@@ -23,6 +23,7 @@ __all__ = [
 IG_OK, IG_EINVAL, IG_ESHAPE, IG_EDTYPE, IG_ECAPACITY, IG_EHIP, IG_ENOCONV, IG_ENOMEM = range(8)
 IG_F32, IG_F16 = 0, 1
 IG_MEM_DEVICE, IG_MEM_HOST_PINNED = 0, 1
+IG_POLICY_COUNTER, IG_POLICY_FIFO, IG_POLICY_LRU = 0, 1, 2
 (IG_K_PROJECT, IG_K_FINALIZE, IG_K_SCAN, IG_K_SELECT, IG_K_GATHER, IG_K_ATTENTION, IG_K_BUILD,
  IG_K_COPY, IG_K_READ, IG_K_LAYER) = range(10)
 
@@ -32,7 +33,7 @@ EXPORTS = [
     "ig_skew_offline", "ig_apply_skew", "ig_rope_rows",
     "ig_partial_index", "ig_skew_device", "ig_partial_index_device", "ig_wq_bytes", "ig_wq_build", "ig_slab_bytes",
     "ig_slab_build", "ig_append_token",
-    "ig_pool_touch", "ig_pool_victim", "ig_pool_replace",
+    "ig_pool_touch", "ig_pool_victim", "ig_pool_replace", "ig_pool_touch_policy", "ig_pool_replace_policy",
     "ig_speculate", "ig_project", "ig_scan_select", "ig_project_indexed", "ig_speculate_indexed",
     "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention", "ig_sparse_attention_static",
     "ig_sparse_attention_indexed", "ig_gather_attention", "ig_layer_step", "ig_set_wait_limit", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
@@ -99,6 +100,9 @@ def lib():
             "ig_pool_touch": (ctypes.c_int, [_vp, _dp, _vp, _i32, _vp, _vp, _i32, _vp]),
             "ig_pool_victim": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp]),
             "ig_pool_replace": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_int, _vp, _vp]),
+            "ig_pool_touch_policy": (ctypes.c_int, [_vp, _dp, ctypes.c_int, _vp, _i32, _vp, _vp, _i32, _vp]),
+            "ig_pool_replace_policy": (ctypes.c_int, [_vp, _dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                                      ctypes.c_int, _vp, _i32, _vp]),
             "ig_speculate": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
             "ig_project": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
             "ig_scan_select": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
@@ -293,6 +297,16 @@ class Context:
         self._ck(lib().ig_pool_replace(self._h, ctypes.byref(desc), _ptr(victim), _ptr(k_new),
                                        _ptr(v_new), _ptr(idx_dev), _ptr(slab), _ptr(Kpool),
                                        _ptr(Vpool), pool_space, _ptr(counters), _stream(stream)))
+
+    def ig_pool_touch_policy(self, desc, policy, sel_idx, sel_stride, sel_cnt, state, param, stream=None):
+        self._ck(lib().ig_pool_touch_policy(self._h, ctypes.byref(desc), policy, _ptr(sel_idx), sel_stride,
+                                            _ptr(sel_cnt), _ptr(state), param, _stream(stream)))
+
+    def ig_pool_replace_policy(self, desc, policy, victim, k_new, v_new, idx_dev, slab, Kpool, Vpool,
+                               pool_space, state, now, stream=None):
+        self._ck(lib().ig_pool_replace_policy(self._h, ctypes.byref(desc), policy, _ptr(victim), _ptr(k_new),
+                                              _ptr(v_new), _ptr(idx_dev), _ptr(slab), _ptr(Kpool),
+                                              _ptr(Vpool), pool_space, _ptr(state), now, _stream(stream)))
 
     def ig_speculate(self, desc, x, wq, bias, A_p, pos, slab, sel_idx, sel_stride, sel_cnt,
                      scores_opt=None, stream=None):

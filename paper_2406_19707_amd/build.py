@@ -10,11 +10,10 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libinfinigen_hip.so")
 SOURCES = ["ig_api.hip", "k_scan.hip", "k_project.hip", "k_kv.hip", "k_layer.hip", "k_equalize.hip", "k_index.hip", "k_skew.hip", "ig_host.cpp"]
-HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+HIPCC = "/opt/rocm/bin/hipcc"
 # packed-fp32 instruction selection is switched off for every device compile
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
-COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
-          *os.environ.get("IG_HIPCC_EXTRA", "").split()]   # extra flags for development builds
+COMMON = ["-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function"]
 
 
 def _compile(src: str) -> str:

@@ -4,6 +4,7 @@
 #include <stdarg.h>
 #include <string.h>
 
+#include <initializer_list>
 #include <new>
 
 #include "ig_internal.h"
@@ -79,6 +80,13 @@ int check_desc(ig_ctx *ctx, const ig_desc *d) {
   if (d->rope && (d->d % 2 || !(d->rope_theta > 0.0f)))
     return ig_fail(ctx, IG_EINVAL, "rope needs an even d and a positive base");
   if ((long)d->B * d->H > 2147483647L / 4) return ig_fail(ctx, IG_ESHAPE, "B*H too large");
+  return IG_OK;
+}
+
+// the kernels read rows, queries and inputs in 16-byte units
+int check_aligned(ig_ctx *ctx, const char *what, std::initializer_list<const void *> ptrs) {
+  for (const void *p : ptrs)
+    if (p && (uintptr_t)p % 16) return ig_fail(ctx, IG_EINVAL, "%s: every array must be 16-byte aligned", what);
   return IG_OK;
 }
 
@@ -298,6 +306,7 @@ int ig_slab_build(ig_ctx *ctx, const ig_desc *d, const void *Kpool, int pool_spa
   int rc = check_desc(ctx, d);
   if (rc) return rc;
   if (!Kpool || !idx_dev || !slab) return ig_fail(ctx, IG_EINVAL, "ig_slab_build: NULL argument");
+  if ((rc = check_aligned(ctx, "ig_slab_build", {Kpool}))) return rc;
   if ((uintptr_t)slab % 16) return ig_fail(ctx, IG_EINVAL, "ig_slab_build: slab must be 16-byte aligned");
   if ((rc = set_device(ctx))) return rc;
   const void *kp = nullptr;
@@ -331,7 +340,7 @@ int ig_append_token(ig_ctx *ctx, const ig_desc *d, const void *k_new, const void
   if ((rc = resolve_pool(ctx, Kpool, pool_space, &kp))) return rc;
   if ((rc = resolve_pool(ctx, Vpool, pool_space, &vp))) return rc;
   return ig_launch_append(ctx, d, k_new, v_new, idx_dev, slab, const_cast<void *>(kp),
-                          const_cast<void *>(vp), nullptr, nullptr, (hipStream_t)stream);
+                          const_cast<void *>(vp), nullptr, nullptr, 0, (hipStream_t)stream);
 }
 
 int ig_pool_touch(ig_ctx *ctx, const ig_desc *d, const int32_t *sel_idx, int32_t sel_stride,
@@ -369,12 +378,49 @@ int ig_pool_replace(ig_ctx *ctx, const ig_desc *d, const int32_t *victim, const 
   if ((rc = resolve_pool(ctx, Kpool, pool_space, &kp))) return rc;
   if ((rc = resolve_pool(ctx, Vpool, pool_space, &vp))) return rc;
   return ig_launch_append(ctx, d, k_new, v_new, idx_dev, slab, const_cast<void *>(kp),
-                          const_cast<void *>(vp), victim, counters, (hipStream_t)stream);
+                          const_cast<void *>(vp), victim, counters, 0, (hipStream_t)stream);
+}
+
+int ig_pool_touch_policy(ig_ctx *ctx, const ig_desc *d, int policy, const int32_t *sel_idx,
+                         int32_t sel_stride, const int32_t *sel_cnt, int32_t *state, int32_t param,
+                         void *stream) {
+  if (policy == IG_POLICY_COUNTER)
+    return ig_pool_touch(ctx, d, sel_idx, sel_stride, sel_cnt, state, param, stream);
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (policy != IG_POLICY_FIFO && policy != IG_POLICY_LRU) return ig_fail(ctx, IG_EINVAL, "unknown pool policy %d", policy);
+  if (!state) return ig_fail(ctx, IG_EINVAL, "ig_pool_touch_policy: state is NULL");
+  if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
+  if (policy == IG_POLICY_FIFO) return IG_OK;        // being prefetched does not change an entry's age
+  if ((rc = set_device(ctx))) return rc;
+  return ig_launch_pool_touch_lru(ctx, d, sel_idx, sel_stride, sel_cnt, state, param, (hipStream_t)stream);
+}
+
+int ig_pool_replace_policy(ig_ctx *ctx, const ig_desc *d, int policy, const int32_t *victim,
+                           const void *k_new, const void *v_new, const int32_t *idx_dev, void *slab,
+                           void *Kpool, void *Vpool, int pool_space, int32_t *state, int32_t now,
+                           void *stream) {
+  int rc = check_desc(ctx, d);
+  if (rc) return rc;
+  if (policy != IG_POLICY_COUNTER && policy != IG_POLICY_FIFO && policy != IG_POLICY_LRU)
+    return ig_fail(ctx, IG_EINVAL, "unknown pool policy %d", policy);
+  if (!victim || !k_new || !v_new || !idx_dev || !slab || !Kpool || !Vpool || !state)
+    return ig_fail(ctx, IG_EINVAL, "ig_pool_replace_policy: NULL argument");
+  if ((uintptr_t)k_new % 16 || (uintptr_t)v_new % 16)
+    return ig_fail(ctx, IG_EINVAL, "ig_pool_replace_policy: k_new and v_new must be 16-byte aligned");
+  if ((rc = set_device(ctx))) return rc;
+  const void *kp = nullptr, *vp = nullptr;
+  if ((rc = resolve_pool(ctx, Kpool, pool_space, &kp))) return rc;
+  if ((rc = resolve_pool(ctx, Vpool, pool_space, &vp))) return rc;
+  return ig_launch_append(ctx, d, k_new, v_new, idx_dev, slab, const_cast<void *>(kp),
+                          const_cast<void *>(vp), victim, state, policy == IG_POLICY_COUNTER ? 0 : now,
+                          (hipStream_t)stream);
 }
 
 static int project_partials(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq,
                             const float *A_p, const int32_t *pos, ProjGeom *g, hipStream_t s) {
   if (!x || !wq) return ig_fail(ctx, IG_EINVAL, "x or wq is NULL");
+  if (int rc0 = check_aligned(ctx, "projection", {x, wq})) return rc0;
   if (d->rope && (!A_p || !pos)) return ig_fail(ctx, IG_EINVAL, "rope mode needs A_p and pos");
   int rc = set_device(ctx);
   if (rc) return rc;
@@ -504,6 +550,7 @@ int ig_gather_kv(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const void *V
   int rc = check_desc(ctx, d);
   if (rc) return rc;
   if (!Kpool || !Vpool || !K_sel || !V_sel) return ig_fail(ctx, IG_EINVAL, "ig_gather_kv: NULL argument");
+  if ((rc = check_aligned(ctx, "ig_gather_kv", {Kpool, Vpool, K_sel, V_sel}))) return rc;
   if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
   if ((rc = set_device(ctx))) return rc;
   const void *kp = nullptr, *vp = nullptr;
@@ -519,6 +566,7 @@ int ig_sparse_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
   int rc = check_desc(ctx, d);
   if (rc) return rc;
   if (!q || !K_sel || !V_sel || !sel_cnt || !out) return ig_fail(ctx, IG_EINVAL, "ig_sparse_attention: NULL argument");
+  if ((rc = check_aligned(ctx, "ig_sparse_attention", {q, K_sel, V_sel, k_new, v_new}))) return rc;
   if ((k_new == nullptr) != (v_new == nullptr)) return ig_fail(ctx, IG_EINVAL, "k_new and v_new go together");
   if (sel_stride < 1) return ig_fail(ctx, IG_ESHAPE, "sel_stride = %d", sel_stride);
   if ((rc = set_device(ctx))) return rc;
@@ -533,6 +581,7 @@ int ig_sparse_attention_static(ig_ctx *ctx, const ig_desc *d, const void *q, con
   if (rc) return rc;
   if (!q || !K_sel || !V_sel || !sel_cnt || !out)
     return ig_fail(ctx, IG_EINVAL, "ig_sparse_attention_static: NULL argument");
+  if ((rc = check_aligned(ctx, "ig_sparse_attention_static", {q, K_sel, V_sel, k_new, v_new}))) return rc;
   if ((k_new == nullptr) != (v_new == nullptr)) return ig_fail(ctx, IG_EINVAL, "k_new and v_new go together");
   if (sel_stride < 1) return ig_fail(ctx, IG_ESHAPE, "sel_stride = %d", sel_stride);
   if ((rc = set_device(ctx))) return rc;
@@ -547,6 +596,7 @@ int ig_sparse_attention_indexed(ig_ctx *ctx, const ig_desc *d, const void *q, co
   int rc = check_desc(ctx, d);
   if (rc) return rc;
   if (!q || !Kpool || !Vpool || !out) return ig_fail(ctx, IG_EINVAL, "ig_sparse_attention_indexed: NULL argument");
+  if ((rc = check_aligned(ctx, "ig_sparse_attention_indexed", {q, Kpool, Vpool, k_new, v_new}))) return rc;
   if ((k_new == nullptr) != (v_new == nullptr)) return ig_fail(ctx, IG_EINVAL, "k_new and v_new go together");
   if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
   if ((rc = set_device(ctx))) return rc;
@@ -562,6 +612,7 @@ int ig_gather_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
   if (rc) return rc;
   if (!q || !Kpool || !Vpool || !K_sel || !V_sel || !out)
     return ig_fail(ctx, IG_EINVAL, "ig_gather_attention: NULL argument");
+  if ((rc = check_aligned(ctx, "ig_gather_attention", {q, Kpool, Vpool, K_sel, V_sel, k_new, v_new}))) return rc;
   if ((k_new == nullptr) != (v_new == nullptr)) return ig_fail(ctx, IG_EINVAL, "k_new and v_new go together");
   if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
   if ((rc = set_device(ctx))) return rc;
@@ -578,6 +629,7 @@ int ig_layer_step(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, 
   if (rc) return rc;
   if (!slab || !q || !Kpool || !Vpool || !K_sel || !V_sel || !out)
     return ig_fail(ctx, IG_EINVAL, "ig_layer_step: NULL argument");
+  if ((rc = check_aligned(ctx, "ig_layer_step", {q, Kpool, Vpool, K_sel, V_sel, k_new, v_new}))) return rc;
   if ((k_new == nullptr) != (v_new == nullptr)) return ig_fail(ctx, IG_EINVAL, "k_new and v_new go together");
   if ((rc = check_sel(ctx, sel_idx_next, sel_stride, sel_cnt_next))) return rc;
   if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;

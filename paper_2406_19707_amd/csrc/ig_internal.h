@@ -24,9 +24,7 @@ template <> struct Elem<float> {
 };
 
 // Tokens of one channel that a lane of the scan loads at once (the slab's tile is 64 lanes of them).
-#ifndef IG_SLAB_TPL_HALF
-#define IG_SLAB_TPL_HALF 8
-#endif
+constexpr int IG_SLAB_TPL_HALF = 8;
 template <typename T> struct SlabElem;
 template <> struct SlabElem<half_t> {
   static constexpr int TPL = IG_SLAB_TPL_HALF;
@@ -156,7 +154,9 @@ int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const
                           float *scores_opt, hipStream_t s);
 int ig_launch_append(ig_ctx *ctx, const ig_desc *d, const void *k_new, const void *v_new,
                      const int32_t *idx, void *slab, void *Kpool, void *Vpool,
-                     const int32_t *slots, int32_t *counters, hipStream_t s);
+                     const int32_t *slots, int32_t *counters, int32_t restart, hipStream_t s);
+int ig_launch_pool_touch_lru(ig_ctx *ctx, const ig_desc *d, const int32_t *sel_idx, int32_t sel_stride,
+                             const int32_t *sel_cnt, int32_t *stamps, int32_t now, hipStream_t s);
 int ig_launch_pool_touch(ig_ctx *ctx, const ig_desc *d, const int32_t *sel_idx, int32_t sel_stride,
                          const int32_t *sel_cnt, int32_t *counters, int counter_max, hipStream_t s);
 int ig_launch_pool_victim(ig_ctx *ctx, const ig_desc *d, const int32_t *counters, int32_t *victim,

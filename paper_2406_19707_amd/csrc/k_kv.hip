@@ -37,7 +37,8 @@ __global__ __launch_bounds__(256) void slab_build(const T *__restrict__ Kpool,
     int t = t0 + tt;
     if (t >= nTiles * TILE) continue;
     int tile = t / TILE, tin = t % TILE;
-    slab[((long)bh * nTiles + tile) * r * TILE + (long)j * TILE + tin] = rows[tt * ldr + idx[h * r + j]];
+    const int col = min(max(idx[h * r + j], 0), d - 1);     // an index outside the head is clamped, never followed
+    slab[((long)bh * nTiles + tile) * r * TILE + (long)j * TILE + tin] = rows[tt * ldr + col];
   }
 }
 
@@ -51,7 +52,7 @@ __global__ __launch_bounds__(64) void append_token(const T *__restrict__ k_new, 
                                                    u128 *__restrict__ Kpool, u128 *__restrict__ Vpool,
                                                    int H, int d, int r, int N_cap, int nTiles, int slot_all,
                                                    const int32_t *__restrict__ slots,
-                                                   int32_t *__restrict__ counters) {
+                                                   int32_t *__restrict__ counters, int32_t restart) {
   constexpr int TPL = Elem<T>::TPL;
   constexpr int TILE = IG_WAVE * SlabElem<T>::TPL;
   const int bh = blockIdx.x, h = bh % H;
@@ -59,7 +60,7 @@ __global__ __launch_bounds__(64) void append_token(const T *__restrict__ k_new, 
   // the pool is ignored
   const int slot = slots ? slots[bh] : slot_all;
   if (slot < 0 || slot >= N_cap) return;
-  if (counters && threadIdx.x == 0) counters[(long)bh * N_cap + slot] = 0;
+  if (counters && threadIdx.x == 0) counters[(long)bh * N_cap + slot] = restart;   // policy state of the new entry
   const int U = d / TPL;
   const u128 *kn = reinterpret_cast<const u128 *>(k_new + (long)bh * d);
   const u128 *vn = reinterpret_cast<const u128 *>(v_new + (long)bh * d);
@@ -69,7 +70,8 @@ __global__ __launch_bounds__(64) void append_token(const T *__restrict__ k_new, 
   }
   const int tile = slot / TILE, tin = slot % TILE;
   for (int j = threadIdx.x; j < r; j += 64)
-    slab[((long)bh * nTiles + tile) * r * TILE + (long)j * TILE + tin] = k_new[(long)bh * d + idx[h * r + j]];
+    slab[((long)bh * nTiles + tile) * r * TILE + (long)j * TILE + tin] =
+        k_new[(long)bh * d + min(max(idx[h * r + j], 0), d - 1)];
 }
 
 // ---- pool counters (Section 4.4, counter-based victim selection) ------------------------------------
@@ -95,6 +97,20 @@ __global__ __launch_bounds__(256) void pool_touch(const int32_t *__restrict__ se
   }
   if (__syncthreads_or(sat))
     for (int t = threadIdx.x; t < N; t += 256) c[t] >>= 1;
+}
+
+// LRU comparison policy (Section 4.4, Table 2): the last-use stamp of every prefetched slot becomes
+// `now`; the victim kernel below then names the slot whose last use lies furthest back.
+__global__ __launch_bounds__(256) void pool_touch_lru(const int32_t *__restrict__ sel_idx,
+                                                      const int32_t *__restrict__ sel_cnt,
+                                                      int32_t *__restrict__ stamps, int stride, int N,
+                                                      int N_cap, int32_t now) {
+  const int bh = blockIdx.x;
+  const int n = min(sel_cnt[bh], stride);
+  for (int j = threadIdx.x; j < n; j += 256) {
+    const int t = sel_idx[(long)bh * stride + j];
+    if (t >= 0 && t < N) stamps[(long)bh * N_cap + t] = now;
+  }
 }
 
 __global__ __launch_bounds__(256) void pool_victim(const int32_t *__restrict__ counters,
@@ -147,7 +163,7 @@ __global__ __launch_bounds__(256) void gather_rows_sliced(
     for (int i = 0; i < GATHER_BATCH; ++i) {
       const int u = min(u0 + 256 * i, total - 1);
       const int rr = u / U, c = u - rr * U;
-      src[i] = src0 + (long)list[rr] * U + c;
+      src[i] = src0 + (long)min(max(list[rr], 0), N_cap - 1) * U + c;   // a slot outside the pool is clamped
     }
 #pragma unroll
     for (int i = 0; i < GATHER_BATCH; ++i) {
@@ -224,7 +240,7 @@ __global__ __launch_bounds__(THREADS) void gather_rows_flat(
         if (cand < BH && pre[cand] <= row) lo = cand;
       }
       const int j = row - pre[lo];
-      const long t = sel_idx[(long)lo * stride + j];
+      const long t = min(max(sel_idx[(long)lo * stride + j], 0), N_cap - 1);   // a slot outside the pool is clamped
       src[i] = ((long)lo * N_cap + t) * U + c;
       dst[i] = ((long)lo * stride + j) * U + c;
     }
@@ -301,7 +317,7 @@ int ig_launch_slab_build(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const
 
 int ig_launch_append(ig_ctx *ctx, const ig_desc *d, const void *k_new, const void *v_new,
                      const int32_t *idx, void *slab, void *Kpool, void *Vpool,
-                     const int32_t *slots, int32_t *counters, hipStream_t s) {
+                     const int32_t *slots, int32_t *counters, int32_t restart, hipStream_t s) {
   const int tile = ig_tile_tokens(d->dtype);
   const int nTiles = (d->N_cap + tile - 1) / tile;
   dim3 grid(d->B * d->H), block(64);
@@ -309,12 +325,12 @@ int ig_launch_append(ig_ctx *ctx, const ig_desc *d, const void *k_new, const voi
     auto k = append_token<half_t>;
     IG_LAUNCH(ctx, IG_K_BUILD, k, grid, block, s, (const half_t *)k_new, (const half_t *)v_new, idx,
               (half_t *)slab, (u128 *)Kpool, (u128 *)Vpool, (int)d->H, (int)d->d, (int)d->r,
-              (int)d->N_cap, nTiles, (int)d->N, slots, counters);
+              (int)d->N_cap, nTiles, (int)d->N, slots, counters, restart);
   } else {
     auto k = append_token<float>;
     IG_LAUNCH(ctx, IG_K_BUILD, k, grid, block, s, (const float *)k_new, (const float *)v_new, idx,
               (float *)slab, (u128 *)Kpool, (u128 *)Vpool, (int)d->H, (int)d->d, (int)d->r,
-              (int)d->N_cap, nTiles, (int)d->N, slots, counters);
+              (int)d->N_cap, nTiles, (int)d->N, slots, counters, restart);
   }
   return IG_OK;
 }
@@ -324,6 +340,14 @@ int ig_launch_pool_touch(ig_ctx *ctx, const ig_desc *d, const int32_t *sel_idx, 
   auto k = pool_touch;
   IG_LAUNCH(ctx, IG_K_BUILD, k, dim3(d->B * d->H), dim3(256), s, sel_idx, sel_cnt, counters,
             (int)sel_stride, (int)d->N, (int)d->N_cap, counter_max);
+  return IG_OK;
+}
+
+int ig_launch_pool_touch_lru(ig_ctx *ctx, const ig_desc *d, const int32_t *sel_idx, int32_t sel_stride,
+                             const int32_t *sel_cnt, int32_t *stamps, int32_t now, hipStream_t s) {
+  auto k = pool_touch_lru;
+  IG_LAUNCH(ctx, IG_K_BUILD, k, dim3(d->B * d->H), dim3(256), s, sel_idx, sel_cnt, stamps,
+            (int)sel_stride, (int)d->N, (int)d->N_cap, now);
   return IG_OK;
 }
 

@@ -41,7 +41,7 @@ namespace {
 __device__ __forceinline__ int colmap(int c, int d, int r, const int32_t *idx) {
   if (!idx) return c;
   int h = c / r, j = c % r;
-  return h * d + idx[h * r + j];
+  return h * d + min(max(idx[h * r + j], 0), d - 1);   // an index outside the head is clamped
 }
 
 // MFMA fragment order: piece (cblk, kblk) is 64 lanes x 8 halves; lane (kg = lane/16, i = lane%16)
