@@ -19,6 +19,7 @@ workload cannot take the others' figures with it.
 from __future__ import annotations
 
 import argparse
+import ctypes
 import json
 import os
 import re
@@ -305,6 +306,35 @@ def run_workload(args) -> dict:
                       "blob_bytes_saved_MB": R.wq.numel() / 1e6,
                       "lists_with_other_count_than_stored_blob_last_layer": differing}
 
+    # ---- partial key cache in host memory, speculation on the CPU (Section 6.2) ----
+    host_spec = None
+    if not brief:
+        R._use(0)
+        n_host = min(L, 4)
+        R.host_speculation_setup(slab_layers=n_host)
+        R.step_host_speculation()
+        torch.cuda.synchronize()
+        host_cnt = R.sel_cnt.clone()          # the last layer's lists, made on the host
+        R.ctx.ig_scan_select(R.desc, R.q_p, R.slab[(L - 1) % n_host], R.sel_idx, R.stride, R.sel_cnt)
+        torch.cuda.synchronize()
+        same = bool(torch.equal(R.sel_cnt, host_cnt))
+        hs_ms = timed(R.step_host_speculation, 2)
+        t0 = time.perf_counter()
+        for l in range(n_host):
+            ig.lib().ig_speculate_host(R.ctx._h, ctypes.byref(R.desc), R.q_p_host.data_ptr(),
+                                       R.slab_host[l].data_ptr(), R.sel_idx_host.data_ptr(), R.stride,
+                                       R.sel_cnt_host.data_ptr(), None, 0)
+        host_us = (time.perf_counter() - t0) * 1e6 / n_host
+        host_spec = {"us_per_layer": hs_ms * 1e3 / L, "launch": "eager, one stream, host threads",
+                     "host_scan_select_us": host_us,
+                     "host_scan_GBps": R.scan_bytes() / (host_us * 1e-6) / 1e9,
+                     "host_threads": min(os.cpu_count() or 1, 64, w.B * w.H),
+                     "partial_key_cache_MB_off_the_gpu_per_layer": R.slab[0].numel() / 1e6,
+                     "host_slab_layers": n_host,
+                     "same_counts_as_device_scan_last_layer": same}
+        del R.slab_host
+        log(f"host speculation {host_spec['us_per_layer']:.0f} us/layer")
+
     # ---- decode loop with a growing cache: append of the decoded token after every layer ----
     decode_loop = None
     if not args.no_decode_loop and not brief:
@@ -484,6 +514,7 @@ def run_workload(args) -> dict:
         "literal_variant": literal,
         "head_equalized_variant": equalized,
         "index_only_weight_variant": index_only,
+        "host_speculation_variant": host_spec,
         "decode_loop_growing_cache": decode_loop,
         "roofline": {"kernel": "partial-K scan + max + threshold + compaction", "bound": "hbm",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

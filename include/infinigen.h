@@ -275,6 +275,23 @@ int ig_speculate_indexed(ig_ctx *ctx, const ig_desc *desc, const void *x, const 
                          int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, float *scores_opt,
                          void *stream);
 
+/* Speculation on the CPU with the partial key cache in host memory (Section 6.2 "Memory
+ * Consumption": the partial key cache is placed in the CPU and the speculation is performed there
+ * after fetching the partial query from the GPU).  The GPU computes the partial query as usual
+ * (ig_project) and the caller copies it to the host; this call, synchronous and on host threads,
+ * does the rest of ig_speculate: scores, per-head maximum, (max - alpha) threshold, ascending lists.
+ * q_p: host float32 [B, H, r], unscaled, as ig_project writes it.  slab_host: host memory holding a
+ * partial key cache in the library's layout, i.e. ig_slab_bytes(desc) bytes that ig_slab_build wrote
+ * on the device and the caller copied to the host (the GPU then no longer needs its copy).
+ * sel_idx: host int32 [B*H, sel_stride], sel_cnt: host int32 [B*H]; scores_opt: NULL or host float32
+ * [B, H, N].  threads: host threads to use (0 = all the host reports, at most 64).  Same arithmetic
+ * in the same order as the GPU scan, so for the same q_p the scores and lists are those of
+ * ig_scan_select bit for bit.  A list longer than sel_stride is clamped and the call returns
+ * IG_ECAPACITY.  ctx may be NULL (no message is kept then); no GPU call is made. */
+int ig_speculate_host(ig_ctx *ctx, const ig_desc *desc, const float *q_p, const void *slab_host,
+                      int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, float *scores_opt,
+                      int threads);
+
 /* Head-equalised selection (Section 4.3 "Decoding Stage", closing sentences; Section 5.1 "Key
  * Metric"): every head of a sequence keeps the same number of tokens,
  *   n_b = max(1, min(floor(sum_h thr_cnt[b,h] / H), floor(max_frac * N))),

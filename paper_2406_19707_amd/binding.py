@@ -17,7 +17,7 @@ __all__ = [
     "IG_ENOMEM", "IG_F32", "IG_F16", "IG_MEM_DEVICE", "IG_MEM_HOST_PINNED", "IG_POLICY_COUNTER", "IG_POLICY_FIFO", "IG_POLICY_LRU", "IG_K_PROJECT",
     "IG_K_FINALIZE", "IG_K_SCAN", "IG_K_SELECT", "IG_K_GATHER", "IG_K_ATTENTION", "IG_K_BUILD",
     "IG_K_COPY", "IG_K_READ", "IG_K_LAYER", "IgDesc", "IgError", "Context", "lib", "lib_path", "ig_skew_offline",
-    "ig_partial_index", "ig_apply_skew", "ig_rope_rows", "ig_wq_bytes", "ig_slab_bytes", "EXPORTS",
+    "ig_partial_index", "ig_apply_skew", "ig_rope_rows", "ig_speculate_host", "ig_wq_bytes", "ig_slab_bytes", "EXPORTS",
 ]
 
 IG_OK, IG_EINVAL, IG_ESHAPE, IG_EDTYPE, IG_ECAPACITY, IG_EHIP, IG_ENOCONV, IG_ENOMEM = range(8)
@@ -35,7 +35,7 @@ EXPORTS = [
     "ig_slab_build", "ig_append_token",
     "ig_pool_touch", "ig_pool_victim", "ig_pool_replace", "ig_pool_touch_policy", "ig_pool_replace_policy",
     "ig_speculate", "ig_project", "ig_scan_select", "ig_project_indexed", "ig_speculate_indexed",
-    "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention", "ig_sparse_attention_static",
+    "ig_speculate_host", "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention", "ig_sparse_attention_static",
     "ig_sparse_attention_indexed", "ig_gather_attention", "ig_layer_step", "ig_set_wait_limit", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
     "ig_copy_bytes", "ig_read_bytes",
 ]
@@ -109,6 +109,7 @@ def lib():
             "ig_project_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp]),
             "ig_speculate_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
             "ig_layer_step": (ctypes.c_int, [_vp, _dp] + [_vp] * 13 + [_i32] + [_vp] * 6),
+            "ig_speculate_host": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _i32, _vp, _vp, ctypes.c_int]),
             "ig_equalize_heads": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_double, _vp, _i32, _vp, _vp]),
             "ig_gather_kv": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_int, _vp, _i32, _vp, _vp, _vp, _vp]),
             "ig_sparse_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
@@ -203,6 +204,23 @@ def ig_rope_rows(q, pos, theta=10000.0, ctx=None):
     if rc != IG_OK:
         raise IgError(rc, ctx.last_error() if ctx else "ig_rope_rows")
     return q
+
+
+def ig_speculate_host(desc, q_p, slab_host, sel_stride=None, want_scores=False, threads=0, ctx=None):
+    """Host call (Section 6.2: speculation on the CPU, partial key cache in host memory).
+    q_p: numpy float32 [B,H,r]; slab_host: numpy uint8 / pinned torch tensor holding the slab bytes.
+    Returns (sel_idx [B*H, stride] int32, sel_cnt [B*H] int32, scores or None, status)."""
+    q_p = _host_f32(q_p)
+    BH = desc.B * desc.H
+    stride = desc.N if sel_stride is None else sel_stride
+    sel_idx = np.full((BH, stride), -1, np.int32)
+    sel_cnt = np.zeros(BH, np.int32)
+    scores = np.zeros((desc.B, desc.H, desc.N), np.float32) if want_scores else None
+    rc = lib().ig_speculate_host(ctx._h if ctx else None, ctypes.byref(desc), _ptr(q_p), _ptr(slab_host),
+                                 _ptr(sel_idx), stride, _ptr(sel_cnt), _ptr(scores), threads)
+    if rc not in (IG_OK, IG_ECAPACITY):
+        raise IgError(rc, ctx.last_error() if ctx else "ig_speculate_host")
+    return sel_idx, sel_cnt, scores, rc
 
 
 def ig_partial_index(Qs, Ks, H, ratio, ctx=None):

@@ -183,3 +183,143 @@ extern "C" int ig_rope_rows(ig_ctx *ctx, int n, int H, int d, const int32_t *pos
     }
   return IG_OK;
 }
+
+// ---- speculation on the CPU with the partial key cache in host memory ---------------------------
+// Section 6.2 "Memory Consumption" names this as a way to take the partial key cache off the GPU:
+// the partial query is computed on the GPU as usual and fetched; scan, maximum, threshold and the
+// index lists are worked out on the host, over a host copy of the partial key cache in the same
+// tiled channel-plane layout the GPU scan reads (a slab built by ig_slab_build and copied to host
+// memory is valid input).  The arithmetic is that of the GPU scan, in the same order: the query
+// entry is scaled first, a token's score is accumulated channel by channel with fused
+// multiply-adds in float32, so for the same partial query the scores and the lists are the same
+// bit for bit.  (sequence, head) pairs are spread over host threads.
+#include <thread>
+
+namespace {
+
+inline float half_bits_to_float(uint16_t h) {
+  const uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+  uint32_t exp = (h >> 10) & 0x1fu, man = h & 0x3ffu;
+  uint32_t bits;
+  if (exp == 0) {
+    if (man == 0) {
+      bits = sign;
+    } else {                                  // subnormal half: normalise
+      int e = -1;
+      do { ++e; man <<= 1; } while (!(man & 0x400u));
+      bits = sign | ((uint32_t)(127 - 15 - e) << 23) | ((man & 0x3ffu) << 13);
+    }
+  } else if (exp == 31) {
+    bits = sign | 0x7f800000u | (man << 13);
+  } else {
+    bits = sign | ((exp + 127 - 15) << 23) | (man << 13);
+  }
+  float f;
+  memcpy(&f, &bits, 4);
+  return f;
+}
+
+// scores of tokens [t0, t1) of one (b,h): s[t] = sum_j float(K[t, j]) * (q_p[j] * scale), in channel
+// order with fused multiply-adds
+template <typename E>
+void scan_range(const E *pair, int t0, int t1, int tile, int r, const float *qs, float *s) {
+  for (int t = t0; t < t1; ++t) {
+    const E *col = pair + (size_t)(t / tile) * r * tile + t % tile;
+    float acc = 0.f;
+    for (int j = 0; j < r; ++j) {
+      float k;
+      if (sizeof(E) == 2) k = half_bits_to_float((uint16_t)col[(size_t)j * tile]);
+      else memcpy(&k, &col[(size_t)j * tile], 4);
+      acc = fmaf(k, qs[j], acc);
+    }
+    s[t] = acc;
+  }
+}
+
+#if defined(__x86_64__)
+#include <immintrin.h>
+// the same sums for n64 whole groups of 64 tokens (F16C conversion, FMA; 64 tokens stay in 8
+// registers over all channels): identical results, lane by lane
+__attribute__((target("avx2,f16c,fma")))
+void scan_groups_f16_avx2(const uint16_t *pair, int n64, int tile, int r, const float *qs, float *s) {
+  for (int g = 0; g < n64; ++g) {
+    const int t0 = g * 64;
+    const uint16_t *base = pair + (size_t)(t0 / tile) * r * tile + t0 % tile;
+    __m256 acc[8];
+    for (int u = 0; u < 8; ++u) acc[u] = _mm256_setzero_ps();
+    for (int j = 0; j < r; ++j) {
+      const uint16_t *p = base + (size_t)j * tile;
+      const __m256 q = _mm256_set1_ps(qs[j]);
+      for (int u = 0; u < 8; ++u)
+        acc[u] = _mm256_fmadd_ps(_mm256_cvtph_ps(_mm_loadu_si128((const __m128i *)(p + 8 * u))), q, acc[u]);
+    }
+    for (int u = 0; u < 8; ++u) _mm256_storeu_ps(s + t0 + 8 * u, acc[u]);
+  }
+}
+#endif
+
+}  // namespace
+
+extern "C" int ig_speculate_host(ig_ctx *ctx, const ig_desc *d, const float *q_p, const void *slab_host,
+                                 int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
+                                 float *scores_opt, int threads) {
+  if (!d) return ig_fail(ctx, IG_EINVAL, "descriptor is NULL");
+  if (d->dtype != IG_F32 && d->dtype != IG_F16) return ig_fail(ctx, IG_EDTYPE, "unknown dtype %d", d->dtype);
+  if (d->B < 1 || d->H < 1 || d->r < 1 || d->N < 1 || d->N_cap < d->N)
+    return ig_fail(ctx, IG_ESHAPE, "ig_speculate_host: bad shape");
+  if (!(d->alpha >= 0.0f)) return ig_fail(ctx, IG_EINVAL, "alpha must be >= 0");
+  if (!q_p || !slab_host || !sel_idx || !sel_cnt) return ig_fail(ctx, IG_EINVAL, "ig_speculate_host: NULL argument");
+  if (sel_stride < 1) return ig_fail(ctx, IG_ESHAPE, "sel_stride = %d", sel_stride);
+  const int tile = d->dtype == IG_F16 ? 512 : 256;
+  const int nTiles = (d->N_cap + tile - 1) / tile;
+  const int BH = d->B * d->H, r = d->r, N = d->N;
+  int nthreads = threads > 0 ? threads : (int)std::thread::hardware_concurrency();
+  nthreads = std::max(1, std::min(nthreads, std::min(BH, 64)));
+#if defined(__x86_64__)
+  const bool simd = d->dtype == IG_F16 && __builtin_cpu_supports("avx2") && __builtin_cpu_supports("f16c") &&
+                    __builtin_cpu_supports("fma");
+#else
+  const bool simd = false;
+#endif
+  std::vector<int> clamped(nthreads, 0);
+  auto work = [&](int tid) {
+    std::vector<float> s((size_t)N), qs(r);
+    for (int bh = tid; bh < BH; bh += nthreads) {
+      for (int j = 0; j < r; ++j) qs[j] = q_p[(size_t)bh * r + j] * d->scale;
+      const size_t pair_off = (size_t)bh * nTiles * r * tile;
+      if (d->dtype == IG_F16) {
+        const uint16_t *pair = static_cast<const uint16_t *>(slab_host) + pair_off;
+        int done = 0;                          // whole groups of 64 tokens go through the vector loop
+#if defined(__x86_64__)
+        if (simd) {
+          scan_groups_f16_avx2(pair, N / 64, tile, r, qs.data(), s.data());
+          done = N / 64 * 64;
+        }
+#endif
+        scan_range<uint16_t>(pair, done, N, tile, r, qs.data(), s.data());
+      } else {
+        scan_range<uint32_t>(static_cast<const uint32_t *>(slab_host) + pair_off, 0, N, tile, r, qs.data(), s.data());
+      }
+      if (scores_opt) memcpy(scores_opt + (size_t)bh * N, s.data(), sizeof(float) * N);
+      float m = -INFINITY;
+      for (int t = 0; t < N; ++t) m = s[t] > m ? s[t] : m;
+      const float thr = m - d->alpha;
+      int n = 0;
+      int32_t *list = sel_idx + (size_t)bh * sel_stride;
+      for (int t = 0; t < N; ++t)
+        if (s[t] >= thr) {
+          if (n < sel_stride) list[n] = t;
+          ++n;
+        }
+      if (n > sel_stride) clamped[tid] = 1;
+      sel_cnt[bh] = std::min(n, (int)sel_stride);
+    }
+  };
+  std::vector<std::thread> pool;
+  for (int t = 1; t < nthreads; ++t) pool.emplace_back(work, t);
+  work(0);
+  for (auto &t : pool) t.join();
+  for (int c : clamped)
+    if (c) return ig_fail(ctx, IG_ECAPACITY, "a selected-token list was longer than sel_stride and was clamped");
+  return IG_OK;
+}

@@ -234,6 +234,40 @@ class Rehearsal:
             self.speculate(l)
             self.attend_indexed(l)
 
+    def host_speculation_setup(self, slab_layers: int = 4):
+        """Moves the partial key cache of `slab_layers` layers to host memory (later layers reuse
+        them in turn) and allocates the pinned staging buffers of step_host_speculation."""
+        w, BH = self.w, self.w.B * self.w.H
+        n = min(self.L, slab_layers)
+        self.slab_host = [self.slab[l].cpu().pin_memory() for l in range(n)]
+        self.q_p = torch.empty((w.B, w.H, self.r), device="cuda")
+        self.q_p_host = torch.empty((w.B, w.H, self.r), pin_memory=True)
+        self.sel_idx_host = torch.zeros((BH, self.stride), dtype=torch.int32, pin_memory=True)
+        self.sel_cnt_host = torch.zeros((BH,), dtype=torch.int32, pin_memory=True)
+
+    def step_host_speculation(self, threads: int = 0, after_layer=None):
+        """Decode step with the partial key cache in host memory and the speculation on the CPU
+        (Section 6.2 "Memory Consumption"): per layer the GPU projects the partial query, the host
+        fetches it, scans its copy of the partial key cache and builds the lists, the lists go back
+        and the GPU prefetches and attends as usual."""
+        for l in range(self.L):
+            self.ctx.ig_project(self.desc, self.x[l], self.wq, None, self.A_p, self.pos, self.q_p)
+            self.q_p_host.copy_(self.q_p, non_blocking=True)
+            torch.cuda.current_stream().synchronize()
+            rc = ig.lib().ig_speculate_host(self.ctx._h, ig.ctypes.byref(self.desc), self.q_p_host.data_ptr(),
+                                            self.slab_host[l % len(self.slab_host)].data_ptr(),
+                                            self.sel_idx_host.data_ptr(), self.stride,
+                                            self.sel_cnt_host.data_ptr(), None, threads)
+            if rc != ig.IG_OK:
+                raise ig.IgError(rc, self.ctx.last_error())
+            self.sel_idx.copy_(self.sel_idx_host, non_blocking=True)
+            self.sel_cnt.copy_(self.sel_cnt_host, non_blocking=True)
+            self.gather(l)
+            self.attend(l)
+            if after_layer is not None:
+                torch.cuda.current_stream().synchronize()
+                after_layer(l)
+
     def step_overlapped(self, after_layer=None):
         """Host-pool decode step (Fig. 3(d)): the rows of layer l are prefetched over PCIe on a side
         stream while the main stream already rehearses layer l+1 and attends layer l-1.

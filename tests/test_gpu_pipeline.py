@@ -143,3 +143,43 @@ def test_decode_loop_matches_oracle_at_every_length(cfg, B, H, N, host, dense_fi
             assert np.all(ref.sel_cnt == N + s)
         check_against_oracle(R, snap, ref, alpha)
     ctx.close()
+
+
+@pytest.mark.parametrize("cfg,B,H,N,L,gain", [
+    (2, 2, 8, 2500, 3, 12.0),      # HBM pool, folded skew
+    (5, 1, 8, 6000, 3, 30.0),      # rotary query, pinned host pool
+])
+def test_host_speculation_step_matches_device_step_and_oracle(cfg, B, H, N, L, gain):
+    """Section 6.2: partial key cache in host memory, speculation on the CPU.  Same lists, rows and
+    attention output as the all-GPU layer, bit for bit, and both against the oracle."""
+    import paper_2406_19707_amd as ig
+    from paper_2406_19707_amd.pipeline import Rehearsal
+    w = wl.shrink(wl.WORKLOADS[cfg], B=B, H=H, N=N, n_cal=256, heavy_count=16)
+    ctx = ig.Context(0)
+    R = Rehearsal(ctx, w, gain=gain, layers=L, host_layers=L)
+    serial = []
+    for l in range(L):
+        R._use(0)
+        R.layer(l)
+        torch.cuda.synchronize()
+        serial.append(snapshot(R))
+    R.host_speculation_setup(slab_layers=L)
+    for st in R.sets:
+        for t in st.values():
+            t.fill_(-1 if t.dtype == torch.int32 else 7)
+    R._use(0)
+    hosted = {}
+    R.step_host_speculation(threads=4, after_layer=lambda l: hosted.__setitem__(l, snapshot(R)))
+    torch.cuda.synchronize()
+    assert ctx.ig_check_status() == ig.IG_OK
+    for l in range(L):
+        n = serial[l]["sel_cnt"]
+        assert torch.equal(hosted[l]["sel_cnt"], n), l
+        assert torch.equal(hosted[l]["out"], serial[l]["out"]), l
+        for i in range(w.B * w.H):
+            k = int(n[i])
+            assert torch.equal(hosted[l]["sel_idx"][i, :k], serial[l]["sel_idx"][i, :k])
+            assert torch.equal(hosted[l]["K_sel"][i, :k], serial[l]["K_sel"][i, :k])
+        ref = oracle_layer(R, l, w.N, w.alpha)
+        check_against_oracle(R, hosted[l], ref, w.alpha)
+    ctx.close()
