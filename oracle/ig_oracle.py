@@ -19,8 +19,22 @@ _lib = None
 OK, EINVAL, ENOCONV, ENOMEM = 0, 1, 2, 3
 
 
+def build_sanitized(out_dir: str, cc: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer, built with `cc` (the
+    clang that builds the library under test, so that one sanitizer runtime serves both)."""
+    os.makedirs(out_dir, exist_ok=True)
+    lib = os.path.join(out_dir, "libig_oracle.so")
+    subprocess.check_call([cc, "-O1", "-g", "-std=c11", "-fPIC", "-shared", "-Wall", "-fsanitize=address",
+                           "-fsanitize=undefined", "-fno-sanitize-recover=undefined", "-shared-libsan",
+                           "-o", lib, _SRC, "-lm"])
+    return lib
+
+
 def build(force: bool = False) -> str:
-    """Compile the oracle with gcc (single-threaded, no fast-math)."""
+    """Compile the oracle with gcc (single-threaded, no fast-math).  IG_ORACLE_LIBRARY names an
+    already built copy to load instead (the sanitized one)."""
+    if os.environ.get("IG_ORACLE_LIBRARY"):
+        return os.environ["IG_ORACLE_LIBRARY"]
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-o", _LIB,
                                _SRC, "-lm"])

@@ -60,6 +60,10 @@ class IgError(RuntimeError):
 
 
 def lib_path() -> str:
+    """The built library beside this file; IG_LIBRARY names another build of it (the host-sanitized
+    one of the CPU test suite)."""
+    if os.environ.get("IG_LIBRARY"):
+        return os.environ["IG_LIBRARY"]
     return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libinfinigen_hip.so")
 
 
