@@ -385,22 +385,24 @@ __device__ __forceinline__ void rescan_pair(const ScanArgs &a, int bh, float q_l
 // -- the arithmetic of the stand-alone finalisation kernel.  Loads return to a wave in the order
 // it issued them, so everything the prologue reads (partial sums, position, the thread's rows of
 // A_p) is issued by rope_issue BEFORE the wave's slab window; rope_finish then runs while the window
-// is still travelling.  Heads of up to 256 columns, at most ROPE_PF rows of A_p per thread.
-constexpr int ROPE_PF = 24;
+// is still travelling.  Heads of up to 256 columns; a thread prefetches rope_pf(r) rows of A_p, the
+// share of a 128-column head when 256 threads are split into groups of r.
+constexpr int rope_pf(int r) { return (128 + 256 / r - 1) / (256 / r); }
 struct RopeArgs {
   const float *A_p;     // [H, d, r]
   const int32_t *pos;   // [B]
   int d;
   double freq_step;     // -(2/d) log2(theta)
 };
+template <int PF>
 struct RopeLoads {
   float part[IG_KS_MAX];
   float bias;
-  float apf[ROPE_PF];
+  float apf[PF];
   int position;
 };
-template <int THREADS>
-__device__ __forceinline__ void rope_issue(const ScanArgs &a, const RopeArgs &ra, int b, int h, RopeLoads &L) {
+template <int THREADS, int PF>
+__device__ __forceinline__ void rope_issue(const ScanArgs &a, const RopeArgs &ra, int b, int h, RopeLoads<PF> &L) {
   // straight-line code, every load unconditional (addresses clamped, surplus values discarded
   // later): the compiler can then count exactly how many loads may still be outstanding at each
   // use, instead of waiting for all of them -- the slab window included -- after a branch
@@ -415,10 +417,10 @@ __device__ __forceinline__ void rope_issue(const ScanArgs &a, const RopeArgs &ra
   const int c0 = min(d, g * per);
   const float *ap = ra.A_p + (long)h * d * r + k;
 #pragma unroll
-  for (int i = 0; i < ROPE_PF; ++i) L.apf[i] = ap[(long)min(c0 + i, d - 1) * r];
+  for (int i = 0; i < PF; ++i) L.apf[i] = ap[(long)min(c0 + i, d - 1) * r];
 }
-template <int THREADS>
-__device__ __forceinline__ void rope_finish(const ScanArgs &a, const RopeArgs &ra, const RopeLoads &L,
+template <int THREADS, int PF>
+__device__ __forceinline__ void rope_finish(const ScanArgs &a, const RopeArgs &ra, const RopeLoads<PF> &L,
                                             float *q_lds, float *qr_lds, float *psum, float *qp_lds) {
   const int t = threadIdx.x, d = ra.d, r = a.r;
   {
@@ -442,7 +444,7 @@ __device__ __forceinline__ void rope_finish(const ScanArgs &a, const RopeArgs &r
   const int c0 = g < G ? min(d, g * per) : d, c1 = g < G ? min(d, (g + 1) * per) : d;
   float acc = 0.f;
 #pragma unroll
-  for (int i = 0; i < ROPE_PF; ++i)
+  for (int i = 0; i < PF; ++i)
     if (c0 + i < c1) acc = fmaf(qr_lds[c0 + i], L.apf[i], acc);
   psum[t] = acc;
   __syncthreads();
@@ -457,7 +459,7 @@ __device__ __forceinline__ void rope_finish(const ScanArgs &a, const RopeArgs &r
 static inline bool rope_prologue_fits(int threads, int d, int r) {
   if (d > threads || d > 256 || r > threads) return false;
   const int G = threads / r;
-  return (d + G - 1) / G <= ROPE_PF;
+  return (d + G - 1) / G <= rope_pf(r);
 }
 
 template <typename T, int R, int NW, int TPW, int WIN, int MINW, bool ROPE>
@@ -489,8 +491,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, 
   vec v[WIN];
   // the query's own loads go out first, so that they head the wave's memory queue
   QueryLoads ql;
-  RopeLoads rl;
-  if constexpr (ROPE) rope_issue<NW * 64>(a, ra, b, h, rl);
+  RopeLoads<rope_pf(R)> rl;
+  if constexpr (ROPE) rope_issue<NW * 64, rope_pf(R)>(a, ra, b, h, rl);
   else query_issue(a, b, h, lane, 0, ql);
   __builtin_amdgcn_sched_barrier(0);
   // (unconditional, like the query's loads: a branch here would make the compiler wait for the
@@ -502,7 +504,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, 
   float q_lane;
   if constexpr (ROPE) {
     __shared__ float q_lds[256], qr_lds[256], psum[NW * 64], qp_lds[64];
-    rope_finish<NW * 64>(a, ra, rl, q_lds, qr_lds, psum, qp_lds);
+    rope_finish<NW * 64, rope_pf(R)>(a, ra, rl, q_lds, qr_lds, psum, qp_lds);
     q_lane = lane < R ? qp_lds[lane] * a.scale : 0.f;
   } else {
     q_lane = query_finish(a, ql);
@@ -673,7 +675,7 @@ int launch_stream_one(ig_ctx *ctx, const ScanArgs &a, const RopeArgs *ra, int BH
   dim3 grid((unsigned)(BH * S)), block(NW * 64);
   PairSync *sync = static_cast<PairSync *>(ctx->pair_sync);
   if (ra) {
-    auto k = scan_select_stream<T, R, NW, TPW, WIN, 4, true>;    // the prologue's loads need the registers
+    auto k = scan_select_stream<T, R, NW, TPW, WIN, MINW, true>;
     IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, *ra, S, sync, ctx->spin_limit);
   } else {
     auto k = scan_select_stream<T, R, NW, TPW, WIN, MINW, false>;
