@@ -61,6 +61,56 @@ def cpu_model() -> str:
     return "unknown"
 
 
+def scan_only(args, R, ctx, timed) -> dict:
+    """The rehearsal kernels alone (projection + partial key cache scan of every layer, back to
+    back) and plain reads of the same slabs: the short run the profiler summaries of the scan
+    kernel are taken from."""
+    import torch
+    import paper_2406_19707_amd as ig
+    L, K = R.L, args.steps
+
+    def spec():
+        for l in range(L):
+            R.speculate(l)
+
+    def read_slabs():
+        n = R.slab[0].numel()
+        for l in range(L):
+            ctx.ig_read_bytes(R.slab[l], n - n % 16)
+
+    for _ in range(args.warmup):
+        spec()
+        read_slabs()
+    torch.cuda.synchronize()
+    assert ctx.ig_check_status() == ig.IG_OK
+    loop_ms = timed(spec, K)
+    ctx.ig_profile_begin()
+    for _ in range(K):
+        spec()
+        read_slabs()
+    torch.cuda.synchronize()
+    ctx.ig_profile_end()
+    out = {}
+    for kid, name in ((ig.IG_K_PROJECT, "project"), (ig.IG_K_FINALIZE, "finalize"), (ig.IG_K_SCAN, "scan"),
+                      (ig.IG_K_SELECT, "select"), (ig.IG_K_READ, "read")):
+        ms, n = ctx.ig_profile_read(kid)
+        if n:
+            out[name] = {"avg_us": ms * 1e3 / n, "launches": n}
+    if args.copy_reference:
+        a_ = torch.zeros(1 << 28, dtype=torch.uint8, device="cuda")
+        b_ = torch.empty_like(a_)
+        for _ in range(3):
+            ctx.ig_copy_bytes(a_, b_, 1 << 28)
+        torch.cuda.synchronize()
+    sb = R.scan_bytes()
+    return {"workload": R.w.name, "mode": "rehearsal kernels only", "layers": L, "steps": K,
+            "kernels_by_hip_events": out, "speculate_loop_us_per_layer": loop_ms * 1e3 / L,
+            "scan_algorithmic_bytes": sb,
+            "scan_GBps": sb / (out["scan"]["avg_us"] * 1e-6) / 1e9,
+            "scan_frac_of_hbm_peak": sb / (out["scan"]["avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS,
+            "plain_read_GBps": R.slab[0].numel() / (out["read"]["avg_us"] * 1e-6) / 1e9}
+
+
 def run_workload(args) -> dict:
     import numpy as np
     import torch
@@ -86,6 +136,9 @@ def run_workload(args) -> dict:
             fn()
         torch.cuda.synchronize()
         return (time.perf_counter() - t) * 1e3 / steps
+
+    if args.scan_only:
+        return scan_only(args, R, ctx, timed)
 
     # ---- eager ----
     pcie = None
@@ -573,6 +626,8 @@ def main():
                     help="skip the side variants (literal, head-equalised, index-only, decode loop)")
     ap.add_argument("--layers", type=int, default=0, help="layers per step (0 = the model's)")
     ap.add_argument("--gain", type=float, default=0.0, help="logit gain (0 = the workload's calibrated one)")
+    ap.add_argument("--scan-only", action="store_true",
+                    help="with --workload N: only the rehearsal kernels and plain reads of the slabs (profiling runs)")
     ap.add_argument("--no-graph", action="store_true", help="time eager launches only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-literal", action="store_true", help="skip the gain-1 (select everything) variant")

@@ -463,7 +463,7 @@ static inline bool rope_prologue_fits(int threads, int d, int r) {
 }
 
 template <typename T, int R, int NW, int TPW, int WIN, int MINW, bool ROPE>
-__global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, RopeArgs ra, int S, PairSync *sync, long spin_limit) {
+__global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, RopeArgs ra, int S, int BH, PairSync *sync, long spin_limit) {
   constexpr int TPL = SlabElem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
   constexpr int NLOAD = TPW * R;              // 1 KiB loads of a wave with all its tiles valid
@@ -473,7 +473,16 @@ __global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, 
   __shared__ int lds_flag[2];
   __shared__ int32_t stage[NW * TPW * TILE];
   __shared__ float lds_gmax;
-  const int bh = blockIdx.x / S, s = blockIdx.x - bh * S;
+  // Workgroup -> (pair, split): groups of 8 pairs take 8*S consecutive ids, split-major inside the
+  // group (id = group*8*S + split*8 + pair%8).  Workgroups are handed to the 8 XCDs round-robin by
+  // id, so the S workgroups of a pair land on one XCD and what they all read besides the slab (the
+  // projection's partial sums; for rotary models the head's columns of the skewing matrix) is
+  // fetched into that XCD's L2 once instead of S times, while a pair's workgroups still start
+  // within 8*S ids of each other.  (Only where bytes are fetched from changes with the hardware's
+  // dispatch order, not the result.)
+  const int grp = blockIdx.x / (8 * S), rem = blockIdx.x - grp * 8 * S;
+  const int s = rem >> 3, bh = grp * 8 + (rem & 7);
+  if (bh >= BH) return;                                   // the grid is rounded up to whole groups
   const int b = bh / a.H, h = bh - b * a.H;
   const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int tile0 = s * (NW * TPW);                       // first tile of this workgroup
@@ -672,14 +681,14 @@ int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
 // to 96 so that five workgroups share a compute unit (one tile or two per wave) or to 128 (four)
 template <typename T, int R, int NW, int TPW, int WIN, int MINW>
 int launch_stream_one(ig_ctx *ctx, const ScanArgs &a, const RopeArgs *ra, int BH, int S, hipStream_t s) {
-  dim3 grid((unsigned)(BH * S)), block(NW * 64);
+  dim3 grid((unsigned)((BH + 7) / 8 * 8 * S)), block(NW * 64);
   PairSync *sync = static_cast<PairSync *>(ctx->pair_sync);
   if (ra) {
     auto k = scan_select_stream<T, R, NW, TPW, WIN, MINW, true>;
-    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, *ra, S, sync, ctx->spin_limit);
+    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, *ra, S, BH, sync, ctx->spin_limit);
   } else {
     auto k = scan_select_stream<T, R, NW, TPW, WIN, MINW, false>;
-    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, RopeArgs{}, S, sync, ctx->spin_limit);
+    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, RopeArgs{}, S, BH, sync, ctx->spin_limit);
   }
   return IG_OK;
 }
