@@ -25,6 +25,15 @@ int ig_hip_fail(ig_ctx *ctx, hipError_t e, const char *what) {
 
 int ig_ensure(ig_ctx *ctx, void **p, size_t *have, size_t need) {
   if (*have >= need && *p) return IG_OK;
+  // Growing means hipMalloc, and for a buffer in use also a device-wide wait and a hipFree: none of
+  // them may happen while the call's stream is being captured into a graph (the runtime would
+  // invalidate the capture, and a replay would use the freed buffer).  Refuse instead.
+  if (ctx->call_stream) {
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(ctx->call_stream, &st) == hipSuccess && st != hipStreamCaptureStatusNone)
+      return ig_fail(ctx, IG_EINVAL, "a workspace of %zu bytes would have to be allocated while the stream is being "
+                     "captured: call ig_reserve for the largest shape before the capture", need);
+  }
   if (*p) {
     IG_HIP(ctx, hipDeviceSynchronize());   // earlier launches may still read the old buffer
     IG_HIP(ctx, hipFree(*p));
@@ -81,6 +90,12 @@ int check_desc(ig_ctx *ctx, const ig_desc *d) {
     return ig_fail(ctx, IG_EINVAL, "rope needs an even d and a positive base");
   if ((long)d->B * d->H > 2147483647L / 4) return ig_fail(ctx, IG_ESHAPE, "B*H too large");
   return IG_OK;
+}
+
+// the same for a call that enqueues on `stream`; remembers the stream for ig_ensure's capture check
+int check_desc(ig_ctx *ctx, const ig_desc *d, void *stream) {
+  if (ctx) ctx->call_stream = (hipStream_t)stream;
+  return check_desc(ctx, d);
 }
 
 // the kernels read rows, queries and inputs in 16-byte units
@@ -221,6 +236,7 @@ const char *ig_last_error(const ig_ctx *ctx) { return ctx ? ctx->err : "context 
 
 int ig_reserve(ig_ctx *ctx, const ig_desc *desc) {
   int rc = check_desc(ctx, desc);
+  if (ctx) ctx->call_stream = nullptr;       // not a stream call: ig_reserve may allocate
   if (rc) return rc;
   if ((rc = set_device(ctx))) return rc;
   return reserve_for(ctx, desc, true);
@@ -256,7 +272,7 @@ size_t ig_wq_bytes(const ig_desc *d) {
 
 int ig_wq_build(ig_ctx *ctx, const ig_desc *d, const void *Wq, const int32_t *idx_dev, void *wq,
                 void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!Wq || !wq || (!d->rope && !idx_dev)) return ig_fail(ctx, IG_EINVAL, "ig_wq_build: NULL argument");
   if ((uintptr_t)wq % 16) return ig_fail(ctx, IG_EINVAL, "ig_wq_build: wq must be 16-byte aligned");
@@ -267,6 +283,7 @@ int ig_wq_build(ig_ctx *ctx, const ig_desc *d, const void *Wq, const int32_t *id
 int ig_skew_device(ig_ctx *ctx, int D, int H, int n_cal, const float *Qcal, float *A, float *sigma,
                    void *stream) {
   if (!ctx) return IG_EINVAL;
+  ctx->call_stream = (hipStream_t)stream;
   if (D < 1 || H < 1 || D % H || n_cal < 1) return ig_fail(ctx, IG_ESHAPE, "ig_skew_device: bad shape");
   const int d = D / H;
   if (d % 2 || d > 256) return ig_fail(ctx, IG_ESHAPE, "ig_skew_device: d = %d must be even and at most 256", d);
@@ -280,6 +297,7 @@ int ig_skew_device(ig_ctx *ctx, int D, int H, int n_cal, const float *Qcal, floa
 int ig_partial_index_device(ig_ctx *ctx, int dtype, int H, int d, int n, const void *Qs,
                             const void *Ks, double ratio, int32_t *idx_dev, void *stream) {
   if (!ctx) return IG_EINVAL;
+  ctx->call_stream = (hipStream_t)stream;
   if (dtype != IG_F32 && dtype != IG_F16) return ig_fail(ctx, IG_EDTYPE, "unknown dtype %d", dtype);
   if (H < 1 || d < 1 || n < 1) return ig_fail(ctx, IG_ESHAPE, "ig_partial_index_device: bad shape");
   if (d > 256) return ig_fail(ctx, IG_ESHAPE, "ig_partial_index_device: d = %d exceeds 256", d);
@@ -303,7 +321,7 @@ size_t ig_slab_bytes(const ig_desc *d) {
 
 int ig_slab_build(ig_ctx *ctx, const ig_desc *d, const void *Kpool, int pool_space,
                   const int32_t *idx_dev, void *slab, void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!Kpool || !idx_dev || !slab) return ig_fail(ctx, IG_EINVAL, "ig_slab_build: NULL argument");
   if ((rc = check_aligned(ctx, "ig_slab_build", {Kpool}))) return rc;
@@ -319,6 +337,7 @@ int ig_append_token(ig_ctx *ctx, const ig_desc *d, const void *k_new, const void
                     void *stream) {
   // the descriptor describes the cache before the append: N valid tokens, the new one goes to slot N
   if (!ctx) return IG_EINVAL;
+  ctx->call_stream = (hipStream_t)stream;
   if (!d) return ig_fail(ctx, IG_EINVAL, "descriptor is NULL");
   if (d->N == 0 && d->N_cap >= 1) {          // appending to an empty cache is allowed
     ig_desc one = *d;
@@ -345,7 +364,7 @@ int ig_append_token(ig_ctx *ctx, const ig_desc *d, const void *k_new, const void
 
 int ig_pool_touch(ig_ctx *ctx, const ig_desc *d, const int32_t *sel_idx, int32_t sel_stride,
                   const int32_t *sel_cnt, int32_t *counters, int32_t counter_max, void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!counters) return ig_fail(ctx, IG_EINVAL, "ig_pool_touch: counters is NULL");
   if (counter_max < 1) return ig_fail(ctx, IG_EINVAL, "counter_max = %d", counter_max);
@@ -357,7 +376,7 @@ int ig_pool_touch(ig_ctx *ctx, const ig_desc *d, const int32_t *sel_idx, int32_t
 
 int ig_pool_victim(ig_ctx *ctx, const ig_desc *d, const int32_t *counters, int32_t *victim,
                    void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!counters || !victim) return ig_fail(ctx, IG_EINVAL, "ig_pool_victim: NULL argument");
   if ((rc = set_device(ctx))) return rc;
@@ -367,7 +386,7 @@ int ig_pool_victim(ig_ctx *ctx, const ig_desc *d, const int32_t *counters, int32
 int ig_pool_replace(ig_ctx *ctx, const ig_desc *d, const int32_t *victim, const void *k_new,
                     const void *v_new, const int32_t *idx_dev, void *slab, void *Kpool, void *Vpool,
                     int pool_space, int32_t *counters, void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!victim || !k_new || !v_new || !idx_dev || !slab || !Kpool || !Vpool)
     return ig_fail(ctx, IG_EINVAL, "ig_pool_replace: NULL argument");
@@ -386,7 +405,7 @@ int ig_pool_touch_policy(ig_ctx *ctx, const ig_desc *d, int policy, const int32_
                          void *stream) {
   if (policy == IG_POLICY_COUNTER)
     return ig_pool_touch(ctx, d, sel_idx, sel_stride, sel_cnt, state, param, stream);
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (policy != IG_POLICY_FIFO && policy != IG_POLICY_LRU) return ig_fail(ctx, IG_EINVAL, "unknown pool policy %d", policy);
   if (!state) return ig_fail(ctx, IG_EINVAL, "ig_pool_touch_policy: state is NULL");
@@ -400,7 +419,7 @@ int ig_pool_replace_policy(ig_ctx *ctx, const ig_desc *d, int policy, const int3
                            const void *k_new, const void *v_new, const int32_t *idx_dev, void *slab,
                            void *Kpool, void *Vpool, int pool_space, int32_t *state, int32_t now,
                            void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (policy != IG_POLICY_COUNTER && policy != IG_POLICY_FIFO && policy != IG_POLICY_LRU)
     return ig_fail(ctx, IG_EINVAL, "unknown pool policy %d", policy);
@@ -431,7 +450,7 @@ static int project_partials(ig_ctx *ctx, const ig_desc *d, const void *x, const 
 
 int ig_project(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, const float *bias,
                const float *A_p, const int32_t *pos, float *q_p, void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!q_p) return ig_fail(ctx, IG_EINVAL, "q_p is NULL");
   ProjGeom g;
@@ -461,7 +480,7 @@ static int project_columns_partials(ig_ctx *ctx, const ig_desc *d, const void *x
 
 int ig_project_indexed(ig_ctx *ctx, const ig_desc *d, const void *x, const void *Wq,
                        const int32_t *idx_dev, const float *bias, float *q_p, void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!q_p) return ig_fail(ctx, IG_EINVAL, "q_p is NULL");
   ProjGeom g;
@@ -475,7 +494,7 @@ int ig_speculate_indexed(ig_ctx *ctx, const ig_desc *d, const void *x, const voi
                          const int32_t *idx_dev, const float *bias, const void *slab,
                          int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, float *scores_opt,
                          void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!slab) return ig_fail(ctx, IG_EINVAL, "slab is NULL");
   if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
@@ -490,7 +509,7 @@ int ig_speculate_indexed(ig_ctx *ctx, const ig_desc *d, const void *x, const voi
 int ig_scan_select(ig_ctx *ctx, const ig_desc *d, const float *q_p, const void *slab,
                    int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, float *scores_opt,
                    void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!q_p || !slab) return ig_fail(ctx, IG_EINVAL, "q_p or slab is NULL");
   if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
@@ -503,7 +522,7 @@ int ig_scan_select(ig_ctx *ctx, const ig_desc *d, const float *q_p, const void *
 int ig_speculate(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, const float *bias,
                  const float *A_p, const int32_t *pos, const void *slab, int32_t *sel_idx,
                  int32_t sel_stride, int32_t *sel_cnt, float *scores_opt, void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!slab) return ig_fail(ctx, IG_EINVAL, "slab is NULL");
   if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
@@ -530,7 +549,7 @@ int ig_speculate(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, c
 int ig_equalize_heads(ig_ctx *ctx, const ig_desc *d, const float *scores, const int32_t *thr_cnt,
                       double max_frac, int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
                       void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!scores || !thr_cnt) return ig_fail(ctx, IG_EINVAL, "ig_equalize_heads: NULL argument");
   if (!(max_frac > 0.0) || max_frac > 1.0)
@@ -547,7 +566,7 @@ int ig_equalize_heads(ig_ctx *ctx, const ig_desc *d, const float *scores, const 
 int ig_gather_kv(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const void *Vpool, int pool_space,
                  const int32_t *sel_idx, int32_t sel_stride, const int32_t *sel_cnt, void *K_sel,
                  void *V_sel, void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!Kpool || !Vpool || !K_sel || !V_sel) return ig_fail(ctx, IG_EINVAL, "ig_gather_kv: NULL argument");
   if ((rc = check_aligned(ctx, "ig_gather_kv", {Kpool, Vpool, K_sel, V_sel}))) return rc;
@@ -563,7 +582,7 @@ int ig_gather_kv(ig_ctx *ctx, const ig_desc *d, const void *Kpool, const void *V
 int ig_sparse_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K_sel,
                         const void *V_sel, const int32_t *sel_cnt, int32_t sel_stride,
                         const void *k_new, const void *v_new, void *out, void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!q || !K_sel || !V_sel || !sel_cnt || !out) return ig_fail(ctx, IG_EINVAL, "ig_sparse_attention: NULL argument");
   if ((rc = check_aligned(ctx, "ig_sparse_attention", {q, K_sel, V_sel, k_new, v_new}))) return rc;
@@ -577,7 +596,7 @@ int ig_sparse_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
 int ig_sparse_attention_static(ig_ctx *ctx, const ig_desc *d, const void *q, const void *K_sel,
                                const void *V_sel, const int32_t *sel_cnt, int32_t sel_stride,
                                const void *k_new, const void *v_new, void *out, void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!q || !K_sel || !V_sel || !sel_cnt || !out)
     return ig_fail(ctx, IG_EINVAL, "ig_sparse_attention_static: NULL argument");
@@ -593,7 +612,7 @@ int ig_sparse_attention_indexed(ig_ctx *ctx, const ig_desc *d, const void *q, co
                                 const void *Vpool, const int32_t *sel_idx, int32_t sel_stride,
                                 const int32_t *sel_cnt, const void *k_new, const void *v_new,
                                 void *out, void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!q || !Kpool || !Vpool || !out) return ig_fail(ctx, IG_EINVAL, "ig_sparse_attention_indexed: NULL argument");
   if ((rc = check_aligned(ctx, "ig_sparse_attention_indexed", {q, Kpool, Vpool, k_new, v_new}))) return rc;
@@ -608,7 +627,7 @@ int ig_gather_attention(ig_ctx *ctx, const ig_desc *d, const void *q, const void
                         const void *Vpool, const int32_t *sel_idx, int32_t sel_stride,
                         const int32_t *sel_cnt, void *K_sel, void *V_sel, const void *k_new,
                         const void *v_new, void *out, void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!q || !Kpool || !Vpool || !K_sel || !V_sel || !out)
     return ig_fail(ctx, IG_EINVAL, "ig_gather_attention: NULL argument");
@@ -625,7 +644,7 @@ int ig_layer_step(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, 
                   int32_t *sel_cnt_next, const void *q, const void *Kpool, const void *Vpool,
                   const int32_t *sel_idx, const int32_t *sel_cnt, int32_t sel_stride, void *K_sel,
                   void *V_sel, const void *k_new, const void *v_new, void *out, void *stream) {
-  int rc = check_desc(ctx, d);
+  int rc = check_desc(ctx, d, stream);
   if (rc) return rc;
   if (!slab || !q || !Kpool || !Vpool || !K_sel || !V_sel || !out)
     return ig_fail(ctx, IG_EINVAL, "ig_layer_step: NULL argument");

@@ -80,6 +80,7 @@ struct ig_ctx {
   float *attn_part; size_t attn_part_bytes;  // attention: per-slice softmax states [B*H][16][d+2]
   int32_t *attn_cnt; size_t attn_cnt_bytes;  // attention: per-(b,h) arrival counters, zero between calls
   void *pair_sync;  size_t pair_sync_bytes;  // scan: per-(b,h) records of pairs split over workgroups, zero between calls
+  hipStream_t call_stream = nullptr;   // stream of the entry point being served (capture check in ig_ensure)
   long spin_limit;                           // scan: bound of a split's wait for its partners, 100 MHz ticks
   double *skew_ws;  size_t skew_ws_bytes;   // ig_skew_device: Gram matrices and eigenvectors [2][H][d][d]
   int32_t *status;                        // device status word (sticky flags)

@@ -65,3 +65,47 @@ def test_graph_replays_match_eager(cfg, kw):
     assert ctx.ig_check_status() == ig.IG_OK
     R.side_ctx.close()
     ctx.close()
+
+
+def test_workspace_growth_under_capture_is_refused():
+    """A call that would have to allocate a workspace while its stream is being captured returns an
+    error (and leaves the capture valid) instead of allocating; after ig_reserve the same call is
+    captured and replays correctly."""
+    import paper_2406_19707_amd as ig
+    from ig_case import make_case
+    from ig_gpu import Uploaded
+    w = wl.shrink(wl.WORKLOADS[2], B=2, H=8, N=1024, heavy_count=8)
+    c = make_case(w, gain=12.0)
+    build_ctx = ig.Context(0)
+    up = Uploaded(build_ctx, c)                      # slab and weight blob built with another context
+    ctx = ig.Context(0)                              # fresh: no workspace yet
+    d = up.desc
+    BH = w.B * w.H
+    sel_idx = torch.zeros((BH, c.N), dtype=torch.int32, device="cuda")
+    sel_cnt = torch.zeros(BH, dtype=torch.int32, device="cuda")
+    s = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=s):
+        with pytest.raises(ig.IgError) as e:
+            ctx.ig_speculate(d, up.x, up.wq, up.bias, up.A_p, up.pos, up.slab, sel_idx, c.N, sel_cnt, None)
+        assert e.value.code == ig.IG_EINVAL and "ig_reserve" in str(e.value)
+        sel_cnt.fill_(7)                             # the capture is still usable
+    g.replay()
+    torch.cuda.synchronize()
+    assert int(sel_cnt[0]) == 7
+    ctx.ig_reserve(d)
+    ref_idx, ref_cnt = torch.zeros_like(sel_idx), torch.zeros_like(sel_cnt)
+    build_ctx.ig_speculate(d, up.x, up.wq, up.bias, up.A_p, up.pos, up.slab, ref_idx, c.N, ref_cnt, None)
+    torch.cuda.synchronize()
+    g2 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g2, stream=s):
+        ctx.ig_speculate(d, up.x, up.wq, up.bias, up.A_p, up.pos, up.slab, sel_idx, c.N, sel_cnt, None)
+    for _ in range(2):
+        sel_cnt.zero_()
+        torch.cuda.synchronize()
+        g2.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(sel_cnt, ref_cnt)
+    ctx.close()
+    build_ctx.close()
