@@ -292,6 +292,22 @@ int ig_speculate_host(ig_ctx *ctx, const ig_desc *desc, const float *q_p, const 
                       int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, float *scores_opt,
                       int threads);
 
+/* Rehearsal with head-equalised lists in one call (Section 4.3 "Decoding Stage", closing sentences;
+ * Section 5.1 "Key Metric"): ig_speculate followed by ig_equalize_heads, with the same results bit
+ * for bit, but for the shapes whose scan keeps a head's scores in one workgroup's registers (half
+ * precision, r = 25 or 38, up to 4096 tokens, at least 128 (sequence, head) pairs) the scan kernel
+ * itself exchanges the heads' threshold counts and selects each head's top n_b, so no score array
+ * is written and no second kernel runs.  Arguments as ig_speculate; max_frac as ig_equalize_heads;
+ * sel_idx / sel_cnt receive the EQUALISED lists and counts; thr_cnt_opt: NULL, or device int32
+ * [B*H] that receives the per-head threshold counts (must not alias sel_cnt).  Other shapes take
+ * the two kernels internally (sel_idx then passes through the threshold lists first and needs
+ * sel_stride >= the longest of them for exact counts, i.e. N to be safe).  The exchange between the
+ * heads of a sequence uses bounded waits (ig_set_wait_limit) like the split scan. */
+int ig_speculate_equalized(ig_ctx *ctx, const ig_desc *desc, const void *x, const void *wq,
+                           const float *bias, const float *A_p, const int32_t *pos, const void *slab,
+                           double max_frac, int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,
+                           int32_t *thr_cnt_opt, void *stream);
+
 /* Head-equalised selection (Section 4.3 "Decoding Stage", closing sentences; Section 5.1 "Key
  * Metric"): every head of a sequence keeps the same number of tokens,
  *   n_b = max(1, min(floor(sum_h thr_cnt[b,h] / H), floor(max_frac * N))),

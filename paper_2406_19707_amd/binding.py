@@ -35,7 +35,7 @@ EXPORTS = [
     "ig_slab_build", "ig_append_token",
     "ig_pool_touch", "ig_pool_victim", "ig_pool_replace", "ig_pool_touch_policy", "ig_pool_replace_policy",
     "ig_speculate", "ig_project", "ig_scan_select", "ig_project_indexed", "ig_speculate_indexed",
-    "ig_speculate_host", "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention", "ig_sparse_attention_static",
+    "ig_speculate_host", "ig_speculate_equalized", "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention", "ig_sparse_attention_static",
     "ig_sparse_attention_indexed", "ig_gather_attention", "ig_layer_step", "ig_set_wait_limit", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
     "ig_copy_bytes", "ig_read_bytes",
 ]
@@ -114,6 +114,8 @@ def lib():
             "ig_speculate_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp]),
             "ig_layer_step": (ctypes.c_int, [_vp, _dp] + [_vp] * 13 + [_i32] + [_vp] * 6),
             "ig_speculate_host": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _i32, _vp, _vp, ctypes.c_int]),
+            "ig_speculate_equalized": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_double, _vp, _i32,
+                                                      _vp, _vp, _vp]),
             "ig_equalize_heads": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_double, _vp, _i32, _vp, _vp]),
             "ig_gather_kv": (ctypes.c_int, [_vp, _dp, _vp, _vp, ctypes.c_int, _vp, _i32, _vp, _vp, _vp, _vp]),
             "ig_sparse_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
@@ -389,6 +391,12 @@ class Context:
                                                    _ptr(Kpool), _ptr(Vpool), _ptr(sel_idx),
                                                    sel_stride, _ptr(sel_cnt), _ptr(k_new),
                                                    _ptr(v_new), _ptr(out), _stream(stream)))
+
+    def ig_speculate_equalized(self, desc, x, wq, bias, A_p, pos, slab, max_frac, sel_idx, sel_stride, sel_cnt,
+                               thr_cnt_opt=None, stream=None):
+        self.call("ig_speculate_equalized", ctypes.byref(desc), _ptr(x), _ptr(wq), _ptr(bias), _ptr(A_p), _ptr(pos),
+                  _ptr(slab), float(max_frac), _ptr(sel_idx), sel_stride, _ptr(sel_cnt), _ptr(thr_cnt_opt),
+                  _stream(stream))
 
     def ig_equalize_heads(self, desc, scores, thr_cnt, max_frac, sel_idx, sel_stride, sel_cnt,
                           stream=None):

@@ -144,6 +144,10 @@ int reserve_for(ig_ctx *ctx, const ig_desc *d, bool scores) {
   if (rc) return rc;
   rc = ig_ensure_zeroed(ctx, &ctx->pair_sync, &ctx->pair_sync_bytes, (size_t)d->B * d->H * IG_PAIR_SYNC_BYTES);
   if (rc) return rc;
+  rc = ig_ensure_zeroed(ctx, &ctx->seq_sync, &ctx->seq_sync_bytes, (size_t)d->B * (d->H + 1) * sizeof(unsigned long long));
+  if (rc) return rc;
+  rc = ig_ensure(ctx, (void **)&ctx->eq_cnt, &ctx->eq_cnt_bytes, (size_t)d->B * d->H * sizeof(int32_t));
+  if (rc) return rc;
   if (scores) {
     const int tile = ig_tile_tokens(d->dtype);
     const int nTiles = (d->N_cap + tile - 1) / tile;
@@ -225,6 +229,8 @@ int ig_destroy(ig_ctx *ctx) {
   if (ctx->pcount) (void)hipFree(ctx->pcount);
   if (ctx->skew_ws) (void)hipFree(ctx->skew_ws);
   if (ctx->pair_sync) (void)hipFree(ctx->pair_sync);
+  if (ctx->seq_sync) (void)hipFree(ctx->seq_sync);
+  if (ctx->eq_cnt) (void)hipFree(ctx->eq_cnt);
   if (ctx->attn_part) (void)hipFree(ctx->attn_part);
   if (ctx->attn_cnt) (void)hipFree(ctx->attn_cnt);
   if (ctx->status) (void)hipFree(ctx->status);
@@ -245,7 +251,7 @@ int ig_reserve(ig_ctx *ctx, const ig_desc *desc) {
 size_t ig_workspace_bytes(const ig_ctx *ctx) {
   if (!ctx) return 0;
   return ctx->part_bytes + ctx->qp_bytes + ctx->scores_bytes + ctx->tmax_bytes + ctx->pcount_bytes +
-         ctx->attn_part_bytes + ctx->attn_cnt_bytes + ctx->skew_ws_bytes + ctx->pair_sync_bytes;
+         ctx->attn_part_bytes + ctx->attn_cnt_bytes + ctx->skew_ws_bytes + ctx->pair_sync_bytes + ctx->seq_sync_bytes + ctx->eq_cnt_bytes;
 }
 
 int ig_check_status(ig_ctx *ctx) {
@@ -544,6 +550,41 @@ int ig_speculate(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, c
   // folded: the scan adds the split-K partial sums (and the bias) itself
   QSource q{ctx->part, g.KS, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias};
   return ig_launch_scan_select(ctx, d, q, slab, sel_idx, sel_stride, sel_cnt, scores_opt, s);
+}
+
+int ig_speculate_equalized(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, const float *bias,
+                           const float *A_p, const int32_t *pos, const void *slab, double max_frac,
+                           int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, int32_t *thr_cnt_opt,
+                           void *stream) {
+  int rc = check_desc(ctx, d, stream);
+  if (rc) return rc;
+  if (!slab) return ig_fail(ctx, IG_EINVAL, "slab is NULL");
+  if (!(max_frac > 0.0) || max_frac > 1.0)
+    return ig_fail(ctx, IG_EINVAL, "max_frac must be in (0, 1] (got %g)", max_frac);
+  if ((rc = check_sel(ctx, sel_idx, sel_stride, sel_cnt))) return rc;
+  if (thr_cnt_opt == sel_cnt) return ig_fail(ctx, IG_EINVAL, "ig_speculate_equalized: thr_cnt_opt and sel_cnt must not alias");
+  int cap = (int)floor(max_frac * (double)d->N);
+  if (cap < 1) cap = 1;
+  hipStream_t s = (hipStream_t)stream;
+  if (ig_scan_equalizes(d)) {
+    // one kernel after the projection: the scan's workgroups exchange their threshold counts and
+    // select each head's top n from the scores they still hold in registers
+    ProjGeom g;
+    if ((rc = project_partials(ctx, d, x, wq, A_p, pos, &g, s))) return rc;
+    if (d->rope) {
+      QSource q{ctx->part, g.KS, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias, A_p, pos};
+      return ig_launch_scan_equalized(ctx, d, q, slab, cap, sel_idx, sel_stride, sel_cnt, thr_cnt_opt, s);
+    }
+    QSource q{ctx->part, g.KS, (long)g.Bpad * g.Cpad, (long)g.Cpad, bias};
+    return ig_launch_scan_equalized(ctx, d, q, slab, cap, sel_idx, sel_stride, sel_cnt, thr_cnt_opt, s);
+  }
+  // other shapes: the rehearsal with the scores kept, then the stand-alone selection on them
+  // (the threshold lists go through sel_idx first and are overwritten by the equalised ones)
+  if ((rc = ig_ensure(ctx, (void **)&ctx->scores, &ctx->scores_bytes, (size_t)d->B * d->H * d->N * sizeof(float)))) return rc;
+  if ((rc = ig_ensure(ctx, (void **)&ctx->eq_cnt, &ctx->eq_cnt_bytes, (size_t)d->B * d->H * sizeof(int32_t)))) return rc;
+  int32_t *thr = thr_cnt_opt ? thr_cnt_opt : ctx->eq_cnt;
+  if ((rc = ig_speculate(ctx, d, x, wq, bias, A_p, pos, slab, sel_idx, sel_stride, thr, ctx->scores, stream))) return rc;
+  return ig_launch_equalize(ctx, d, ctx->scores, thr, cap, sel_idx, sel_stride, sel_cnt, s);
 }
 
 int ig_equalize_heads(ig_ctx *ctx, const ig_desc *d, const float *scores, const int32_t *thr_cnt,

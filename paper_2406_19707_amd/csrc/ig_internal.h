@@ -80,6 +80,10 @@ struct ig_ctx {
   float *attn_part; size_t attn_part_bytes;  // attention: per-slice softmax states [B*H][16][d+2]
   int32_t *attn_cnt; size_t attn_cnt_bytes;  // attention: per-(b,h) arrival counters, zero between calls
   void *pair_sync;  size_t pair_sync_bytes;  // scan: per-(b,h) records of pairs split over workgroups, zero between calls
+  void *seq_sync = nullptr;            // scan, head-equalised form: per-sequence exchange records (zero between calls)
+  size_t seq_sync_bytes = 0;
+  int32_t *eq_cnt = nullptr;            // threshold counts of ig_speculate_equalized's two-kernel route
+  size_t eq_cnt_bytes = 0;
   hipStream_t call_stream = nullptr;   // stream of the entry point being served (capture check in ig_ensure)
   long spin_limit;                           // scan: bound of a split's wait for its partners, 100 MHz ticks
   double *skew_ws;  size_t skew_ws_bytes;   // ig_skew_device: Gram matrices and eigenvectors [2][H][d][d]
@@ -149,6 +153,10 @@ struct QSource {
 };
 bool ig_scan_is_fused(const ig_desc *d);
 bool ig_scan_takes_rope(const ig_desc *d);
+bool ig_scan_equalizes(const ig_desc *d);
+int ig_launch_scan_equalized(ig_ctx *ctx, const ig_desc *d, const QSource &q, const void *slab, int cap,
+                             int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, int32_t *thr_cnt_opt,
+                             hipStream_t s);
 bool ig_scan_stream_form(const ig_desc *d, int *tiles_per_wave, int *splits);
 int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const void *slab,
                           int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt,

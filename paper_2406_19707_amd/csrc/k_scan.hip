@@ -315,6 +315,174 @@ __device__ __forceinline__ int compact_tiles(const float (&sc)[TPW][TPL], float 
   return all;
 }
 
+// ---- head-equalised selection inside the streaming kernel ----------------------------------------
+// Section 4.3 "Decoding Stage", closing sentences: every head of a sequence keeps the same number
+// of tokens, the (truncated) mean over the heads of the per-head threshold counts, at most `cap`
+// (Section 5.1 "Key Metric"); a head keeps its n highest scores, the earlier token on equal scores.
+// The workgroups of a sequence's heads exchange their threshold counts through a small record in
+// device memory, the way the splits of a pair exchange maxima: one self-validating word per head,
+// a bounded wait, and a self-sufficient route for a workgroup whose wait runs out (it works out the
+// other heads' counts alone).  The scores never leave the registers.
+struct EqArgs {
+  unsigned long long *seq;   // [B][H + 1]: per head "published | threshold count"; then the arrivals counter
+  int32_t *thr_cnt;          // optional: the per-head threshold counts [B*H]
+  int cap;                   // floor(max_frac * N), at least 1
+};
+
+// order-preserving image of a score (larger score <-> larger key; -0 folded onto +0): the key the
+// stand-alone equalisation kernel selects on, so both give the same lists
+__device__ __forceinline__ unsigned eq_key(float s) {
+  const unsigned b = __float_as_uint(s + 0.0f);
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+// Wave 0 only: waits until all H heads of the sequence have published, returns their sum.
+__device__ __forceinline__ bool poll_heads(const unsigned long long *slots, int H, int lane, long limit, int *total) {
+  *total = 0;
+  if (limit < 0) return false;
+  const long t0 = wall_clock64();
+  while (true) {
+    int sum = 0;
+    bool all = true;
+    for (int c = 0; c < H; c += IG_WAVE) {
+      unsigned long long v = PUBLISHED;
+      if (c + lane < H) v = __hip_atomic_load(slots + c + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      all = all && __ballot((v & PUBLISHED) != 0) == ~0ull;
+      sum += (c + lane < H) ? (int)(unsigned)v : 0;
+    }
+    if (all) {
+      *total = wave_sum(sum);
+      return true;
+    }
+    if (wall_clock64() - t0 > limit) return false;
+    __builtin_amdgcn_s_sleep(2);
+  }
+}
+
+// Key of the n-th largest valid score of the workgroup's tokens (4 waves; wave w holds tiles
+// w*TPW + i): most-significant-digit radix select, 4 passes of 8 bits, one 256-bin LDS histogram
+// each.  *need_out = how many tokens equal to that key are to be kept.
+template <int TPL, int TPW>
+__device__ __forceinline__ unsigned nth_largest_key(const float (&sc)[TPW][TPL], const unsigned (&valid)[TPW], int n,
+                                                    unsigned *hist /*[256]*/, unsigned *wsum /*[4]*/,
+                                                    unsigned *s_prefix, int *s_need, int *need_out) {
+  const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+  unsigned prefix = 0;
+  int need = n;
+  for (int pass = 0; pass < 4; ++pass) {
+    const int shift = 24 - 8 * pass;
+    const unsigned hi_mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+    hist[tid] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < TPW; ++i)
+#pragma unroll
+      for (int e = 0; e < TPL; ++e) {
+        const unsigned k = eq_key(sc[i][e]);
+        if (((valid[i] >> e) & 1u) && (k & hi_mask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+      }
+    __syncthreads();
+    // bin d holds the target when (#keys in bins above d) < need <= (#keys in bins >= d)
+    const unsigned mine = hist[tid];
+    unsigned incl = mine;                     // suffix sum inside the wave: bins tid .. (wave end)
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const unsigned u = __shfl_down(incl, o, 64);
+      if (lane + o < 64) incl += u;
+    }
+    if (lane == 0) wsum[w] = incl;
+    __syncthreads();
+    unsigned above = incl - mine;
+    for (int k = w + 1; k < 4; ++k) above += wsum[k];
+    if ((int)above < need && need <= (int)(above + mine)) {
+      *s_prefix = prefix | ((unsigned)tid << shift);
+      *s_need = need - (int)above;
+    }
+    __syncthreads();
+    prefix = *s_prefix;
+    need = *s_need;
+    __syncthreads();
+  }
+  *need_out = need;
+  return prefix;
+}
+
+// Ordered compaction of the tokens whose key exceeds T plus the first `need` tokens (in token
+// order) whose key equals T; otherwise as compact_tiles.  Returns the number of tokens kept.
+template <int TPL, int NW, int TPW>
+__device__ __forceinline__ int compact_tiles_topn(const float (&sc)[TPW][TPL], const unsigned (&valid)[TPW], unsigned T,
+                                                  int need, int32_t *list, int sel_stride, int *lds_cnt /*[NW]*/,
+                                                  int32_t *stage, int w, int lane) {
+  constexpr int TILE = IG_WAVE * TPL;
+  unsigned eqm[TPW], keep[TPW];
+  int eq_rank[TPW], eq_mine = 0;
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+    eqm[i] = 0;
+    keep[i] = 0;
+    int below = 0, total = 0;
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) {
+      const unsigned k = eq_key(sc[i][e]);
+      const bool ok = (valid[i] >> e) & 1u;
+      const bool eq = ok && k == T;
+      const unsigned long long bal = __ballot(eq);
+      below += lanes_below(bal);
+      total += __popcll(bal);
+      eqm[i] |= (eq ? 1u : 0u) << e;
+      keep[i] |= ((ok && k > T) ? 1u : 0u) << e;
+    }
+    eq_rank[i] = eq_mine + below;
+    eq_mine += total;
+  }
+  if (lane == 0) lds_cnt[w] = eq_mine;
+  __syncthreads();
+  int eq_before = 0;
+#pragma unroll
+  for (int k = 0; k < NW; ++k) eq_before += (k < w) ? lds_cnt[k] : 0;
+  __syncthreads();   // lds_cnt is reused
+  int rank[TPW], mine = 0;
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+    int p = eq_before + eq_rank[i];
+    int below = 0, total = 0;
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) {
+      if ((eqm[i] >> e) & 1u) {
+        if (p < need) keep[i] |= 1u << e;
+        ++p;
+      }
+      const unsigned long long bal = __ballot((keep[i] >> e) & 1u);
+      below += lanes_below(bal);
+      total += __popcll(bal);
+    }
+    rank[i] = mine + below;
+    mine += total;
+  }
+  if (lane == 0) lds_cnt[w] = mine;
+  __syncthreads();
+  int before = 0, all = 0;
+#pragma unroll
+  for (int k = 0; k < NW; ++k) {
+    const int c = lds_cnt[k];
+    before += (k < w) ? c : 0;
+    all += c;
+  }
+  __syncthreads();
+  int32_t *row = stage + w * (TPW * TILE);
+#pragma unroll
+  for (int i = 0; i < TPW; ++i) {
+    const int t0 = (w * TPW + i) * TILE + lane * TPL;
+    int p = rank[i];
+#pragma unroll
+    for (int e = 0; e < TPL; ++e)
+      if ((keep[i] >> e) & 1u) row[p++] = t0 + e;
+  }
+  for (int j = lane; j < mine; j += IG_WAVE)
+    if (before + j < sel_stride) list[before + j] = row[j];
+  return all;
+}
+
 // The slow route, step by step: 16-byte loads in blocks of 8 channels, NW tiles per round in token
 // order, by this workgroup alone.  pair_max: the pair's maximum; rescan_pair: scores again, then
 // threshold and the whole ascending list and its count.
@@ -374,6 +542,38 @@ __device__ __forceinline__ void rescan_pair(const ScanArgs &a, int bh, float q_l
     a.sel_cnt[bh] = min(base, a.sel_stride);
     if (base > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
   }
+}
+
+// Slow route of the head-equalised form: the threshold count of another head of the sequence,
+// worked out by this workgroup alone (q_lane: that head's partial query).
+template <typename T, int NW>
+__device__ __forceinline__ int count_pair(const ScanArgs &a, int bh, float q_lane, float thr, int *lds_cnt) {
+  constexpr int TPL = SlabElem<T>::TPL;
+  constexpr int TILE = IG_WAVE * TPL;
+  const int w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const T *head = static_cast<const T *>(a.slab) + (long)bh * a.nTiles * a.r * TILE;
+  const float qv[4] = {q_lane, 0.f, 0.f, 0.f};
+  typename SlabElem<T>::vec v[8];
+  int n = 0;
+  for (int ti = w; ti < a.nValid; ti += NW) {
+    const T *tile = head + (long)ti * a.r * TILE;
+    float acc[TPL];
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) acc[e] = 0.f;
+    load_block<T, 8>(tile, a.r, 0, lane, v);
+    scan_tile_given_q<T, 8>(a, tile, lane, v, qv, acc);
+#pragma unroll
+    for (int e = 0; e < TPL; ++e) n += (ti * TILE + lane * TPL + e < a.N && acc[e] >= thr) ? 1 : 0;
+  }
+  n = wave_sum(n);
+  __syncthreads();
+  if (lane == 0) lds_cnt[w] = n;
+  __syncthreads();
+  int all = 0;
+#pragma unroll
+  for (int k = 0; k < NW; ++k) all += lds_cnt[k];
+  __syncthreads();
+  return all;
 }
 
 // Partial query of a rotary model inside the streaming kernel (Section 4.3 "Decoding Stage" for
@@ -462,8 +662,8 @@ static inline bool rope_prologue_fits(int threads, int d, int r) {
   return (d + G - 1) / G <= rope_pf(r);
 }
 
-template <typename T, int R, int NW, int TPW, int WIN, int MINW, bool ROPE>
-__global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, RopeArgs ra, int S, int BH, PairSync *sync, long spin_limit) {
+template <typename T, int R, int NW, int TPW, int WIN, int MINW, bool ROPE, bool EQ>
+__global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, RopeArgs ra, EqArgs eq, int S, int BH, PairSync *sync, long spin_limit) {
   constexpr int TPL = SlabElem<T>::TPL;
   constexpr int TILE = IG_WAVE * TPL;
   constexpr int NLOAD = TPW * R;              // 1 KiB loads of a wave with all its tiles valid
@@ -511,8 +711,8 @@ __global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, 
     v[k] = *reinterpret_cast<const vec *>(tbase[k / R] + (k % R) * PLANE + lane_off);
   __builtin_amdgcn_sched_barrier(0);
   float q_lane;
+  __shared__ float q_lds[ROPE ? 256 : 1], qr_lds[ROPE ? 256 : 1], psum[ROPE ? NW * 64 : 1], qp_lds[ROPE ? 64 : 1];
   if constexpr (ROPE) {
-    __shared__ float q_lds[256], qr_lds[256], psum[NW * 64], qp_lds[64];
     rope_finish<NW * 64, rope_pf(R)>(a, ra, rl, q_lds, qr_lds, psum, qp_lds);
     q_lane = lane < R ? qp_lds[lane] * a.scale : 0.f;
   } else {
@@ -555,6 +755,79 @@ __global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, 
 #pragma unroll
   for (int k = 1; k < NW; ++k) mm = fmaxf(mm, lds_max[k]);
   int32_t *list = a.sel_idx + (long)bh * a.sel_stride;
+  if constexpr (EQ) {
+    // ---- head-equalised lists (one workgroup per pair: S == 1) ----
+    static_assert(NW == 4, "the radix select's histogram scan is written for 4 waves");
+    __shared__ unsigned eq_hist[256], eq_wsum[4], eq_prefix;
+    __shared__ int eq_need;
+    const int cnt = compact_tiles<TPL, NW, TPW>(sc, mm - a.alpha, a.N, 0, list, a.sel_stride, 0, lds_cnt, stage, w, lane, true);
+    if (eq.thr_cnt && threadIdx.x == 0) eq.thr_cnt[bh] = cnt;
+    unsigned long long *rec = eq.seq + (long)b * (a.H + 1);
+    if (w == 0) {
+      if (lane == 0)
+        __hip_atomic_store(&rec[h], PUBLISHED | (unsigned long long)(unsigned)cnt, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      int total = 0;
+      const bool ok = poll_heads(rec, a.H, lane, spin_limit, &total);
+      if (lane == 0) {
+        lds_flag[0] = ok;
+        lds_flag[1] = total;
+      }
+      if (!ok) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // own slot has landed before "done"
+    }
+    __syncthreads();
+    int total = lds_flag[1];
+    if (lds_flag[0] == 0) {
+      // the other heads' counts did not arrive in time: work them out alone, head by head
+      total = 0;
+      for (int h2 = 0; h2 < a.H; ++h2) {
+        if (h2 == h) {
+          total += cnt;
+          continue;
+        }
+        float q2;
+        if constexpr (ROPE) {
+          RopeLoads<rope_pf(R)> rl2;
+          rope_issue<NW * 64, rope_pf(R)>(a, ra, b, h2, rl2);
+          __syncthreads();
+          rope_finish<NW * 64, rope_pf(R)>(a, ra, rl2, q_lds, qr_lds, psum, qp_lds);
+          q2 = lane < R ? qp_lds[lane] * a.scale : 0.f;
+        } else {
+          QueryLoads ql2;
+          query_issue(a, b, h2, lane, 0, ql2);
+          q2 = query_finish(a, ql2);
+        }
+        const float m2 = pair_max<T, NW>(a, b * a.H + h2, q2, lds_max);
+        total += count_pair<T, NW>(a, b * a.H + h2, q2, m2 - a.alpha, lds_cnt);
+      }
+    }
+    const int n = max(1, min(min(total / a.H, eq.cap), a.N));
+    unsigned valid[TPW];
+#pragma unroll
+    for (int i = 0; i < TPW; ++i) {
+      const int t0 = (my0 + i) * TILE + lane * TPL;
+      valid[i] = 0;
+#pragma unroll
+      for (int e = 0; e < TPL; ++e) valid[i] |= ((i < nact && t0 + e < a.N) ? 1u : 0u) << e;
+    }
+    int need = 0;
+    const unsigned Tkey = nth_largest_key<TPL, TPW>(sc, valid, n, eq_hist, eq_wsum, &eq_prefix, &eq_need, &need);
+    const int all = compact_tiles_topn<TPL, NW, TPW>(sc, valid, Tkey, need, list, a.sel_stride, lds_cnt, stage, w, lane);
+    if (threadIdx.x == 0) {
+      a.sel_cnt[bh] = min(all, a.sel_stride);
+      if (all > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
+    }
+    // done with the sequence's record; the last head to get here clears it for the next call
+    if (w == 0) {
+      unsigned long long prev = 0;
+      if (lane == 0) prev = __hip_atomic_fetch_add(&rec[a.H], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int prev_lo = __builtin_amdgcn_readfirstlane((int)prev);
+      if (prev_lo == a.H - 1) {
+        for (int c = lane; c <= a.H; c += IG_WAVE)
+          __hip_atomic_store(&rec[c], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+    return;
+  }
   if (S == 1) {
     const int all = compact_tiles<TPL, NW, TPW>(sc, mm - a.alpha, a.N, 0, list, a.sel_stride, 0, lds_cnt, stage, w, lane, false);
     if (threadIdx.x == 0) {
@@ -680,37 +953,51 @@ int launch_fused(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
 // workgroup, 8 loads of 1 KiB in flight per wave (deeper windows measured the same), registers held
 // to 96 so that five workgroups share a compute unit (one tile or two per wave) or to 128 (four)
 template <typename T, int R, int NW, int TPW, int WIN, int MINW>
-int launch_stream_one(ig_ctx *ctx, const ScanArgs &a, const RopeArgs *ra, int BH, int S, hipStream_t s) {
+int launch_stream_one(ig_ctx *ctx, const ScanArgs &a, const RopeArgs *ra, const EqArgs *eq, int BH, int S, hipStream_t s) {
   dim3 grid((unsigned)((BH + 7) / 8 * 8 * S)), block(NW * 64);
   PairSync *sync = static_cast<PairSync *>(ctx->pair_sync);
+  if (eq) {
+    if constexpr (TPW <= 2) {      // head-equalised lists: the forms with one workgroup per pair
+      if (S != 1) return ig_fail(ctx, IG_ESHAPE, "scan: head-equalised lists need one workgroup per pair");
+      if (ra) {
+        auto k = scan_select_stream<T, R, NW, TPW, WIN, 3, true, true>;    // (few workgroups per compute unit here)
+        IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, *ra, *eq, S, BH, sync, ctx->spin_limit);
+      } else {
+        auto k = scan_select_stream<T, R, NW, TPW, WIN, 4, false, true>;
+        IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, RopeArgs{}, *eq, S, BH, sync, ctx->spin_limit);
+      }
+      return IG_OK;
+    }
+    return ig_fail(ctx, IG_ESHAPE, "scan: head-equalised lists are not built for %d tiles per wave", TPW);
+  }
   if (ra) {
-    auto k = scan_select_stream<T, R, NW, TPW, WIN, MINW, true>;
-    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, *ra, S, BH, sync, ctx->spin_limit);
+    auto k = scan_select_stream<T, R, NW, TPW, WIN, MINW, true, false>;
+    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, *ra, EqArgs{}, S, BH, sync, ctx->spin_limit);
   } else {
-    auto k = scan_select_stream<T, R, NW, TPW, WIN, MINW, false>;
-    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, RopeArgs{}, S, BH, sync, ctx->spin_limit);
+    auto k = scan_select_stream<T, R, NW, TPW, WIN, MINW, false, false>;
+    IG_LAUNCH(ctx, IG_K_SCAN, k, grid, block, s, a, RopeArgs{}, EqArgs{}, S, BH, sync, ctx->spin_limit);
   }
   return IG_OK;
 }
 
 template <typename T, int R>
-int launch_stream_r(ig_ctx *ctx, const ScanArgs &a, const RopeArgs *ra, int BH, int TPW, int S, hipStream_t s) {
-  if (TPW == 1) return launch_stream_one<T, R, 4, 1, 8, 5>(ctx, a, ra, BH, S, s);
-  if (TPW == 2) return launch_stream_one<T, R, 4, 2, 8, 5>(ctx, a, ra, BH, S, s);
+int launch_stream_r(ig_ctx *ctx, const ScanArgs &a, const RopeArgs *ra, const EqArgs *eq, int BH, int TPW, int S, hipStream_t s) {
+  if (TPW == 1) return launch_stream_one<T, R, 4, 1, 8, 5>(ctx, a, ra, eq, BH, S, s);
+  if (TPW == 2) return launch_stream_one<T, R, 4, 2, 8, 5>(ctx, a, ra, eq, BH, S, s);
   if constexpr (R <= 32) {   // (with more channels the unrolled stream of 4 tiles no longer stays in registers)
-    if (TPW == 4) return launch_stream_one<T, R, 4, 4, 8, 4>(ctx, a, ra, BH, S, s);
+    if (TPW == 4) return launch_stream_one<T, R, 4, 4, 8, 4>(ctx, a, ra, eq, BH, S, s);
   }
   return ig_fail(ctx, IG_ESHAPE, "scan: streaming form with %d tiles per wave is not built", TPW);
 }
 
-int launch_stream(ig_ctx *ctx, const ScanArgs &a, const RopeArgs *ra, int BH, int TPW, int S, hipStream_t s) {
+int launch_stream(ig_ctx *ctx, const ScanArgs &a, const RopeArgs *ra, const EqArgs *eq, int BH, int TPW, int S, hipStream_t s) {
   if (S < 1 || S > IG_SPLIT_MAX) return ig_fail(ctx, IG_ESHAPE, "scan: %d splits per pair", S);
   if (S > 1) {
     int rc = ig_ensure_zeroed(ctx, &ctx->pair_sync, &ctx->pair_sync_bytes, (size_t)BH * IG_PAIR_SYNC_BYTES);
     if (rc) return rc;
   }
-  if (a.r == 38) return launch_stream_r<half_t, 38>(ctx, a, ra, BH, TPW, S, s);
-  if (a.r == 25) return launch_stream_r<half_t, 25>(ctx, a, ra, BH, TPW, S, s);
+  if (a.r == 38) return launch_stream_r<half_t, 38>(ctx, a, ra, eq, BH, TPW, S, s);
+  if (a.r == 25) return launch_stream_r<half_t, 25>(ctx, a, ra, eq, BH, TPW, S, s);
   return ig_fail(ctx, IG_ESHAPE, "scan: streaming form is not built for r = %d", a.r);
 }
 
@@ -756,18 +1043,19 @@ int launch_tiles(ig_ctx *ctx, const ScanArgs &a, int BH, int ch, hipStream_t s) 
 }
 
 template <typename T>
-int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, const QSource *rope, hipStream_t s) {
+int launch_scan(ig_ctx *ctx, const ig_desc *d, ScanArgs &a, const QSource *rope, const EqArgs *eq, hipStream_t s) {
   const int BH = d->B * d->H;
   const int nTiles = a.nValid;     // the work, not the capacity, picks the kernel
   // One workgroup per (b,h) when it fits and there are enough (b,h) pairs to fill the chip;
   // otherwise one wave per tile so that long sequences spread over all compute units.
   int tpw = 0, S = 0;
   if (ig_scan_stream_form(d, &tpw, &S)) {
-    if (!rope) return launch_stream(ctx, a, nullptr, BH, tpw, S, s);
+    if (!rope) return launch_stream(ctx, a, nullptr, eq, BH, tpw, S, s);
     RopeArgs ra{rope->A_p, rope->pos, d->d, -2.0 / (double)d->d * log2((double)d->rope_theta)};
-    return launch_stream(ctx, a, &ra, BH, tpw, S, s);
+    return launch_stream(ctx, a, &ra, eq, BH, tpw, S, s);
   }
   if (rope) return ig_fail(ctx, IG_EINVAL, "scan: a rotary query source needs the streaming form");
+  if (eq) return ig_fail(ctx, IG_EINVAL, "scan: head-equalised lists need the streaming form");
   const bool fused = ig_scan_is_fused(d);
   if (fused) {
     // When all workgroups fit on the chip at once (one round) a wave should have all its channels
@@ -889,5 +1177,27 @@ int ig_launch_scan_select(ig_ctx *ctx, const ig_desc *d, const QSource &q, const
   if (rc) return rc;
   const QSource *rope = q.A_p ? &q : nullptr;
   if (rope && !ig_scan_takes_rope(d)) return ig_fail(ctx, IG_EINVAL, "scan: this shape takes no rotary query source");
-  return d->dtype == IG_F16 ? launch_scan<half_t>(ctx, d, a, rope, s) : launch_scan<float>(ctx, d, a, rope, s);
+  return d->dtype == IG_F16 ? launch_scan<half_t>(ctx, d, a, rope, nullptr, s)
+                            : launch_scan<float>(ctx, d, a, rope, nullptr, s);
+}
+
+// Shapes whose scan builds the head-equalised lists itself: the streaming form with one
+// workgroup per pair (every head's workgroup of a sequence then runs at the same time).
+bool ig_scan_equalizes(const ig_desc *d) {
+  int tpw = 0, S = 0;
+  return ig_scan_stream_form(d, &tpw, &S) && S == 1 && tpw <= 2 && (!d->rope || ig_scan_takes_rope(d));
+}
+
+int ig_launch_scan_equalized(ig_ctx *ctx, const ig_desc *d, const QSource &q, const void *slab, int cap,
+                             int32_t *sel_idx, int32_t sel_stride, int32_t *sel_cnt, int32_t *thr_cnt_opt,
+                             hipStream_t s) {
+  if (!ig_scan_equalizes(d)) return ig_fail(ctx, IG_ESHAPE, "scan: this shape does not build equalised lists itself");
+  ScanArgs a;
+  int rc = ig_scan_args(ctx, d, q, slab, sel_idx, sel_stride, sel_cnt, nullptr, &a);
+  if (rc) return rc;
+  rc = ig_ensure_zeroed(ctx, &ctx->seq_sync, &ctx->seq_sync_bytes, (size_t)d->B * (d->H + 1) * sizeof(unsigned long long));
+  if (rc) return rc;
+  EqArgs eq{static_cast<unsigned long long *>(ctx->seq_sync), thr_cnt_opt, cap};
+  const QSource *rope = q.A_p ? &q : nullptr;
+  return launch_scan<half_t>(ctx, d, a, rope, &eq, s);
 }

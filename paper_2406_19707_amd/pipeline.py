@@ -340,8 +340,20 @@ class Rehearsal:
 
     def step_equalized(self, max_frac=0.2):
         """The paper's batched variant (Section 4.3, closing sentences): every head of a sequence
-        fetches the same number of tokens.  Rehearsal with the scores kept, equalisation, then
-        prefetch and attention over the equalised lists (HBM pool: in one pass)."""
+        fetches the same number of tokens.  Rehearsal with equalised lists in one call (for the
+        shapes that allow it the scan kernel selects each head's top n itself), then prefetch and
+        attention over the equalised lists (HBM pool: in one pass)."""
+        for l in range(self.L):
+            self.ctx.ig_speculate_equalized(self.desc, self.x[l], self.wq, None, self.A_p, self.pos,
+                                            self.slab[l], max_frac, self.sel_idx, self.stride, self.sel_cnt)
+            if self.host_pool:
+                self.gather(l)
+                self.attend(l)
+            else:
+                self.gather_attend(l)
+
+    def step_equalized_two_calls(self, max_frac=0.2):
+        """The same through ig_speculate (scores kept) and ig_equalize_heads."""
         w = self.w
         if not hasattr(self, "scores"):
             self.scores = torch.zeros((w.B, w.H, w.N), device="cuda")

@@ -160,3 +160,80 @@ def test_end_to_end_with_speculated_scores(ctx, cfg, shape, gain):
             nth = np.sort(s2[i])[::-1][r_cnt[i] - 1]
             assert np.all(np.abs(s2[i, diff] - nth) <= 1e-3)
     print(f"  equalised count per sequence {r_n}, mean threshold count {ref.sel_cnt.mean():.1f}", flush=True)
+
+
+# ---- ig_speculate_equalized: the selection inside the scan kernel ---------------------------------
+
+def two_kernel_reference(ctx, up, N, max_frac):
+    d = up.desc
+    w = up.c.w
+    BH = w.B * w.H
+    scores = torch.zeros((w.B, w.H, N), device="cuda")
+    t_idx = torch.zeros((BH, N), dtype=torch.int32, device="cuda")
+    t_cnt = torch.zeros((BH,), dtype=torch.int32, device="cuda")
+    e_idx = torch.full((BH, N), -1, dtype=torch.int32, device="cuda")
+    e_cnt = torch.zeros((BH,), dtype=torch.int32, device="cuda")
+    ctx.ig_speculate(d, up.x, up.wq, up.bias, up.A_p, up.pos, up.slab, t_idx, N, t_cnt, scores)
+    ctx.ig_equalize_heads(d, scores, t_cnt, max_frac, e_idx, N, e_cnt)
+    torch.cuda.synchronize()
+    return scores.cpu().numpy(), t_cnt.cpu().numpy(), e_idx.cpu().numpy(), e_cnt.cpu().numpy()
+
+
+@pytest.mark.parametrize("cfg,shape,gain,max_frac,fused", [
+    (2, dict(B=4, H=32, N=2048), 20.0, 0.2, True),     # one tile per wave
+    (2, dict(B=5, H=32, N=1800), 32.0, 0.05, True),    # ragged last tile, the cap binds
+    (3, dict(B=4, H=32, N=4096), 40.0, 0.2, True),     # rotary prologue, two tiles per wave
+    (3, dict(B=3, H=48, N=3000), 30.0, 0.2, True),     # ragged, H not a multiple of 8
+    (2, dict(B=2, H=40, N=300), 12.0, 1.0, False),     # too few pairs for the streaming form: two kernels
+    (5, dict(B=1, H=8, N=20000), 6.0, 0.2, False),     # long sequence: two kernels
+])
+def test_speculate_equalized_matches_the_two_calls_and_the_oracle(cfg, shape, gain, max_frac, fused):
+    import paper_2406_19707_amd as ig
+    from ig_gpu import Uploaded
+    ctx = ig.Context(0)
+    w = wl.shrink(wl.WORKLOADS[cfg], **shape, pool="hbm", n_cal=256)
+    c = make_case(w, gain=gain)
+    print(f"case {w.name} B{w.B} H{w.H} N{c.N} r{c.r} rope={w.rope} max_frac={max_frac}", flush=True)
+    up = Uploaded(ctx, c)
+    d = up.desc
+    BH, N = w.B * w.H, c.N
+    scores, t_cnt, ref_idx, ref_cnt = two_kernel_reference(ctx, up, N, max_frac)
+    # the reference itself against the oracle on the GPU's scores (exact) ...
+    o_idx, o_cnt, _ = o.select_equalized(scores, w.alpha, max_frac)
+    assert_same_lists(ref_idx, ref_cnt, o_idx, o_cnt)
+    assert 0 < ref_cnt.min() and ref_cnt.max() < N
+    for limit, what in ((None, "waits"), (-1, "every workgroup alone"), (None, "waits again")):
+        if limit is not None:
+            ctx.ig_set_wait_limit(limit)
+        idx = torch.full((BH, N), -1, dtype=torch.int32, device="cuda")
+        cnt = torch.full((BH,), -1, dtype=torch.int32, device="cuda")
+        thr = torch.full((BH,), -1, dtype=torch.int32, device="cuda")
+        ctx.ig_speculate_equalized(d, up.x, up.wq, up.bias, up.A_p, up.pos, up.slab, max_frac, idx, N, cnt, thr)
+        torch.cuda.synchronize()
+        assert ctx.ig_check_status() == ig.IG_OK, what
+        assert np.array_equal(thr.cpu().numpy(), t_cnt), what
+        assert_same_lists(idx.cpu().numpy(), cnt.cpu().numpy(), ref_idx, ref_cnt)
+        if limit is not None:
+            ctx.ig_set_wait_limit(2000000)
+    # without the optional counts; the kernels launched tell which route the shape took
+    idx = torch.full((BH, N), -1, dtype=torch.int32, device="cuda")
+    cnt = torch.full((BH,), -1, dtype=torch.int32, device="cuda")
+    ctx.ig_profile_begin()
+    ctx.ig_speculate_equalized(d, up.x, up.wq, up.bias, up.A_p, up.pos, up.slab, max_frac, idx, N, cnt)
+    torch.cuda.synchronize()
+    ctx.ig_profile_end()
+    assert_same_lists(idx.cpu().numpy(), cnt.cpu().numpy(), ref_idx, ref_cnt)
+    assert ctx.ig_profile_read(ig.IG_K_SCAN)[1] >= 1
+    assert (ctx.ig_profile_read(ig.IG_K_SELECT)[1] == 0) == fused, "route taken is not the one this case is for"
+    # a short stride is clamped and flagged
+    if fused:
+        short = int(ref_cnt.max()) - 1
+        idx = torch.full((BH, short), -1, dtype=torch.int32, device="cuda")
+        ctx.ig_speculate_equalized(d, up.x, up.wq, up.bias, up.A_p, up.pos, up.slab, max_frac, idx, short, cnt)
+        torch.cuda.synchronize()
+        assert ctx.ig_check_status() == ig.IG_ECAPACITY
+        got = idx.cpu().numpy()
+        for i in range(BH):
+            k = min(short, int(ref_cnt[i]))
+            assert np.array_equal(got[i, :k], ref_idx[i, :k])
+    ctx.close()

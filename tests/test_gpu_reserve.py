@@ -18,6 +18,8 @@ pytestmark = pytest.mark.gpu
     (2, dict(B=8, H=8, d=32, N=9000), 12000),               # scores parked in LDS
     (5, dict(B=1, H=2, N=9000), 20000),                     # one wave per tile, rotary (finalisation kernel)
     (3, dict(B=2, H=4, N=2000), 2048),                      # rotary prologue inside the scan
+    (2, dict(B=4, H=32, N=1500), 2048),                     # streaming form; equalised lists built by the scan
+    (3, dict(B=4, H=32, N=3000), 4096),                     # the same with the rotary prologue
 ])
 def test_no_allocation_after_reserve(cfg, kw, N_cap):
     import paper_2406_19707_amd as ig
@@ -42,6 +44,8 @@ def test_no_allocation_after_reserve(cfg, kw, N_cap):
         ctx.ig_speculate(d, up.x, up.wq, up.bias, up.A_p, up.pos, up.slab, idx[0], stride, cnt[0], scores)
         ctx.ig_speculate(d, up.x, up.wq, up.bias, up.A_p, up.pos, up.slab, idx[0], stride, cnt[0], None)
         ctx.ig_equalize_heads(d, scores, cnt[0], 0.2, idx[1], stride, cnt[1])
+        ctx.ig_speculate_equalized(d, up.x, up.wq, up.bias, up.A_p, up.pos, up.slab, 0.2, idx[1], stride, cnt[1])
+        ctx.ig_speculate_equalized(d, up.x, up.wq, up.bias, up.A_p, up.pos, up.slab, 0.2, idx[1], stride, cnt[1], cnt[0])
         ctx.ig_gather_kv(d, up.K, up.V, up.space, idx[0], stride, cnt[0], Ks, Vs)
         ctx.ig_sparse_attention(d, up.q, Ks, Vs, cnt[0], stride, up.k_new, up.v_new, out)
         ctx.ig_gather_attention(d, up.q, up.K, up.V, idx[0], stride, cnt[0], Ks, Vs, None, None, out)
