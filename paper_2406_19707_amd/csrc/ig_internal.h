@@ -124,6 +124,21 @@ void ig_prof_events(ig_ctx *ctx, int which, hipEvent_t *e0, hipEvent_t *e1);
     if (le__ != hipSuccess) return ig_hip_fail(ctx, le__, #kernel);                                \
   } while (0)
 
+// the same with `lds` bytes of dynamic LDS
+#define IG_LAUNCH_LDS(ctx, which, kernel, grid, block, lds, stream, ...)                           \
+  do {                                                                                             \
+    if ((ctx)->profiling) {                                                                        \
+      hipEvent_t e0__, e1__;                                                                       \
+      ig_prof_events(ctx, which, &e0__, &e1__);                                                    \
+      hipExtLaunchKernelGGL(kernel, grid, block, lds, (hipStream_t)(stream), e0__, e1__, 0,        \
+                            __VA_ARGS__);                                                          \
+    } else {                                                                                       \
+      hipLaunchKernelGGL(kernel, grid, block, lds, (hipStream_t)(stream), __VA_ARGS__);            \
+    }                                                                                              \
+    hipError_t le__ = hipGetLastError();                                                           \
+    if (le__ != hipSuccess) return ig_hip_fail(ctx, le__, #kernel);                                \
+  } while (0)
+
 // ---- launchers implemented in the kernel sources (host functions, return IG_* codes) ----------
 int ig_launch_wq_build(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const void *Wq,
                        const int32_t *idx, void *wq, hipStream_t s);

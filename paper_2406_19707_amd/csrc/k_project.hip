@@ -137,6 +137,78 @@ __global__ __launch_bounds__(256) void project_mfma(const half8 *__restrict__ bl
   }
 }
 
+// The same product for more than 16 batch rows (NB blocks of 16) with the x fragments shared
+// through LDS.  With NB = 2 the plain kernel above issues one weight load and two x loads per K
+// block and needs three batches of loads per wave for the register budget; here the four waves of
+// a workgroup (four neighbouring column blocks, the same K slice) stage the NB*16 rows of x for
+// their K slice in LDS once, a wave keeps only its weight pieces in registers -- all of its K slice
+// in flight at once, up to PKB pieces -- and reads each x fragment from LDS right before the MFMA
+// that uses it.  grid (ceil(nCblk/4), KS); LDS row stride padded by 16 bytes so that the 16 rows a
+// fragment read touches fall into different banks.
+template <int NB, int PKB>
+__global__ __launch_bounds__(256) void project_mfma_shared(const half8 *__restrict__ blob,
+                                                           const half_t *__restrict__ x,
+                                                           float *__restrict__ part, int B, int D,
+                                                           int nCblk, int nKblk, int kb_per, int Bpad,
+                                                           int Cpad) {
+  extern __shared__ uint4 xs[];                       // [NB*16 rows][kb_per*4 + 1] 16-byte pieces
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int ks = blockIdx.y;
+  const int cblk_raw = blockIdx.x * 4 + w;
+  const bool live = cblk_raw < nCblk;                 // a surplus wave still helps staging x
+  const int cblk = min(cblk_raw, nCblk - 1);
+  const int n = lane & 15, kg = lane >> 4;
+  const int kb0 = ks * kb_per, kb1 = min(nKblk, kb0 + kb_per);
+  const int nkb = kb1 - kb0;
+  // x rows of the slice (rows past B are zero): loaded first, because they are needed first -- a
+  // wave's loads return in the order it issued them -- then the weight pieces of the whole K slice
+  const int ppr = kb_per * 4, stride = ppr + 1;       // 16-byte pieces per row, padded stride
+  const int pieces = NB * 16 * ppr;
+  constexpr int XPT = NB * 16 * PKB * 4 / 256;         // x pieces per thread at most
+  uint4 xv[XPT];
+#pragma unroll
+  for (int u = 0; u < XPT; ++u) {
+    const int p = threadIdx.x + u * 256;
+    const int row = p / ppr, c = p - row * ppr;
+    xv[u] = make_uint4(0, 0, 0, 0);
+    if (p < pieces && row < B && kb0 * 4 + c < nKblk * 4)
+      xv[u] = *reinterpret_cast<const uint4 *>(x + (long)row * D + (long)kb0 * 32 + c * 8);
+  }
+  half8 a[PKB];
+  const half8 *wp = blob + ((long)cblk * nKblk + kb0) * 64 + lane;
+#pragma unroll
+  for (int t = 0; t < PKB; ++t) a[t] = wp[(long)min(t, nkb - 1) * 64];
+#pragma unroll
+  for (int u = 0; u < XPT; ++u) {
+    const int p = threadIdx.x + u * 256;
+    const int row = p / ppr, c = p - row * ppr;
+    if (p < pieces) xs[row * stride + c] = xv[u];
+  }
+  __syncthreads();
+  if (!live) return;
+  floatx4 acc[NB];
+#pragma unroll
+  for (int i = 0; i < NB; ++i) acc[i] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int t = 0; t < PKB; ++t) {
+    if (t < nkb) {
+#pragma unroll
+      for (int i = 0; i < NB; ++i) {
+        const uint4 raw = xs[(i * 16 + n) * stride + t * 4 + kg];
+        acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a[t], *reinterpret_cast<const half8 *>(&raw), acc[i], 0, 0, 0);
+      }
+    }
+  }
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    const int row = i * 16 + n;
+    if (row < Bpad) {
+      float *o = part + ((long)ks * Bpad + row) * Cpad + cblk * 16 + kg * 4;
+      *reinterpret_cast<floatx4 *>(o) = acc[i];
+    }
+  }
+}
+
 // One thread per output column, 16 batch rows per pass, K rows [ks*kb_per, ...).
 template <typename T>
 __global__ __launch_bounds__(64) void project_fma(const T *__restrict__ blob, const T *__restrict__ x,
@@ -480,6 +552,13 @@ int ig_launch_project(ig_ctx *ctx, const ig_desc *d, const ProjGeom &g, const vo
       IG_LAUNCH(ctx, IG_K_PROJECT, k, dim3((unsigned)((waves + 3) / 4), 1), block, s,
                 (const half8 *)wq, (const half_t *)x, part, (int)d->B, D, g.nCblk, g.nKblk, g.kb_per,
                 g.KS, g.Bpad, g.Cpad);
+    } else if (g.NBtot == 2 && g.kb_per <= 16) {
+      // 17..32 batch rows: x fragments through LDS, a wave's whole K slice of weights in flight
+      auto k = project_mfma_shared<2, 16>;
+      const size_t lds = (size_t)32 * (g.kb_per * 4 + 1) * 16;
+      const dim3 grid((unsigned)((g.nCblk + 3) / 4), (unsigned)g.KS);
+      IG_LAUNCH_LDS(ctx, IG_K_PROJECT, k, grid, block, lds, s, (const half8 *)wq, (const half_t *)x, part,
+                    (int)d->B, D, g.nCblk, g.nKblk, g.kb_per, g.Bpad, g.Cpad);
     } else if (g.NBtot == 2) {
       auto k = project_mfma<2>;
       IG_LAUNCH(ctx, IG_K_PROJECT, k, dim3((unsigned)((waves + 3) / 4), 1), block, s,

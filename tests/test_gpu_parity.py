@@ -141,6 +141,16 @@ def test_many_pairs_small_heads(ctx):
     check_case(ctx, make_case(w, gain=2.0))
 
 
+@pytest.mark.parametrize("cfg,B,H,N,gain", [
+    (4, 20, 7, 600, 10.0),     # 20 sequences: projection with the x fragments shared through LDS; 17 column blocks
+    (3, 18, 3, 700, 16.0),     # the same for a rotary model (every column of W_q)
+    (4, 32, 6, 300, 10.0),     # both batch blocks full
+])
+def test_seventeen_to_thirty_two_sequences(ctx, cfg, B, H, N, gain):
+    w = wl.shrink(wl.WORKLOADS[cfg], B=B, H=H, N=N, n_cal=256, heavy_count=8, pool="hbm")
+    check_case(ctx, make_case(w, gain=gain))
+
+
 def test_cfg3_shape_rope_f16(ctx):
     w = wl.shrink(wl.WORKLOADS[3], B=2, H=4, N=4096)
     check_case(ctx, make_case(w, gain=24.0))
