@@ -391,6 +391,33 @@ int ig_layer_step(ig_ctx *ctx, const ig_desc *desc, const void *x, const void *w
                   const int32_t *sel_idx, const int32_t *sel_cnt, int32_t sel_stride, void *K_sel,
                   void *V_sel, const void *k_new, const void *v_new, void *out, void *stream);
 
+/* One decode step over n_layers layers with the KV pool prefetched on a side stream (Section 4.1,
+ * Fig. 3(d): the selected rows of layer l cross to the GPU while layer l+1 is already being
+ * rehearsed and layer l-1 attended).  For every layer the call enqueues ig_speculate on
+ * main_stream, ig_gather_kv on side_stream and ig_sparse_attention on main_stream, with the events
+ * that order them, over n_sets >= 2 rotating buffer sets (layer l uses set l % n_sets).
+ * layers: host array [n_layers]; x, slab, q, Kpool, Vpool, out of a layer as in the three calls,
+ * k_new / v_new NULL or the always-attended row.  sets: host array [n_sets] of device buffers
+ * (sel_idx [B*H, sel_stride], sel_cnt [B*H], K_sel / V_sel [B*H, sel_stride, d]).  wq, bias, A_p,
+ * pos as ig_speculate (one model: the same for every layer here; callers with per-layer weights
+ * issue the three calls themselves).  The two streams must differ and have the default priority;
+ * the context keeps a second context for the side stream's workspaces and the events, created on
+ * the first call (so the first call allocates; calls for larger shapes may too).  Nothing is
+ * synchronised: when the call returns everything is enqueued, and main_stream's last work depends
+ * on side_stream's. */
+typedef struct {
+  const void *x, *slab, *q, *Kpool, *Vpool, *k_new, *v_new;
+  void *out;
+} ig_layer_io;
+typedef struct {
+  int32_t *sel_idx, *sel_cnt;
+  void *K_sel, *V_sel;
+} ig_buffer_set;
+int ig_decode_step_overlapped(ig_ctx *ctx, const ig_desc *desc, int n_layers, const ig_layer_io *layers,
+                              const void *wq, const float *bias, const float *A_p, const int32_t *pos,
+                              int pool_space, int n_sets, const ig_buffer_set *sets, int32_t sel_stride,
+                              void *main_stream, void *side_stream);
+
 /* Long sequences are scanned by several workgroups per (sequence, head), which meet through device
  * memory; each waits for its partners at most `ticks` periods of the GPU's 100 MHz clock (10 ns)
  * and then finishes the pair on its own (slower, same result bit for bit).  0 restores the

@@ -16,7 +16,7 @@ __all__ = [
     "IG_OK", "IG_EINVAL", "IG_ESHAPE", "IG_EDTYPE", "IG_ECAPACITY", "IG_EHIP", "IG_ENOCONV",
     "IG_ENOMEM", "IG_F32", "IG_F16", "IG_MEM_DEVICE", "IG_MEM_HOST_PINNED", "IG_POLICY_COUNTER", "IG_POLICY_FIFO", "IG_POLICY_LRU", "IG_K_PROJECT",
     "IG_K_FINALIZE", "IG_K_SCAN", "IG_K_SELECT", "IG_K_GATHER", "IG_K_ATTENTION", "IG_K_BUILD",
-    "IG_K_COPY", "IG_K_READ", "IG_K_LAYER", "IgDesc", "IgError", "Context", "lib", "lib_path", "ig_skew_offline",
+    "IG_K_COPY", "IG_K_READ", "IG_K_LAYER", "IgDesc", "IgLayerIO", "IgBufferSet", "IgError", "Context", "lib", "lib_path", "ig_skew_offline",
     "ig_partial_index", "ig_apply_skew", "ig_rope_rows", "ig_speculate_host", "ig_wq_bytes", "ig_slab_bytes", "EXPORTS",
 ]
 
@@ -36,7 +36,7 @@ EXPORTS = [
     "ig_pool_touch", "ig_pool_victim", "ig_pool_replace", "ig_pool_touch_policy", "ig_pool_replace_policy",
     "ig_speculate", "ig_project", "ig_scan_select", "ig_project_indexed", "ig_speculate_indexed",
     "ig_speculate_host", "ig_speculate_equalized", "ig_equalize_heads", "ig_gather_kv", "ig_sparse_attention", "ig_sparse_attention_static",
-    "ig_sparse_attention_indexed", "ig_gather_attention", "ig_layer_step", "ig_set_wait_limit", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
+    "ig_sparse_attention_indexed", "ig_gather_attention", "ig_layer_step", "ig_decode_step_overlapped", "ig_set_wait_limit", "ig_profile_begin", "ig_profile_end", "ig_profile_read",
     "ig_copy_bytes", "ig_read_bytes",
 ]
 
@@ -51,6 +51,16 @@ class IgDesc(ctypes.Structure):
                  rope_theta=10000.0):
         super().__init__(B, H, d, r, N, N if N_cap is None else N_cap, dtype, scale, alpha, rope,
                          rope_theta)
+
+
+class IgLayerIO(ctypes.Structure):
+    """One layer's tensors for ig_decode_step_overlapped (device / pinned-host addresses)."""
+    _fields_ = [(n, ctypes.c_void_p) for n in ("x", "slab", "q", "Kpool", "Vpool", "k_new", "v_new", "out")]
+
+
+class IgBufferSet(ctypes.Structure):
+    """One rotating set of list and row buffers for ig_decode_step_overlapped."""
+    _fields_ = [(n, ctypes.c_void_p) for n in ("sel_idx", "sel_cnt", "K_sel", "V_sel")]
 
 
 class IgError(RuntimeError):
@@ -122,6 +132,8 @@ def lib():
             "ig_sparse_attention_static": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
             "ig_sparse_attention_indexed": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp]),
             "ig_gather_attention": (ctypes.c_int, [_vp, _dp, _vp, _vp, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+            "ig_decode_step_overlapped": (ctypes.c_int, [_vp, _dp, ctypes.c_int, _vp, _vp, _vp, _vp, _vp, ctypes.c_int,
+                                                         ctypes.c_int, _vp, _i32, _vp, _vp]),
             "ig_set_wait_limit": (ctypes.c_int, [_vp, ctypes.c_int64]),
             "ig_profile_begin": (ctypes.c_int, [_vp]),
             "ig_profile_end": (ctypes.c_int, [_vp]),
@@ -394,9 +406,9 @@ class Context:
 
     def ig_speculate_equalized(self, desc, x, wq, bias, A_p, pos, slab, max_frac, sel_idx, sel_stride, sel_cnt,
                                thr_cnt_opt=None, stream=None):
-        self.call("ig_speculate_equalized", ctypes.byref(desc), _ptr(x), _ptr(wq), _ptr(bias), _ptr(A_p), _ptr(pos),
-                  _ptr(slab), float(max_frac), _ptr(sel_idx), sel_stride, _ptr(sel_cnt), _ptr(thr_cnt_opt),
-                  _stream(stream))
+        self._ck(self.call("ig_speculate_equalized", ctypes.byref(desc), _ptr(x), _ptr(wq), _ptr(bias), _ptr(A_p),
+                           _ptr(pos), _ptr(slab), float(max_frac), _ptr(sel_idx), sel_stride, _ptr(sel_cnt),
+                           _ptr(thr_cnt_opt), _stream(stream)))
 
     def ig_equalize_heads(self, desc, scores, thr_cnt, max_frac, sel_idx, sel_stride, sel_cnt,
                           stream=None):
@@ -410,6 +422,13 @@ class Context:
                                            _ptr(Vpool), _ptr(sel_idx), sel_stride, _ptr(sel_cnt),
                                            _ptr(K_sel), _ptr(V_sel), _ptr(k_new), _ptr(v_new),
                                            _ptr(out), _stream(stream)))
+
+    def ig_decode_step_overlapped(self, desc, layers, wq, bias, A_p, pos, pool_space, sets, sel_stride,
+                                  main_stream, side_stream):
+        """layers: ctypes array of IgLayerIO; sets: ctypes array of IgBufferSet (kept by the caller)."""
+        self._ck(self.call("ig_decode_step_overlapped", ctypes.byref(desc), len(layers), ctypes.addressof(layers),
+                           _ptr(wq), _ptr(bias), _ptr(A_p), _ptr(pos), pool_space, len(sets), ctypes.addressof(sets),
+                           sel_stride, _stream(main_stream), _stream(side_stream)))
 
     def ig_set_wait_limit(self, ticks: int):
         self._ck(lib().ig_set_wait_limit(self._h, int(ticks)))

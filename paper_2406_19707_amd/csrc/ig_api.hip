@@ -222,6 +222,8 @@ int ig_destroy(ig_ctx *ctx) {
     (void)hipEventDestroy(r.e1);
   }
   for (auto &e : ctx->free_events) (void)hipEventDestroy(e);
+  for (auto &e : ctx->pipe_events) (void)hipEventDestroy(e);
+  if (ctx->side) (void)ig_destroy(ctx->side);
   if (ctx->part) (void)hipFree(ctx->part);
   if (ctx->qp) (void)hipFree(ctx->qp);
   if (ctx->scores) (void)hipFree(ctx->scores);
@@ -714,6 +716,62 @@ int ig_layer_step(ig_ctx *ctx, const ig_desc *d, const void *x, const void *wq, 
   }
   return ig_launch_scan_attend(ctx, d, qs, slab, sel_idx_next, sel_cnt_next, q, Kpool, Vpool, sel_idx,
                                sel_cnt, sel_stride, k_new, v_new, out, K_sel, V_sel, s);
+}
+
+int ig_decode_step_overlapped(ig_ctx *ctx, const ig_desc *d, int n_layers, const ig_layer_io *layers,
+                              const void *wq, const float *bias, const float *A_p, const int32_t *pos,
+                              int pool_space, int n_sets, const ig_buffer_set *sets, int32_t sel_stride,
+                              void *main_stream, void *side_stream) {
+  int rc = check_desc(ctx, d, main_stream);
+  if (rc) return rc;
+  if (n_layers < 1 || n_sets < 2 || !layers || !sets)
+    return ig_fail(ctx, IG_EINVAL, "ig_decode_step_overlapped: needs layers and at least two buffer sets");
+  if (main_stream == side_stream) return ig_fail(ctx, IG_EINVAL, "ig_decode_step_overlapped: the two streams must differ");
+  for (int i = 0; i < n_sets; ++i)
+    if (!sets[i].sel_idx || !sets[i].sel_cnt || !sets[i].K_sel || !sets[i].V_sel)
+      return ig_fail(ctx, IG_EINVAL, "ig_decode_step_overlapped: buffer set %d has a NULL member", i);
+  if ((rc = set_device(ctx))) return rc;
+  if (!ctx->side) {
+    if ((rc = ig_create(ctx->device, &ctx->side))) return ig_fail(ctx, rc, "ig_decode_step_overlapped: no context for the side stream");
+  }
+  while ((int)ctx->pipe_events.size() < 3 * n_layers) {
+    hipEvent_t e;
+    IG_HIP(ctx, hipEventCreateWithFlags(&e, hipEventDisableTiming));
+    ctx->pipe_events.push_back(e);
+  }
+  hipStream_t ms = (hipStream_t)main_stream, ss = (hipStream_t)side_stream;
+  auto ev_spec = [&](int l) { return ctx->pipe_events[3 * l]; };
+  auto ev_gath = [&](int l) { return ctx->pipe_events[3 * l + 1]; };
+  auto ev_attn = [&](int l) { return ctx->pipe_events[3 * l + 2]; };
+  // Fig. 3(d): iteration l rehearses layer l on the main stream, hands its lists to the side stream
+  // for the prefetch, and attends layer l-1 whose rows have arrived meanwhile.  A buffer set is
+  // written again only after the attention that read it has been enqueued (lists: same stream) or
+  // has finished (rows: the side stream waits for that attention's event).
+  for (int l = 0; l <= n_layers; ++l) {
+    if (l < n_layers) {
+      const ig_layer_io &io = layers[l];
+      const ig_buffer_set &st = sets[l % n_sets];
+      if ((rc = ig_speculate(ctx, d, io.x, wq, bias, A_p, pos, io.slab, st.sel_idx, sel_stride, st.sel_cnt, nullptr, ms)))
+        return rc;
+      IG_HIP(ctx, hipEventRecord(ev_spec(l), ms));
+      IG_HIP(ctx, hipStreamWaitEvent(ss, ev_spec(l), 0));
+      if (l >= n_sets) IG_HIP(ctx, hipStreamWaitEvent(ss, ev_attn(l - n_sets), 0));
+      rc = ig_gather_kv(ctx->side, d, io.Kpool, io.Vpool, pool_space, st.sel_idx, sel_stride, st.sel_cnt, st.K_sel,
+                        st.V_sel, ss);
+      if (rc) return ig_fail(ctx, rc, "prefetch of layer %d: %s", l, ig_last_error(ctx->side));
+      IG_HIP(ctx, hipEventRecord(ev_gath(l), ss));
+    }
+    if (l >= 1) {
+      const ig_layer_io &io = layers[l - 1];
+      const ig_buffer_set &st = sets[(l - 1) % n_sets];
+      IG_HIP(ctx, hipStreamWaitEvent(ms, ev_gath(l - 1), 0));
+      if ((rc = ig_sparse_attention(ctx, d, io.q, st.K_sel, st.V_sel, st.sel_cnt, sel_stride, io.k_new, io.v_new, io.out, ms)))
+        return rc;
+      IG_HIP(ctx, hipEventRecord(ev_attn(l - 1), ms));
+    }
+  }
+  // the side stream's last work is joined to the main stream by the last wait above
+  return IG_OK;
 }
 
 int ig_set_wait_limit(ig_ctx *ctx, int64_t ticks) {

@@ -93,6 +93,8 @@ struct ig_ctx {
   bool profiling;
   std::vector<ProfRec> recs;
   std::vector<hipEvent_t> free_events;
+  ig_ctx *side = nullptr;                     // ig_decode_step_overlapped: the side stream's own workspaces
+  std::vector<hipEvent_t> pipe_events;        // ... and its cross-stream events (3 per layer), reused from call to call
   double prof_ms[IG_K_COUNT];
   int prof_n[IG_K_COUNT];
 };

@@ -302,6 +302,25 @@ class Rehearsal:
                 ev_attn[l - 1] = torch.cuda.Event()
                 ev_attn[l - 1].record(main)
 
+    def step_overlapped_native(self):
+        """The same step issued by the library (ig_decode_step_overlapped): one call enqueues every
+        layer's rehearsal, prefetch and attention on the two streams with the events between them.
+        Every layer writes its own output row block (self.outs[l])."""
+        if not hasattr(self, "_native_layers"):
+            self.outs = [torch.zeros_like(self.out) for _ in range(self.L)]
+            L_t = ig.IgLayerIO * self.L
+            S_t = ig.IgBufferSet * self.n_sets
+            self._native_layers = L_t(*[
+                ig.IgLayerIO(x=self.x[l].data_ptr(), slab=self.slab[l].data_ptr(), q=self.q[l].data_ptr(),
+                             Kpool=self.K[l % self.n_pool].data_ptr(), Vpool=self.V[l % self.n_pool].data_ptr(),
+                             k_new=None, v_new=None, out=self.outs[l].data_ptr()) for l in range(self.L)])
+            self._native_sets = S_t(*[
+                ig.IgBufferSet(sel_idx=st["sel_idx"].data_ptr(), sel_cnt=st["sel_cnt"].data_ptr(),
+                               K_sel=st["K_sel"].data_ptr(), V_sel=st["V_sel"].data_ptr()) for st in self.sets])
+        self.ctx.ig_decode_step_overlapped(self.desc, self._native_layers, self.wq, None, self.A_p, self.pos,
+                                           self.space, self._native_sets, self.stride,
+                                           torch.cuda.current_stream(), self.side)
+
     def step_one_pass(self):
         """HBM-pool decode step with prefetch and attention in one pass over the pool."""
         for l in range(self.L):

@@ -183,3 +183,47 @@ def test_host_speculation_step_matches_device_step_and_oracle(cfg, B, H, N, L, g
         ref = oracle_layer(R, l, w.N, w.alpha)
         check_against_oracle(R, hosted[l], ref, w.alpha)
     ctx.close()
+
+
+@pytest.mark.parametrize("cfg,B,H,N,L,sets,gain", [
+    (4, 2, 8, 2048, 6, 2, 12.0),
+    (5, 1, 8, 6000, 5, 3, 30.0),
+])
+def test_native_overlapped_step_matches_the_serial_layers(cfg, B, H, N, L, sets, gain):
+    """ig_decode_step_overlapped (the two-stream pipeline issued by the library) against one layer at
+    a time on one stream: every layer's output bit for bit, twice in a row, and the lists and rows
+    the last `sets` layers left in the buffer sets."""
+    import paper_2406_19707_amd as ig
+    from paper_2406_19707_amd.pipeline import Rehearsal
+    w = wl.shrink(wl.WORKLOADS[cfg], B=B, H=H, N=N, n_cal=256, heavy_count=16)
+    ctx = ig.Context(0)
+    R = Rehearsal(ctx, w, gain=gain, layers=L, host_layers=L, sets=sets)
+    serial = []
+    for l in range(L):
+        R._use(l)
+        R.layer(l)
+        torch.cuda.synchronize()
+        serial.append(snapshot(R))
+    for rep in range(2):
+        for st in R.sets:
+            for t in st.values():
+                t.fill_(-1 if t.dtype == torch.int32 else 7)
+        R.step_overlapped_native()
+        torch.cuda.synchronize()
+        assert ctx.ig_check_status() == ig.IG_OK
+        for l in range(L):
+            assert torch.equal(R.outs[l], serial[l]["out"]), (rep, l)
+        for l in range(L - sets, L):
+            st = R.sets[l % sets]
+            n = serial[l]["sel_cnt"]
+            assert torch.equal(st["sel_cnt"], n), (rep, l)
+            for i in range(w.B * w.H):
+                k = int(n[i])
+                assert torch.equal(st["sel_idx"][i, :k], serial[l]["sel_idx"][i, :k])
+                assert torch.equal(st["K_sel"][i, :k], serial[l]["K_sel"][i, :k])
+                assert torch.equal(st["V_sel"][i, :k], serial[l]["V_sel"][i, :k])
+    # the library refuses what it cannot order
+    with pytest.raises(ig.IgError):
+        ctx.ig_decode_step_overlapped(R.desc, R._native_layers, R.wq, None, R.A_p, R.pos, R.space,
+                                      R._native_sets, R.stride, R.side, R.side)
+    ctx.close()
