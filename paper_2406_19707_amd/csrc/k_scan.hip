@@ -1123,11 +1123,15 @@ bool ig_scan_stream_form(const ig_desc *d, int *tpw, int *S) {
 }
 
 // Shapes whose scan finishes a rotary model's partial query itself (from the full projection's
-// split-K sums) instead of reading it from the finalisation kernel: the streaming form, heads that
-// fit its prologue.
+// split-K sums) instead of reading it from the finalisation kernel: the streaming form with one
+// workgroup per pair, heads that fit its prologue.  Where a pair is split over S workgroups every
+// one of them would repeat the prologue (S times the work, and 2.5-3 us of latency at the start of
+// each): there the query is finished once, by the finalisation kernel, and the scan starts with it
+// (measured on 160 pairs of 32768 tokens, S = 8: scan 52.1 -> 49.7 us, the finalisation kernel adds
+// 4.8 us including its launch, the projection + scan sequence 65.3 -> 66.7 us).
 bool ig_scan_takes_rope(const ig_desc *d) {
   int tpw = 0, S = 0;
-  return d->rope && ig_scan_stream_form(d, &tpw, &S) && rope_prologue_fits(256, d->d, d->r);
+  return d->rope && ig_scan_stream_form(d, &tpw, &S) && S == 1 && rope_prologue_fits(256, d->d, d->r);
 }
 
 // One workgroup per (b,h) and a single kernel when a pair fits 16 waves (scores stay in registers)
