@@ -265,17 +265,27 @@ __device__ __forceinline__ bool poll_slots(const unsigned long long *slots, int 
 // then copies the row out with whole-wave stores: a handful of coalesced store instructions per
 // wave instead of one scattered store per score register, which matters because every memory
 // instruction of the epilogue queues behind the other workgroups' streaming loads.
-template <int TPL, int NW, int TPW>
-__device__ __forceinline__ int compact_tiles(const float (&sc)[TPW][TPL], float thr, int N, int base,
-                                             int32_t *list, int sel_stride, int t_first, int *lds_cnt /* [NW] */,
-                                             int32_t *stage, int w, int lane, bool count_only) {
-  constexpr int TILE = IG_WAVE * TPL;
+// The three steps are separate so that a split pair can publish its count right after the first
+// and pack (LDS only) while the partners' counts are on their way:
+//   compact_rank  -> which scores are kept (bit masks), each lane's rank inside its wave, the
+//                    wave's total, and across the workgroup: kept tokens in earlier waves / in all
+//   compact_pack  -> the wave's kept token ids into its LDS row, in token order
+//   compact_store -> the row to list[base + before ...]
+template <int TPW>
+struct Kept {
   unsigned mask[TPW];
-  int rank[TPW], mine = 0;
+  int rank[TPW];
+  int mine, before, all;
+};
+template <int TPL, int NW, int TPW>
+__device__ __forceinline__ void compact_rank(const float (&sc)[TPW][TPL], float thr, int N, int t_first,
+                                             int *lds_cnt /* [NW] */, int w, int lane, Kept<TPW> &k) {
+  constexpr int TILE = IG_WAVE * TPL;
+  k.mine = 0;
 #pragma unroll
   for (int i = 0; i < TPW; ++i) {
     const int t0 = t_first + (w * TPW + i) * TILE + lane * TPL;
-    mask[i] = 0;
+    k.mask[i] = 0;
     int below = 0, total = 0;
 #pragma unroll
     for (int e = 0; e < TPL; ++e) {
@@ -283,36 +293,56 @@ __device__ __forceinline__ int compact_tiles(const float (&sc)[TPW][TPL], float 
       const unsigned long long bal = __ballot(keep);
       below += lanes_below(bal);
       total += __popcll(bal);
-      mask[i] |= (keep ? 1u : 0u) << e;
+      k.mask[i] |= (keep ? 1u : 0u) << e;
     }
-    rank[i] = mine + below;
-    mine += total;
+    k.rank[i] = k.mine + below;
+    k.mine += total;
   }
-  if (lane == 0) lds_cnt[w] = mine;
+  if (lane == 0) lds_cnt[w] = k.mine;
   __syncthreads();
-  int before = 0, all = 0;
+  k.before = 0;
+  k.all = 0;
 #pragma unroll
-  for (int k = 0; k < NW; ++k) {
-    const int c = lds_cnt[k];
-    before += (k < w) ? c : 0;
-    all += c;
+  for (int j = 0; j < NW; ++j) {
+    const int c = lds_cnt[j];
+    k.before += (j < w) ? c : 0;
+    k.all += c;
   }
   __syncthreads();   // lds_cnt is reused
-  if (count_only) return all;
+}
+template <int TPL, int NW, int TPW>
+__device__ __forceinline__ void compact_pack(const Kept<TPW> &k, int t_first, int32_t *stage, int w, int lane) {
+  constexpr int TILE = IG_WAVE * TPL;
   int32_t *row = stage + w * (TPW * TILE);
 #pragma unroll
   for (int i = 0; i < TPW; ++i) {
     const int t0 = t_first + (w * TPW + i) * TILE + lane * TPL;
-    int p = rank[i];
+    int p = k.rank[i];
 #pragma unroll
     for (int e = 0; e < TPL; ++e) {
-      if (mask[i] & (1u << e)) row[p++] = t0 + e;
+      if (k.mask[i] & (1u << e)) row[p++] = t0 + e;
     }
   }
-  const int out0 = base + before;
-  for (int j = lane; j < mine; j += IG_WAVE)
+}
+template <int TPL, int TPW>
+__device__ __forceinline__ void compact_store(const Kept<TPW> &k, int base, int32_t *list, int sel_stride,
+                                              const int32_t *stage, int w, int lane) {
+  constexpr int TILE = IG_WAVE * TPL;
+  const int32_t *row = stage + w * (TPW * TILE);
+  const int out0 = base + k.before;
+  for (int j = lane; j < k.mine; j += IG_WAVE)
     if (out0 + j < sel_stride) list[out0 + j] = row[j];
-  return all;
+}
+template <int TPL, int NW, int TPW>
+__device__ __forceinline__ int compact_tiles(const float (&sc)[TPW][TPL], float thr, int N, int base,
+                                             int32_t *list, int sel_stride, int t_first, int *lds_cnt /* [NW] */,
+                                             int32_t *stage, int w, int lane, bool count_only) {
+  Kept<TPW> k;
+  compact_rank<TPL, NW, TPW>(sc, thr, N, t_first, lds_cnt, w, lane, k);
+  if (count_only) return k.all;
+  compact_pack<TPL, NW, TPW>(k, t_first, stage, w, lane);
+  compact_store<TPL, TPW>(k, base, list, sel_stride, stage, w, lane);
+  return k.all;
 }
 
 // ---- head-equalised selection inside the streaming kernel ----------------------------------------
@@ -856,10 +886,15 @@ __global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, 
   const float gmax = slow ? pair_max<T, NW>(a, bh, q_lane, lds_max) : lds_gmax;
   const float thr = gmax - a.alpha;
   // ---- the pair's splits meet: counts ----
-  const int mine = compact_tiles<TPL, NW, TPW>(sc, thr, a.N, 0, list, a.sel_stride, tile0 * TILE, lds_cnt, stage, w, lane, true);
+  // (ranks first, then the count goes out; the kept ids are packed into LDS while the partners'
+  // counts are on their way, and only the stores wait for this split's offset)
+  Kept<TPW> kept;
+  compact_rank<TPL, NW, TPW>(sc, thr, a.N, tile0 * TILE, lds_cnt, w, lane, kept);
+  const int mine = kept.all;
+  if (w == 0 && lane == 0)
+    __hip_atomic_store(&ps->scnt[s], PUBLISHED | (unsigned)mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  compact_pack<TPL, NW, TPW>(kept, tile0 * TILE, stage, w, lane);
   if (w == 0) {
-    if (lane == 0)
-      __hip_atomic_store(&ps->scnt[s], PUBLISHED | (unsigned)mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     unsigned long long v = 0;
     const bool ok = !slow && poll_slots(ps->scnt, S, lane, spin_limit, &v);
     const int c = (ok && lane < S) ? (int)(unsigned)v : 0;
@@ -875,8 +910,7 @@ __global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, 
   __syncthreads();
   if (lds_flag[1]) {
     const int base = lds_cnt[0], all = lds_flag[0];
-    __syncthreads();
-    compact_tiles<TPL, NW, TPW>(sc, thr, a.N, base, list, a.sel_stride, tile0 * TILE, lds_cnt, stage, w, lane, false);
+    compact_store<TPL, TPW>(kept, base, list, a.sel_stride, stage, w, lane);
     if (s == S - 1 && threadIdx.x == 0) {
       a.sel_cnt[bh] = min(all, a.sel_stride);
       if (all > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);

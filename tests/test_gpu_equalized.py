@@ -237,3 +237,20 @@ def test_speculate_equalized_matches_the_two_calls_and_the_oracle(cfg, shape, ga
             k = min(short, int(ref_cnt[i]))
             assert np.array_equal(got[i, :k], ref_idx[i, :k])
     ctx.close()
+
+
+def test_speculate_equalized_error_paths(ctx):
+    import ctypes
+    import paper_2406_19707_amd as ig
+    buf = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda")
+    p = buf.data_ptr()
+    d = ig.IgDesc(B=1, H=2, d=128, r=38, N=64)
+    def call(frac, slab=p + 4096, cnt=p + 65536, thr=0):
+        return ctx.call("ig_speculate_equalized", ctypes.byref(d), p, p + 1024, 0, 0, 0, slab,
+                        ctypes.c_double(frac), p + 131072, 64, cnt, thr, 0)
+    assert call(0.0) == ig.IG_EINVAL
+    assert call(1.5) == ig.IG_EINVAL
+    assert call(float("nan")) == ig.IG_EINVAL
+    assert call(0.2, slab=0) == ig.IG_EINVAL
+    assert call(0.2, cnt=0) == ig.IG_EINVAL
+    assert call(0.2, cnt=p + 65536, thr=p + 65536) == ig.IG_EINVAL and "alias" in ctx.last_error()

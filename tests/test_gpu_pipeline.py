@@ -227,3 +227,26 @@ def test_native_overlapped_step_matches_the_serial_layers(cfg, B, H, N, L, sets,
         ctx.ig_decode_step_overlapped(R.desc, R._native_layers, R.wq, None, R.A_p, R.pos, R.space,
                                       R._native_sets, R.stride, R.side, R.side)
     ctx.close()
+
+
+def test_native_overlapped_step_error_paths():
+    import ctypes
+    import paper_2406_19707_amd as ig
+    ctx = ig.Context(0)
+    d = ig.IgDesc(B=1, H=2, d=128, r=38, N=64)
+    buf = torch.zeros(1 << 16, dtype=torch.uint8, device="cuda")
+    p = buf.data_ptr()
+    layers = (ig.IgLayerIO * 1)(ig.IgLayerIO(x=p, slab=p, q=p, Kpool=p, Vpool=p, k_new=None, v_new=None, out=p))
+    sets = (ig.IgBufferSet * 2)(ig.IgBufferSet(sel_idx=p, sel_cnt=p, K_sel=p, V_sel=p),
+                                ig.IgBufferSet(sel_idx=p, sel_cnt=p, K_sel=p, V_sel=None))
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    def call(n_layers=1, n_sets=2, main=s1.cuda_stream, side=s2.cuda_stream, la=ctypes.addressof(layers)):
+        return ctx.call("ig_decode_step_overlapped", ctypes.byref(d), n_layers, la, p, 0, 0, 0, ig.IG_MEM_DEVICE,
+                        n_sets, ctypes.addressof(sets), 64, main, side)
+    assert call(n_layers=0) == ig.IG_EINVAL
+    assert call(n_sets=1) == ig.IG_EINVAL
+    assert call(la=0) == ig.IG_EINVAL
+    assert call(side=s1.cuda_stream) == ig.IG_EINVAL and "differ" in ctx.last_error()
+    assert call() == ig.IG_EINVAL and "NULL member" in ctx.last_error()     # second set lacks V_sel
+    torch.cuda.synchronize()
+    ctx.close()
