@@ -39,6 +39,20 @@ class Case:
         return np.ascontiguousarray(getattr(self, name), dtype=np.float32)
 
 
+def _skew_keys(K: np.ndarray, A: np.ndarray) -> np.ndarray:
+    """K~ = K A_h with the oracle, one sequence per thread for large caches (sequences are
+    independent; the C routine itself is single-threaded and untouched)."""
+    B = K.shape[0]
+    if K.size < (1 << 24) or B == 1:
+        return o.apply_skew(K.transpose(0, 2, 1, 3), A).transpose(0, 2, 1, 3)
+    from concurrent.futures import ThreadPoolExecutor
+    import os
+    one = lambda b: o.apply_skew(np.ascontiguousarray(K[b:b + 1].transpose(0, 2, 1, 3)), A)   # noqa: E731
+    with ThreadPoolExecutor(min(B, os.cpu_count() or 1, 16)) as ex:
+        parts = list(ex.map(one, range(B)))
+    return np.concatenate(parts, axis=0).transpose(0, 2, 1, 3)
+
+
 def make_case(w: wl.Workload, gain: float = 1.0, layer: int = 0, bias: bool = False,
               N_cap: int | None = None, all_columns: bool = False, use_keys_for_index: bool = False) -> Case:
     N_cap = w.N if N_cap is None else N_cap
@@ -51,7 +65,7 @@ def make_case(w: wl.Workload, gain: float = 1.0, layer: int = 0, bias: bool = Fa
     sk = o.skew(Wq, None, Qcal, w.H, bq=bq)
     A = sk["A"]
     K, V = wl.kv_cache(w, layer)                                  # K: (rotated) keys before skewing
-    Kt = o.apply_skew(K.transpose(0, 2, 1, 3), A).transpose(0, 2, 1, 3)
+    Kt = _skew_keys(K, A)
     Qs_cal = o.apply_skew(Qcal, A)
     if all_columns:
         idx = np.tile(np.arange(w.d, dtype=np.int32), (w.H, 1))
@@ -104,23 +118,44 @@ class OracleResult:
     out_new: np.ndarray   # with the new-token row
 
 
-def run_oracle(c: Case, alpha: float | None = None, attend: bool = True) -> OracleResult:
+def _run_oracle_rows(c: Case, alpha: float, attend: bool, b0: int, b1: int) -> OracleResult:
+    """The oracle on sequences b0 .. b1-1 of the case."""
     w = c.w
-    alpha = w.alpha if alpha is None else alpha
+    x, pos = c.f32("x")[b0:b1], c.pos[b0:b1]
     if w.rope:
-        q_p = o.project_rope(c.f32("x"), c.f32("W_in"), c.pos, c.A, c.idx, bq=c.bias_full)
+        q_p = o.project_rope(x, c.f32("W_in"), pos, c.A, c.idx, bq=c.bias_full)
     else:
-        q_p = o.project(c.f32("x"), c.f32("W_in"), c.idx, bq_s=c.bias_full)
-    Kt = c.f32("Kt")
+        q_p = o.project(x, c.f32("W_in"), c.idx, bq_s=c.bias_full)
+    Kt = np.ascontiguousarray(c.Kt[b0:b1], dtype=np.float32)
     s = o.scan(q_p, Kt, c.idx, c.scale, N=c.N)
     sel_idx, sel_cnt = o.select(s, alpha)
     if not attend:
         return OracleResult(q_p, s, sel_idx, sel_cnt, None, None, None, None)
+    V = np.ascontiguousarray(c.V[b0:b1], dtype=np.float32)
+    q = np.ascontiguousarray(c.q[b0:b1], dtype=np.float32)
     K_sel = o.gather(Kt, sel_idx, sel_cnt)
-    V_sel = o.gather(c.f32("V"), sel_idx, sel_cnt)
-    out = o.attend(c.f32("q"), K_sel, V_sel, sel_cnt, c.scale)
-    out_new = o.attend(c.f32("q"), K_sel, V_sel, sel_cnt, c.scale, c.f32("k_new"), c.f32("v_new"))
+    V_sel = o.gather(V, sel_idx, sel_cnt)
+    out = o.attend(q, K_sel, V_sel, sel_cnt, c.scale)
+    kn = np.ascontiguousarray(c.k_new[b0:b1], dtype=np.float32)
+    vn = np.ascontiguousarray(c.v_new[b0:b1], dtype=np.float32)
+    out_new = o.attend(q, K_sel, V_sel, sel_cnt, c.scale, kn, vn)
     return OracleResult(q_p, s, sel_idx, sel_cnt, K_sel, V_sel, out, out_new)
+
+
+def run_oracle(c: Case, alpha: float | None = None, attend: bool = True) -> OracleResult:
+    """The oracle on the whole case.  Sequences are independent, so large cases run one sequence per
+    thread (the C oracle itself stays single-threaded and untouched; ctypes releases the GIL)."""
+    w = c.w
+    alpha = w.alpha if alpha is None else alpha
+    if w.B * w.H * c.N < (1 << 22) or w.B == 1:
+        return _run_oracle_rows(c, alpha, attend, 0, w.B)
+    from concurrent.futures import ThreadPoolExecutor
+    import os
+    with ThreadPoolExecutor(min(w.B, os.cpu_count() or 1, 16)) as ex:
+        parts = list(ex.map(lambda b: _run_oracle_rows(c, alpha, attend, b, b + 1), range(w.B)))
+    cat = lambda name: (None if getattr(parts[0], name) is None   # noqa: E731
+                        else np.concatenate([getattr(p, name) for p in parts], axis=0))
+    return OracleResult(*[cat(n) for n in ("q_p", "s", "sel_idx", "sel_cnt", "K_sel", "V_sel", "out", "out_new")])
 
 
 def selected_fraction(res: OracleResult, N: int) -> float:
