@@ -805,6 +805,10 @@ __global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, 
       if (!ok) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // own slot has landed before "done"
     }
     __syncthreads();
+    // the record has been read for the last time: report it now, the answer is looked at at the end
+    unsigned long long prev_done = 0;
+    if (w == 0 && lane == 0)
+      prev_done = __hip_atomic_fetch_add(&rec[a.H], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     int total = lds_flag[1];
     if (lds_flag[0] == 0) {
       // the other heads' counts did not arrive in time: work them out alone, head by head
@@ -846,11 +850,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, 
       a.sel_cnt[bh] = min(all, a.sel_stride);
       if (all > a.sel_stride) atomicOr(a.status, IG_STATUS_CAPACITY);
     }
-    // done with the sequence's record; the last head to get here clears it for the next call
+    // the last head to have reported clears the sequence's record for the next call
     if (w == 0) {
-      unsigned long long prev = 0;
-      if (lane == 0) prev = __hip_atomic_fetch_add(&rec[a.H], 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      const int prev_lo = __builtin_amdgcn_readfirstlane((int)prev);
+      const int prev_lo = __builtin_amdgcn_readfirstlane((int)prev_done);
       if (prev_lo == a.H - 1) {
         for (int c = lane; c <= a.H; c += IG_WAVE)
           __hip_atomic_store(&rec[c], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -908,6 +910,11 @@ __global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, 
     if (!ok) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
   __syncthreads();
+  // This split has read the record for the last time: its "done" goes out now, so that the trip to
+  // the counter runs under the list stores; the last split to get there clears the record for the
+  // next call (below, once the counter's answer is back).
+  int prev_done = 0;
+  if (w == 0 && lane == 0) prev_done = __hip_atomic_fetch_add(&ps->done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   if (lds_flag[1]) {
     const int base = lds_cnt[0], all = lds_flag[0];
     compact_store<TPL, TPW>(kept, base, list, a.sel_stride, stage, w, lane);
@@ -918,11 +925,9 @@ __global__ __launch_bounds__(NW * 64, MINW) void scan_select_stream(ScanArgs a, 
   } else {
     rescan_pair<T, NW>(a, bh, q_lane, thr, lds_cnt);
   }
-  // ---- done with the record; the last split to get here clears it for the next call ----
+  // ---- the last split to have reported "done" clears the record for the next call ----
   if (w == 0) {
-    int prev = 0;
-    if (lane == 0) prev = __hip_atomic_fetch_add(&ps->done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    prev = __builtin_amdgcn_readfirstlane(prev);
+    const int prev = __builtin_amdgcn_readfirstlane(prev_done);
     if (prev == S - 1) {
       if (lane < S) {
         __hip_atomic_store(&ps->smax[lane], 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
